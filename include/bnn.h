@@ -1,0 +1,170 @@
+/*
+ * bnn.h - C ABI of the MI355X (gfx950) library for the forward hot path of
+ * Binarized Neural Networks (Courbariaux, Hubara, Soudry, El-Yaniv, Bengio).
+ *
+ * The path is the hidden-layer loop of Alg. 4 ("Running a BNN"):
+ *     a_k   = XnorDotProduct(a^b_{k-1}, W^b_k)
+ *     a^b_k = Sign(BatchNorm(a_k, theta_k))
+ * on +-1 values concatenated 32 per 32-bit word (Sec. 4, Eq. (5)).
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Packed rows: bit = 1 <=> +1, bit = 0 <=> -1.  Element k of a row lives in
+ *    word k / 32 at bit k % 32 (least significant bit first).  A row of K
+ *    elements occupies bnn_words_per_row(K) words; the unused high bits of its
+ *    last word ("pad bits") are written as 0 by this library, and are ignored
+ *    (masked) wherever this library reads packed operands.
+ *  - Matrices are row-major with a leading dimension ("ld", counted in
+ *    elements of the array's own type: floats, words, int32 or bytes).
+ *  - Unless an argument is marked HOST, every pointer is a DEVICE pointer on
+ *    the current HIP device, owned by the caller.  The library allocates
+ *    nothing, keeps no pointer after returning, and never synchronises: work
+ *    is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *    default stream) and the caller orders it against its own work.
+ *  - Inputs and outputs must not overlap.
+ *  - Every function returns a bnn_status.  On any status other than BNN_OK no
+ *    kernel was launched and no output was written.  A dimension of 0 for
+ *    rows/M/N/B is a valid empty problem: BNN_OK, nothing launched.
+ *  - Limits: every dimension < 2^31; K <= 2^31 - 2 so that |dot| <= K and the
+ *    threshold K + 1 fit in int32.
+ */
+#ifndef BNN_H
+#define BNN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BNN_VERSION 100 /* 0.1.0 */
+
+typedef enum bnn_status {
+    BNN_OK = 0,
+    BNN_ERR_INVALID_ARG = 1, /* null pointer, negative size, ld too small, K out of range */
+    BNN_ERR_ALIGNMENT = 2,   /* pointer not aligned to its element type */
+    BNN_ERR_UNSUPPORTED = 3, /* valid request this build has no kernel for */
+    BNN_ERR_LAUNCH = 4       /* the HIP runtime refused the launch */
+} bnn_status;
+
+int bnn_version(void);
+const char *bnn_status_string(int status);
+
+/* ceil(K / 32): words in a packed row of K elements (Sec. 4: 32 binary
+ * variables per 32-bit register).  Returns -1 if K < 0. */
+int64_t bnn_words_per_row(int64_t K);
+
+/*
+ * Eq. (1) + Sec. 4 packing:  out[r][k/32] bit (k%32) = (x[r][k] >= 0).
+ * The comparison is the IEEE one: +0.0, -0.0 -> 1; negative subnormals -> 0;
+ * NaN -> 0.
+ *   x     [rows][ld_x] float32, ld_x >= cols
+ *   out   [rows][ld_out] uint32, ld_out >= ceil(cols/32); words
+ *         [ceil(cols/32), ld_out) of each row are left untouched
+ * Fast path when x is 16-byte aligned and ld_x % 4 == 0; any other layout
+ * takes a slower element-wise path with the same result.
+ */
+int bnn_pack_sign(const float *x, int64_t rows, int64_t cols, int64_t ld_x,
+                  uint32_t *out, int64_t ld_out, void *stream);
+
+/*
+ * Sec. 4, Eq. (5) over whole matrices (the XnorDotProduct of Alg. 4):
+ *   C[m][n] = sum_{k<K} a[m][k] * b[n][k],  a, b in {-1,+1}
+ *           = 2 * popcount(xnor(A[m], B[n]) over the K valid bits) - K
+ * computed as K - 2 * sum_w popcount(A[m][w] ^ B[n][w]) with the pad bits of
+ * both operands masked off, so their content never matters.
+ *   A  [M][lda] packed rows of K bits (activations a^b)
+ *   B  [N][ldb] packed rows of K bits: row n is output unit n's weight vector,
+ *      i.e. B is the transpose of W^b in s = a W (both operands K-contiguous)
+ *   C  [M][ldc] int32, ldc >= N
+ * lda, ldb >= ceil(K/32).  Fast tiles need A, B 16-byte aligned with lda, ldb
+ * multiples of 4; other layouts run a slower path with the same result.
+ * K == 0 writes C = 0.
+ */
+int bnn_xnor_gemm(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb,
+                  int32_t *C, int64_t ldc, int64_t M, int64_t N, int64_t K,
+                  void *stream);
+
+/* Same contract, with the kernel chosen by the caller (for tests and
+ * profiling): 0 = automatic (what bnn_xnor_gemm does), 1 = one thread per
+ * output, 2 = 128x128 LDS-tiled register-blocked kernel, 3 = K-split kernel
+ * with wavefront reduction (skinny outputs), 4 = 64x64 tiled kernel.
+ * Unknown ids give BNN_ERR_INVALID_ARG. */
+int bnn_xnor_gemm_kernel(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb,
+                         int32_t *C, int64_t ldc, int64_t M, int64_t N, int64_t K,
+                         int kernel_id, void *stream);
+
+/*
+ * HOST function.  Folds Sign(BatchNorm(s)) of Alg. 4 (inference BatchNorm with
+ * running statistics, evaluated in float32 as
+ *     y = gamma * ((float(s) - mean) * (1 / sqrt(var + eps))) + beta,
+ * every operation rounded separately) into one integer compare per channel:
+ *     Sign(y(s)) = +1  <=>  (s >= thr[n]) XOR flip[n]     for all integer s in [-K, K].
+ * The threshold is found by searching the float expression itself (which is
+ * monotone in s), not by solving it algebraically, so the equivalence is exact
+ * at rounding boundaries.  gamma < 0 reverses the inequality (flip = 1);
+ * gamma == 0 gives a constant bit (thr = -K or K + 1).
+ *   gamma, beta, mean, var  HOST [N] float32; all finite, var + eps > 0
+ *   thr        HOST [N] int32, each in [-K, K + 1]
+ *   flip_bits  HOST [ceil(N/32)] uint32, channel n at word n/32 bit n%32, pad bits 0
+ * Non-finite parameters or var + eps <= 0 give BNN_ERR_INVALID_ARG.
+ */
+int bnn_bn_fold(const float *gamma, const float *beta, const float *mean,
+                const float *var, float eps, int64_t N, int64_t K, int32_t *thr,
+                uint32_t *flip_bits);
+
+/*
+ * Alg. 4, a^b_k = Sign(BatchNorm(a_k, theta_k)), on folded parameters, packed
+ * for the next layer:
+ *   out[m][n/32] bit (n%32) = (C[m][n] >= thr[n]) XOR flip[n]
+ *   C    [M][ldc] int32, ldc >= N
+ *   thr  [N] int32 (device), flip_bits [ceil(N/32)] uint32 (device), from bnn_bn_fold
+ *   out  [M][ld_out] uint32, ld_out >= ceil(N/32); pad bits of the last word 0;
+ *        words beyond ceil(N/32) untouched
+ * Fast path when C and thr are 16-byte aligned and ldc % 4 == 0.
+ */
+int bnn_bn_sign_pack(const int32_t *C, int64_t ldc, int64_t M, int64_t N,
+                     const int32_t *thr, const uint32_t *flip_bits, uint32_t *out,
+                     int64_t ld_out, void *stream);
+
+/*
+ * Lowers a binary kh x kw convolution (3 x 3 in the paper's nets, Sec. 3.3) to
+ * the matrix product above: row m = (b*Ho + oy)*Wo + ox of `out` holds the
+ * receptive field of output pixel (b, oy, ox) as K = kh*kw*Cin bits,
+ *   bit (ky*kw + kx)*Cin + ci = in(b, oy*stride + ky - pad, ox*stride + kx - pad, ci),
+ * and taps that fall outside the image read as +1 (bit 1): zero padding
+ * binarised by Eq. (1), Sign(0) = +1.  Ho = (H + 2*pad - kh)/stride + 1, same for Wo.
+ *   in   packed NHWC [B][H][W][ceil(Cin/32)] uint32 (pad bits ignored)
+ *   out  [B*Ho*Wo][ld_out] uint32, ld_out >= ceil(kh*kw*Cin/32); pad bits 0
+ * Weights for the product are [Cout][kh][kw][Cin] packed along (ky,kx,ci).
+ * Cin % 32 == 0 copies whole words; other Cin take a bit-gather path.
+ * Requires kh, kw, stride >= 1, pad >= 0 and Ho, Wo >= 1.
+ */
+int bnn_conv_im2col_pack(const uint32_t *in, int64_t B, int64_t H, int64_t W,
+                         int64_t Cin, int kh, int kw, int stride, int pad,
+                         uint32_t *out, int64_t ld_out, void *stream);
+
+/*
+ * The competing dense-engine variant of the same product (the role the vendor
+ * GEMM plays in Sec. 4 / Fig. 3): +-1 stored one per int8, multiplied on the
+ * int8 MFMA units with int32 accumulation.
+ *   C[m][n] = sum_k A[m][k] * B[n][k]
+ *   A [M][lda] int8, B [N][ldb] int8 (row n = weights of output n), C [M][ldc] int32
+ * Exact for any int8 contents with |sum| < 2^31.  Requires A, B 16-byte
+ * aligned and lda, ldb multiples of 16 (else BNN_ERR_ALIGNMENT); K need not be.
+ */
+int bnn_gemm_i8_mfma(const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
+                     int32_t *C, int64_t ldc, int64_t M, int64_t N, int64_t K,
+                     void *stream);
+
+/* Expands packed rows to one int8 (+1 / -1) per element, the operand format of
+ * bnn_gemm_i8_mfma: out[r][k] = bit k of in[r] ? +1 : -1 for k < K, and 0 for
+ * K <= k < ld_out (so padded columns add nothing to a product).
+ *   in [rows][ld_in] uint32, out [rows][ld_out] int8, ld_out >= K. */
+int bnn_unpack_i8(const uint32_t *in, int64_t ld_in, int64_t rows, int64_t K,
+                  int8_t *out, int64_t ld_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BNN_H */

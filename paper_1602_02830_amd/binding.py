@@ -1,0 +1,233 @@
+"""ctypes binding of the C ABI in ``include/bnn.h``; same names, same argument order.
+
+Only marshalling happens here: shapes and strides are read off the tensors,
+outputs are allocated with torch on the inputs' device, and the call is
+enqueued on torch's current stream.  No arithmetic of the method is done in
+Python, and nothing falls back to the CPU.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libbnn_hip.so")
+
+KERNEL_AUTO, KERNEL_NAIVE, KERNEL_TILED128, KERNEL_KSPLIT, KERNEL_TILED64 = range(5)
+
+_i64 = ctypes.c_int64
+_int = ctypes.c_int
+_ptr = ctypes.c_void_p
+_f32 = ctypes.c_float
+
+_SIGNATURES = {
+    "bnn_version": (_int, []),
+    "bnn_status_string": (ctypes.c_char_p, [_int]),
+    "bnn_words_per_row": (_i64, [_i64]),
+    "bnn_pack_sign": (_int, [_ptr, _i64, _i64, _i64, _ptr, _i64, _ptr]),
+    "bnn_xnor_gemm": (_int, [_ptr, _i64, _ptr, _i64, _ptr, _i64, _i64, _i64, _i64, _ptr]),
+    "bnn_xnor_gemm_kernel": (_int, [_ptr, _i64, _ptr, _i64, _ptr, _i64, _i64, _i64, _i64, _int, _ptr]),
+    "bnn_bn_fold": (_int, [_ptr, _ptr, _ptr, _ptr, _f32, _i64, _i64, _ptr, _ptr]),
+    "bnn_bn_sign_pack": (_int, [_ptr, _i64, _i64, _i64, _ptr, _ptr, _ptr, _i64, _ptr]),
+    "bnn_conv_im2col_pack": (_int, [_ptr, _i64, _i64, _i64, _i64, _int, _int, _int, _int, _ptr, _i64, _ptr]),
+    "bnn_gemm_i8_mfma": (_int, [_ptr, _i64, _ptr, _i64, _ptr, _i64, _i64, _i64, _i64, _ptr]),
+    "bnn_unpack_i8": (_int, [_ptr, _i64, _i64, _i64, _ptr, _i64, _ptr]),
+}
+
+_lib = None
+
+
+class BnnError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        msg = load_library().bnn_status_string(status).decode()
+        super().__init__(f"{fn} failed with status {status} ({msg})")
+        self.status = status
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libbnn_hip.so (built in-tree by ``build.build_library``).  Raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                f"{_LIB_PATH} is not built; run `python -m paper_1602_02830_amd.build` "
+                "(there is no CPU fallback)")
+        lib = ctypes.CDLL(_LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def exported_symbols():
+    return sorted(_SIGNATURES)
+
+
+def _check(fn: str, status: int):
+    if status != 0:
+        raise BnnError(fn, status)
+
+
+def _stream():
+    return _ptr(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError(f"{name} must be 2-D with unit stride along its rows")
+    return t
+
+
+def _ld(t: torch.Tensor) -> int:
+    return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
+
+
+def version() -> int:
+    return int(load_library().bnn_version())
+
+
+def words_per_row(K: int) -> int:
+    return int(load_library().bnn_words_per_row(K))
+
+
+def _alloc_words(rows: int, kw: int, device, ld: int | None = None) -> torch.Tensor:
+    ld = kw if ld is None else ld
+    if ld < kw:
+        raise ValueError("ld smaller than the packed row")
+    if ld == kw:
+        return torch.empty((rows, kw), dtype=torch.int32, device=device)
+    # Words between the packed row and ld are never written by the library: define them.
+    return torch.zeros((rows, ld), dtype=torch.int32, device=device)[:, :kw]
+
+
+def pack_sign(x: torch.Tensor, out: torch.Tensor | None = None, ld_out: int | None = None) -> torch.Tensor:
+    """bnn_pack_sign: float32 [rows][cols] -> packed int32 words [rows][ceil(cols/32)]."""
+    lib = load_library()
+    _dev(x, torch.float32, "x")
+    rows, cols = x.shape
+    kw = words_per_row(cols)
+    if out is None:
+        out = _alloc_words(rows, kw, x.device, ld_out)
+    _dev(out, torch.int32, "out")
+    _check("bnn_pack_sign", lib.bnn_pack_sign(x.data_ptr(), rows, cols, _ld(x), out.data_ptr(), _ld(out),
+                                             _stream()))
+    return out
+
+
+def xnor_gemm(A: torch.Tensor, B: torch.Tensor, K: int, out: torch.Tensor | None = None,
+              kernel: int = KERNEL_AUTO) -> torch.Tensor:
+    """bnn_xnor_gemm: packed A [M][Kw], packed B [N][Kw] -> int32 C [M][N]."""
+    lib = load_library()
+    _dev(A, torch.int32, "A")
+    _dev(B, torch.int32, "B")
+    M, N = A.shape[0], B.shape[0]
+    kw = words_per_row(K)
+    if A.shape[1] < kw or B.shape[1] < kw:
+        raise ValueError("packed operands have fewer words per row than K needs")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    _dev(out, torch.int32, "out")
+    if kernel == KERNEL_AUTO:
+        st = lib.bnn_xnor_gemm(A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), out.data_ptr(), _ld(out), M, N, K,
+                               _stream())
+    else:
+        st = lib.bnn_xnor_gemm_kernel(A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), out.data_ptr(), _ld(out),
+                                      M, N, K, kernel, _stream())
+    _check("bnn_xnor_gemm", st)
+    return out
+
+
+def bn_fold(gamma, beta, mean, var, eps: float, K: int):
+    """bnn_bn_fold (host): float32 arrays [N] -> (thr int32 [N], flip_bits uint32 [ceil(N/32)]) numpy."""
+    lib = load_library()
+    arrs = [np.ascontiguousarray(a, dtype=np.float32) for a in (gamma, beta, mean, var)]
+    N = arrs[0].shape[0]
+    for a in arrs:
+        if a.shape != (N,):
+            raise ValueError("BatchNorm parameter arrays must all be [N]")
+    thr = np.empty(N, np.int32)
+    flip = np.empty((N + 31) // 32, np.uint32)
+    st = lib.bnn_bn_fold(*(a.ctypes.data for a in arrs), eps, N, K, thr.ctypes.data, flip.ctypes.data)
+    _check("bnn_bn_fold", st)
+    return thr, flip
+
+
+def bn_sign_pack(C: torch.Tensor, thr: torch.Tensor, flip_bits: torch.Tensor,
+                 out: torch.Tensor | None = None, ld_out: int | None = None) -> torch.Tensor:
+    """bnn_bn_sign_pack: int32 C [M][N] + folded thresholds -> packed bits [M][ceil(N/32)]."""
+    lib = load_library()
+    _dev(C, torch.int32, "C")
+    M, N = C.shape
+    nw = words_per_row(N)
+    if thr.dtype != torch.int32 or flip_bits.dtype != torch.int32 or not thr.is_cuda or not flip_bits.is_cuda:
+        raise ValueError("thr and flip_bits must be int32 device tensors")
+    if thr.numel() != N or flip_bits.numel() != nw or not thr.is_contiguous() or not flip_bits.is_contiguous():
+        raise ValueError("thr must be [N] and flip_bits [ceil(N/32)], contiguous")
+    if out is None:
+        out = _alloc_words(M, nw, C.device, ld_out)
+    _dev(out, torch.int32, "out")
+    _check("bnn_bn_sign_pack", lib.bnn_bn_sign_pack(C.data_ptr(), _ld(C), M, N, thr.data_ptr(),
+                                                   flip_bits.data_ptr(), out.data_ptr(), _ld(out), _stream()))
+    return out
+
+
+def conv_im2col_pack(x_bits: torch.Tensor, Cin: int, kh: int = 3, kw: int = 3, stride: int = 1, pad: int = 1,
+                     out: torch.Tensor | None = None, ld_out: int | None = None) -> torch.Tensor:
+    """bnn_conv_im2col_pack: packed NHWC int32 [B][H][W][ceil(Cin/32)] -> [B*Ho*Wo][ceil(kh*kw*Cin/32)]."""
+    lib = load_library()
+    if not x_bits.is_cuda or x_bits.dtype != torch.int32 or x_bits.dim() != 4 or not x_bits.is_contiguous():
+        raise ValueError("x_bits must be a contiguous int32 device tensor [B][H][W][ceil(Cin/32)]")
+    B, H, W, Cw = x_bits.shape
+    if Cw != words_per_row(Cin):
+        raise ValueError("last dimension does not match Cin")
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (W + 2 * pad - kw) // stride + 1
+    kwords = words_per_row(kh * kw * Cin)
+    if out is None:
+        out = _alloc_words(B * max(Ho, 0) * max(Wo, 0), kwords, x_bits.device, ld_out)
+    _dev(out, torch.int32, "out")
+    _check("bnn_conv_im2col_pack",
+           lib.bnn_conv_im2col_pack(x_bits.data_ptr(), B, H, W, Cin, kh, kw, stride, pad, out.data_ptr(),
+                                    _ld(out), _stream()))
+    return out
+
+
+def gemm_i8_mfma(A: torch.Tensor, B: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """bnn_gemm_i8_mfma: int8 A [M][K], int8 B [N][K] -> int32 C [M][N]."""
+    lib = load_library()
+    _dev(A, torch.int8, "A")
+    _dev(B, torch.int8, "B")
+    M, K = A.shape
+    N, K2 = B.shape
+    if K != K2:
+        raise ValueError("A and B disagree on K")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    _dev(out, torch.int32, "out")
+    _check("bnn_gemm_i8_mfma", lib.bnn_gemm_i8_mfma(A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), out.data_ptr(),
+                                                   _ld(out), M, N, K, _stream()))
+    return out
+
+
+def unpack_i8(bits: torch.Tensor, K: int, ld_out: int | None = None) -> torch.Tensor:
+    """bnn_unpack_i8: packed rows -> int8 +-1 [rows][K] (row stride ld_out, default K rounded up to 16)."""
+    lib = load_library()
+    _dev(bits, torch.int32, "bits")
+    rows = bits.shape[0]
+    ld = ld_out if ld_out is not None else (K + 15) // 16 * 16
+    buf = torch.empty((rows, ld), dtype=torch.int8, device=bits.device)
+    _check("bnn_unpack_i8", lib.bnn_unpack_i8(bits.data_ptr(), _ld(bits), rows, K, buf.data_ptr(), ld, _stream()))
+    return buf[:, :K] if ld != K else buf

@@ -1,0 +1,105 @@
+// bnn_bn_sign_pack: a^b_k = Sign(BatchNorm(a_k, theta_k)) of Alg. 4 on folded
+// per-channel integer thresholds, written as packed bits for the next layer.
+//
+//   out[m][n/32] bit (n%32) = (C[m][n] >= thr[n]) XOR flip[n]
+//
+// HBM-bound streaming kernel (4 B read, 1/8 B written per element; thresholds
+// and flip words stay in cache).  Same work split as the Sign packer: an
+// aligned group of 8 lanes produces one output word, each lane comparing 4
+// consecutive int32 (one 16-byte load on the fast path), nibbles combined by
+// three DPP permutes.
+#include "bnn_internal.h"
+
+namespace bnn {
+
+constexpr int kBnThreads = 256;
+constexpr int kBnUnroll = 4;
+
+template <bool VEC>
+__global__ __launch_bounds__(kBnThreads) void bn_sign_pack_kernel(
+    const int32_t* __restrict__ C, int64_t ldc, int64_t M, int64_t N,
+    const int32_t* __restrict__ thr, const uint32_t* __restrict__ flip_bits,
+    uint32_t* __restrict__ out, int64_t ld_out, int64_t nw, int64_t n_words) {
+    const int q = threadIdx.x & 7;
+    const int64_t groups_per_pass = int64_t(gridDim.x) * (kBnThreads / 8);
+    int64_t g0 = int64_t(blockIdx.x) * (kBnThreads / 8) + (threadIdx.x >> 3);
+
+    for (; g0 < n_words; g0 += groups_per_pass * kBnUnroll) {
+        int4 c[kBnUnroll];
+        int64_t row_of[kBnUnroll], word_of[kBnUnroll];
+#pragma unroll
+        for (int u = 0; u < kBnUnroll; ++u) {
+            const int64_t g = g0 + u * groups_per_pass;
+            const bool live = g < n_words;
+            const int64_t row = live ? g / nw : 0;
+            const int64_t w = live ? g - row * nw : 0;
+            row_of[u] = live ? row : -1;
+            word_of[u] = w;
+            const int64_t n0 = w * 32 + q * 4;
+            const int32_t* p = C + row * ldc + n0;
+            c[u] = make_int4(0, 0, 0, 0);
+            if (live) {
+                if (VEC && n0 + 3 < N) {
+                    c[u] = *reinterpret_cast<const int4*>(p);
+                } else {
+                    if (n0 + 0 < N) c[u].x = p[0];
+                    if (n0 + 1 < N) c[u].y = p[1];
+                    if (n0 + 2 < N) c[u].z = p[2];
+                    if (n0 + 3 < N) c[u].w = p[3];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kBnUnroll; ++u) {
+            const int64_t n0 = word_of[u] * 32 + q * 4;
+            int4 t = make_int4(0, 0, 0, 0);
+            if (VEC && n0 + 3 < N) {
+                t = *reinterpret_cast<const int4*>(thr + n0);
+            } else {
+                if (n0 + 0 < N) t.x = thr[n0 + 0];
+                if (n0 + 1 < N) t.y = thr[n0 + 1];
+                if (n0 + 2 < N) t.z = thr[n0 + 2];
+                if (n0 + 3 < N) t.w = thr[n0 + 3];
+            }
+            // Bits of channels >= N: flip word has zero pad bits, and the mask below clears them.
+            const uint32_t flip = (flip_bits[word_of[u]] >> (4 * q)) & 0xFu;
+            uint32_t nib = uint32_t(c[u].x >= t.x) | (uint32_t(c[u].y >= t.y) << 1) |
+                           (uint32_t(c[u].z >= t.z) << 2) | (uint32_t(c[u].w >= t.w) << 3);
+            nib ^= flip;
+            const int64_t valid = N - n0;                       // channels left from this lane's first
+            const uint32_t vmask = valid >= 4 ? 0xFu : (valid <= 0 ? 0u : ((1u << valid) - 1u));
+            nib &= vmask;
+            const uint32_t word = or_reduce8(nib << (4 * q));
+            if (q == 0 && row_of[u] >= 0) out[row_of[u] * ld_out + word_of[u]] = word;
+        }
+    }
+}
+
+}  // namespace bnn
+
+extern "C" int bnn_bn_sign_pack(const int32_t* C, int64_t ldc, int64_t M, int64_t N,
+                                const int32_t* thr, const uint32_t* flip_bits, uint32_t* out,
+                                int64_t ld_out, void* stream) {
+    using namespace bnn;
+    if (M < 0 || N < 0 || M > kMaxDim || N > kMaxDim) return BNN_ERR_INVALID_ARG;
+    const int64_t nw = ceil_div(N, 32);
+    if (ldc < N || ld_out < nw) return BNN_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return BNN_OK;
+    if (!C || !thr || !flip_bits || !out) return BNN_ERR_INVALID_ARG;
+    if (!aligned_to(C, 4) || !aligned_to(thr, 4) || !aligned_to(flip_bits, 4) || !aligned_to(out, 4))
+        return BNN_ERR_ALIGNMENT;
+
+    const int64_t n_words = M * nw;
+    int64_t blocks = ceil_div(n_words, int64_t(kBnThreads / 8) * kBnUnroll);
+    const int64_t max_blocks = 256 * 32;
+    if (blocks > max_blocks) blocks = max_blocks;
+    const bool vec = aligned_to(C, 16) && aligned_to(thr, 16) && ldc % 4 == 0;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (vec)
+        hipLaunchKernelGGL(bn_sign_pack_kernel<true>, dim3(unsigned(blocks)), dim3(kBnThreads), 0, s, C, ldc,
+                           M, N, thr, flip_bits, out, ld_out, nw, n_words);
+    else
+        hipLaunchKernelGGL(bn_sign_pack_kernel<false>, dim3(unsigned(blocks)), dim3(kBnThreads), 0, s, C, ldc,
+                           M, N, thr, flip_bits, out, ld_out, nw, n_words);
+    return check_launch();
+}

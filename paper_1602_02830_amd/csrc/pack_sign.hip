@@ -1,0 +1,91 @@
+// bnn_pack_sign: Eq. (1) binarisation fused with the 32-per-word packing of Sec. 4.
+//
+// HBM-bound streaming kernel: 4 B read and 1/8 B written per element.
+// Work unit: one output word = 32 consecutive elements of a row, handled by an
+// aligned group of 8 lanes; each lane reads 4 consecutive floats (one 16-byte
+// load on the fast path), forms a 4-bit nibble and the group ORs the shifted
+// nibbles together with three DPP permutes.  A wavefront therefore reads eight
+// 128-byte segments and writes eight words per step, and groups never straddle
+// a row, so rows whose length is not a multiple of 32 cost nothing extra apart
+// from their own partial last word.
+#include "bnn_internal.h"
+
+namespace bnn {
+
+constexpr int kPackThreads = 256;
+constexpr int kPackUnroll = 4;   // words per group of 8 lanes per pass (loads in flight)
+
+__device__ inline uint32_t ge_zero(float v) { return v >= 0.0f ? 1u : 0u; }
+
+template <bool VEC>
+__global__ __launch_bounds__(kPackThreads) void pack_sign_kernel(
+    const float* __restrict__ x, int64_t rows, int64_t cols, int64_t ld_x,
+    uint32_t* __restrict__ out, int64_t ld_out, int64_t kw, int64_t n_words) {
+    const int q = threadIdx.x & 7;                       // lane within its group
+    const int64_t groups_per_pass = int64_t(gridDim.x) * (kPackThreads / 8);
+    int64_t g0 = int64_t(blockIdx.x) * (kPackThreads / 8) + (threadIdx.x >> 3);
+
+    for (; g0 < n_words; g0 += groups_per_pass * kPackUnroll) {
+        float v[kPackUnroll][4];
+        int64_t word_of[kPackUnroll];
+        int64_t row_of[kPackUnroll];
+#pragma unroll
+        for (int u = 0; u < kPackUnroll; ++u) {
+            const int64_t g = g0 + u * groups_per_pass;
+            const bool live = g < n_words;
+            const int64_t row = live ? g / kw : 0;
+            const int64_t w = live ? g - row * kw : 0;
+            row_of[u] = live ? row : -1;
+            word_of[u] = w;
+            const int64_t c0 = w * 32 + q * 4;
+            const float* p = x + row * ld_x + c0;
+            // Out-of-range elements take a negative value: bit 0.
+            v[u][0] = v[u][1] = v[u][2] = v[u][3] = -1.0f;
+            if (live) {
+                if (VEC && c0 + 3 < cols) {
+                    const float4 f = *reinterpret_cast<const float4*>(p);
+                    v[u][0] = f.x; v[u][1] = f.y; v[u][2] = f.z; v[u][3] = f.w;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (c0 + e < cols) v[u][e] = p[e];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kPackUnroll; ++u) {
+            uint32_t nib = ge_zero(v[u][0]) | (ge_zero(v[u][1]) << 1) |
+                           (ge_zero(v[u][2]) << 2) | (ge_zero(v[u][3]) << 3);
+            const uint32_t word = or_reduce8(nib << (4 * q));
+            if (q == 0 && row_of[u] >= 0) out[row_of[u] * ld_out + word_of[u]] = word;
+        }
+    }
+}
+
+}  // namespace bnn
+
+extern "C" int bnn_pack_sign(const float* x, int64_t rows, int64_t cols, int64_t ld_x,
+                             uint32_t* out, int64_t ld_out, void* stream) {
+    using namespace bnn;
+    if (rows < 0 || cols < 0 || rows > kMaxDim || cols > kMaxDim) return BNN_ERR_INVALID_ARG;
+    const int64_t kw = ceil_div(cols, 32);
+    if (ld_x < cols || ld_out < kw) return BNN_ERR_INVALID_ARG;
+    if (rows == 0 || cols == 0) return BNN_OK;
+    if (!x || !out) return BNN_ERR_INVALID_ARG;
+    if (!aligned_to(x, 4) || !aligned_to(out, 4)) return BNN_ERR_ALIGNMENT;
+
+    const int64_t n_words = rows * kw;
+    const int64_t groups_per_block = kPackThreads / 8;
+    int64_t blocks = ceil_div(n_words, groups_per_block * kPackUnroll);
+    const int64_t max_blocks = 256 * 32;   // 256 CUs, enough blocks in flight to cover HBM latency
+    if (blocks > max_blocks) blocks = max_blocks;
+    const bool vec = aligned_to(x, 16) && (ld_x % 4 == 0);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (vec)
+        hipLaunchKernelGGL(pack_sign_kernel<true>, dim3(unsigned(blocks)), dim3(kPackThreads), 0, s,
+                           x, rows, cols, ld_x, out, ld_out, kw, n_words);
+    else
+        hipLaunchKernelGGL(pack_sign_kernel<false>, dim3(unsigned(blocks)), dim3(kPackThreads), 0, s,
+                           x, rows, cols, ld_x, out, ld_out, kw, n_words);
+    return check_launch();
+}

@@ -1,0 +1,345 @@
+// bnn_xnor_gemm: the XNOR-popcount matrix product of Sec. 4, Eq. (5), i.e. the
+// XnorDotProduct of Alg. 4 over whole matrices.
+//
+//   C[m][n] = K - 2 * sum_w popcount(A[m][w] ^ B[n][w])
+//
+// which equals 2*popcount(xnor)-K over the K valid bits once the pad bits of
+// both operands are masked (done when a tile is staged, never in the inner loop).
+//
+// The inner step is two full-rate vector-ALU instructions per 32 connections
+// and output: v_xor_b32 and v_bcnt_u32_b32 (whose third operand is the running
+// accumulator).  The kernels below differ only in how operands reach registers:
+//
+//   tiled   - BMxBN output tile per 256-thread workgroup, TMxTN accumulators per
+//             thread, operand tiles staged global -> registers -> LDS (double
+//             buffered, one barrier per K-tile), read back as 128-bit LDS loads.
+//   ksplit  - skinny outputs (few columns or few rows): a wavefront owns a
+//             small output tile and its 64 lanes split K; lane partial sums
+//             are combined with DPP / cross-lane adds.
+//   naive   - one thread per output, for tiny problems and as a cross-check.
+#include "bnn_internal.h"
+
+namespace bnn {
+
+// ----------------------------------------------------------------------------
+// naive: one thread per output element
+// ----------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void xnor_gemm_naive_kernel(
+    const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B, int64_t ldb,
+    int32_t* __restrict__ C, int64_t ldc, int M, int N, int K) {
+    const int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (idx >= int64_t(M) * N) return;
+    const int m = int(idx / N);
+    const int n = int(idx - int64_t(m) * N);
+    const int kw = (K + 31) >> 5;
+    const uint32_t* a = A + m * lda;
+    const uint32_t* b = B + n * ldb;
+    uint32_t acc = 0;
+    for (int w = 0; w + 1 < kw; ++w) acc += __popc(a[w] ^ b[w]);
+    if (kw > 0) acc += __popc((a[kw - 1] ^ b[kw - 1]) & tail_mask(K));
+    C[m * ldc + n] = K - 2 * int(acc);
+}
+
+// ----------------------------------------------------------------------------
+// tiled: LDS-staged, register-blocked
+// ----------------------------------------------------------------------------
+// Workgroup = 256 threads = 16 (tx) x 16 (ty).  Thread (ty,tx) owns rows
+// ty + 16*i (i < TM) and columns tx + 16*j (j < TN) of the BM x BN tile, with
+// BM = 16*TM, BN = 16*TN.  A wavefront is 4 consecutive ty x all 16 tx, so an
+// LDS read of an A row is a 16-lane broadcast and the 16 B rows read by one
+// instruction are 16 consecutive 16-byte slots: both conflict-free.
+//
+// LDS holds, per operand and buffer, KQ planes of (rows + 2) 16-byte slots;
+// plane q, slot r = words [4q, 4q+4) of tile row r.  The 2-slot pad staggers
+// the planes so that the staging stores of 8 consecutive lanes (2 rows x 4
+// planes) fall in distinct bank groups.
+template <int TM, int TN, int KT>
+struct TileCfg {
+    static constexpr int BM = 16 * TM;
+    static constexpr int BN = 16 * TN;
+    static constexpr int KQ = KT / 4;                  // 128-bit quads per K-tile
+    static constexpr int PLANE_A = BM + 2;             // slots per plane
+    static constexpr int PLANE_B = BN + 2;
+    static constexpr int SLOTS_A = KQ * PLANE_A;
+    static constexpr int SLOTS_B = KQ * PLANE_B;
+    static constexpr int LOADS_A = BM * KQ / 256;      // 16-byte loads per thread per K-tile
+    static constexpr int LOADS_B = BN * KQ / 256;
+    static_assert(BM * KQ % 256 == 0 && BN * KQ % 256 == 0, "tile must divide among 256 threads");
+};
+
+// Loads words [4*quad, 4*quad+4) of row `row` (quad counted from the matrix's
+// first word), zero where the row or word does not exist, pad bits masked.
+template <bool VEC>
+__device__ inline uint4 load_quad(const uint32_t* __restrict__ P, int64_t ld, int rows, int kw,
+                                  uint32_t tmask, int row, int quad) {
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    const int w0 = quad * 4;
+    if (row < rows && w0 < kw) {
+        const uint32_t* p = P + int64_t(row) * ld + w0;
+        if (VEC && w0 + 4 <= kw) {
+            v = *reinterpret_cast<const uint4*>(p);
+        } else {
+            v.x = p[0];
+            if (w0 + 1 < kw) v.y = p[1];
+            if (w0 + 2 < kw) v.z = p[2];
+            if (w0 + 3 < kw) v.w = p[3];
+        }
+        const int last = kw - 1 - w0;     // position of the row's last word inside this quad
+        if (last == 0) v.x &= tmask;
+        else if (last == 1) v.y &= tmask;
+        else if (last == 2) v.z &= tmask;
+        else if (last == 3) v.w &= tmask;
+    }
+    return v;
+}
+
+// Maps the hardware's round-robin placement of consecutive workgroups on the 8
+// accelerator dies (each with its own L2) to compact panels of tiles: die d
+// gets the contiguous range [d*per, (d+1)*per) of logical tile ids, and
+// logical ids walk the tile grid in column-major bands of 8 tile-rows, so the
+// tiles resident on one die at a time share a few A panels and B panels.
+__device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
+    const int total = tiles_m * tiles_n;
+    constexpr int kDies = 8;
+    int logical = bid;
+    const int per = total / kDies;
+    if (bid < per * kDies) logical = (bid % kDies) * per + bid / kDies;
+    constexpr int kBand = 8;
+    const int band_tiles = kBand * tiles_n;
+    const int band = logical / band_tiles;
+    const int in_band = logical - band * band_tiles;
+    const int rows_in_band = min(kBand, tiles_m - band * kBand);
+    tn = in_band / rows_in_band;
+    tm = band * kBand + (in_band - tn * rows_in_band);
+}
+
+template <int TM, int TN, int KT, bool VEC>
+__global__ __launch_bounds__(256) void xnor_gemm_tiled_kernel(
+    const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B, int64_t ldb,
+    int32_t* __restrict__ C, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n) {
+    using Cfg = TileCfg<TM, TN, KT>;
+    __shared__ uint4 lds_a[2][Cfg::SLOTS_A];
+    __shared__ uint4 lds_b[2][Cfg::SLOTS_B];
+
+    int tile_m, tile_n;
+    tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+    const int row0 = tile_m * Cfg::BM;
+    const int col0 = tile_n * Cfg::BN;
+
+    const int tid = threadIdx.x;
+    const int tx = tid & 15;
+    const int ty = tid >> 4;
+    const int kw = (K + 31) >> 5;
+    const uint32_t tmask = tail_mask(K);
+    const int n_ktiles = (kw + KT - 1) / KT;
+
+    // Staging assignment: load l of this thread covers tile row (tid / KQ) + l * (256 / KQ), plane tid % KQ.
+    const int st_q = tid % Cfg::KQ;
+    const int st_r = tid / Cfg::KQ;
+    constexpr int ST_ROWS = 256 / Cfg::KQ;
+
+    uint4 ra[Cfg::LOADS_A], rb[Cfg::LOADS_B];
+    auto fetch = [&](int kt) {
+        const int quad = kt * Cfg::KQ + st_q;
+#pragma unroll
+        for (int l = 0; l < Cfg::LOADS_A; ++l)
+            ra[l] = load_quad<VEC>(A, lda, M, kw, tmask, row0 + st_r + l * ST_ROWS, quad);
+#pragma unroll
+        for (int l = 0; l < Cfg::LOADS_B; ++l)
+            rb[l] = load_quad<VEC>(B, ldb, N, kw, tmask, col0 + st_r + l * ST_ROWS, quad);
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int l = 0; l < Cfg::LOADS_A; ++l)
+            lds_a[buf][st_q * Cfg::PLANE_A + st_r + l * ST_ROWS] = ra[l];
+#pragma unroll
+        for (int l = 0; l < Cfg::LOADS_B; ++l)
+            lds_b[buf][st_q * Cfg::PLANE_B + st_r + l * ST_ROWS] = rb[l];
+    };
+
+    uint32_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = 0u;
+
+    if (n_ktiles > 0) {
+        fetch(0);
+        stage(0);
+    }
+    __syncthreads();
+
+    for (int kt = 0; kt < n_ktiles; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < n_ktiles) fetch(kt + 1);   // global loads in flight during the compute below
+
+#pragma unroll 1
+        for (int q = 0; q < Cfg::KQ; ++q) {
+            uint4 a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = lds_a[buf][q * Cfg::PLANE_A + ty + 16 * i];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = lds_b[buf][q * Cfg::PLANE_B + tx + 16 * j];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    acc[i][j] += __popc(a[i].x ^ b[j].x);
+                    acc[i][j] += __popc(a[i].y ^ b[j].y);
+                    acc[i][j] += __popc(a[i].z ^ b[j].z);
+                    acc[i][j] += __popc(a[i].w ^ b[j].w);
+                }
+        }
+
+        if (kt + 1 < n_ktiles) stage(buf ^ 1);
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = row0 + ty + 16 * i;
+        if (m < M) {
+            int32_t* crow = C + int64_t(m) * ldc;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = col0 + tx + 16 * j;
+                if (n < N) crow[n] = K - 2 * int(acc[i][j]);
+            }
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------
+// ksplit: one wavefront per RS x CS output tile, lanes split K
+// ----------------------------------------------------------------------------
+template <int RS, int CS>
+__global__ __launch_bounds__(256) void xnor_gemm_ksplit_kernel(
+    const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B, int64_t ldb,
+    int32_t* __restrict__ C, int64_t ldc, int M, int N, int K, int tiles_n, int64_t n_tiles) {
+    const int lane = threadIdx.x & 63;
+    const int64_t tile = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (tile >= n_tiles) return;                  // whole wavefront leaves together
+    const int tm = int(tile / tiles_n);
+    const int tn = int(tile - int64_t(tm) * tiles_n);
+    const int row0 = tm * RS, col0 = tn * CS;
+    const int kw = (K + 31) >> 5;
+    const uint32_t tmask = tail_mask(K);
+
+    int acc[RS][CS];
+#pragma unroll
+    for (int i = 0; i < RS; ++i)
+#pragma unroll
+        for (int j = 0; j < CS; ++j) acc[i][j] = 0;
+
+    for (int w = lane; w < kw; w += 64) {
+        const uint32_t mask = (w == kw - 1) ? tmask : 0xFFFFFFFFu;
+        uint32_t a[RS], b[CS];
+#pragma unroll
+        for (int i = 0; i < RS; ++i) a[i] = (row0 + i < M) ? A[int64_t(row0 + i) * lda + w] & mask : 0u;
+#pragma unroll
+        for (int j = 0; j < CS; ++j) b[j] = (col0 + j < N) ? B[int64_t(col0 + j) * ldb + w] & mask : 0u;
+#pragma unroll
+        for (int i = 0; i < RS; ++i)
+#pragma unroll
+            for (int j = 0; j < CS; ++j) acc[i][j] += __popc(a[i] ^ b[j]);
+    }
+    // Lanes that ran fewer iterations hold smaller partial sums; all 64 lanes are
+    // active again here, as the reduction needs.
+#pragma unroll
+    for (int i = 0; i < RS; ++i)
+#pragma unroll
+        for (int j = 0; j < CS; ++j) {
+            const int total = wave_sum(acc[i][j]);
+            if (lane == 0 && row0 + i < M && col0 + j < N)
+                C[int64_t(row0 + i) * ldc + col0 + j] = K - 2 * total;
+        }
+}
+
+// ----------------------------------------------------------------------------
+// host side
+// ----------------------------------------------------------------------------
+enum { KERNEL_AUTO = 0, KERNEL_NAIVE = 1, KERNEL_TILED128 = 2, KERNEL_KSPLIT = 3, KERNEL_TILED64 = 4 };
+
+template <int TM, int TN, int KT>
+static void launch_tiled(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
+                         int64_t ldc, int M, int N, int K, hipStream_t s) {
+    using Cfg = TileCfg<TM, TN, KT>;
+    const int tiles_m = int(ceil_div(M, Cfg::BM));
+    const int tiles_n = int(ceil_div(N, Cfg::BN));
+    const bool vec = aligned_to(A, 16) && aligned_to(B, 16) && lda % 4 == 0 && ldb % 4 == 0;
+    const dim3 grid(unsigned(int64_t(tiles_m) * tiles_n));
+    if (vec)
+        hipLaunchKernelGGL((xnor_gemm_tiled_kernel<TM, TN, KT, true>), grid, dim3(256), 0, s, A, lda, B,
+                           ldb, C, ldc, M, N, K, tiles_m, tiles_n);
+    else
+        hipLaunchKernelGGL((xnor_gemm_tiled_kernel<TM, TN, KT, false>), grid, dim3(256), 0, s, A, lda, B,
+                           ldb, C, ldc, M, N, K, tiles_m, tiles_n);
+}
+
+static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
+                              int64_t ldc, int64_t M, int64_t N, int64_t K, int kernel_id,
+                              void* stream) {
+    if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return BNN_ERR_INVALID_ARG;
+    if (kernel_id < KERNEL_AUTO || kernel_id > KERNEL_TILED64) return BNN_ERR_INVALID_ARG;
+    const int64_t kw = ceil_div(K, 32);
+    if (lda < kw || ldb < kw || ldc < N) return BNN_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return BNN_OK;
+    if (!C || (K > 0 && (!A || !B))) return BNN_ERR_INVALID_ARG;
+    if (!aligned_to(A, 4) || !aligned_to(B, 4) || !aligned_to(C, 4)) return BNN_ERR_ALIGNMENT;
+    // Tile grids are indexed with 32-bit integers.
+    if (ceil_div(M, 16) * ceil_div(N, 16) > kMaxDim) return BNN_ERR_UNSUPPORTED;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int m = int(M), n = int(N), k = int(K);
+
+    if (kernel_id == KERNEL_AUTO) {
+        const int64_t tiles128 = ceil_div(M, 128) * ceil_div(N, 128);
+        if (N <= 16 || M <= 4)
+            kernel_id = KERNEL_KSPLIT;
+        else if (tiles128 >= 512)
+            kernel_id = KERNEL_TILED128;
+        else
+            kernel_id = KERNEL_TILED64;
+    }
+
+    switch (kernel_id) {
+        case KERNEL_NAIVE: {
+            const int64_t total = M * N;
+            if (ceil_div(total, 256) > kMaxDim) return BNN_ERR_UNSUPPORTED;
+            hipLaunchKernelGGL(xnor_gemm_naive_kernel, dim3(unsigned(ceil_div(total, 256))), dim3(256), 0, s,
+                               A, lda, B, ldb, C, ldc, m, n, k);
+            break;
+        }
+        case KERNEL_TILED128:
+            launch_tiled<8, 8, 16>(A, lda, B, ldb, C, ldc, m, n, k, s);
+            break;
+        case KERNEL_TILED64:
+            launch_tiled<4, 4, 16>(A, lda, B, ldb, C, ldc, m, n, k, s);
+            break;
+        case KERNEL_KSPLIT: {
+            constexpr int RS = 2, CS = 4;
+            const int tiles_n = int(ceil_div(N, CS));
+            const int64_t n_tiles = ceil_div(M, RS) * tiles_n;
+            if (ceil_div(n_tiles, 4) > kMaxDim) return BNN_ERR_UNSUPPORTED;
+            hipLaunchKernelGGL((xnor_gemm_ksplit_kernel<RS, CS>), dim3(unsigned(ceil_div(n_tiles, 4))),
+                               dim3(256), 0, s, A, lda, B, ldb, C, ldc, m, n, k, tiles_n, n_tiles);
+            break;
+        }
+        default:
+            return BNN_ERR_INVALID_ARG;
+    }
+    return check_launch();
+}
+
+}  // namespace bnn
+
+extern "C" int bnn_xnor_gemm(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
+                             int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream) {
+    return bnn::xnor_gemm_dispatch(A, lda, B, ldb, C, ldc, M, N, K, bnn::KERNEL_AUTO, stream);
+}
+
+extern "C" int bnn_xnor_gemm_kernel(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb,
+                                    int32_t* C, int64_t ldc, int64_t M, int64_t N, int64_t K,
+                                    int kernel_id, void* stream) {
+    return bnn::xnor_gemm_dispatch(A, lda, B, ldb, C, ldc, M, N, K, kernel_id, stream);
+}

@@ -1,0 +1,112 @@
+"""Layer chaining for the forward path of Alg. 4 ("Running a BNN").
+
+These classes own device buffers and call the library in the order the
+algorithm states; they do no arithmetic themselves.  Packed words are held in
+int32 tensors.  Leading dimensions of packed buffers are rounded up to 4 words
+so that every row is 16-byte aligned (the fast-path requirement of the GEMM).
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def _round_up(x: int, m: int) -> int:
+    return (x + m - 1) // m * m
+
+
+def _packed_buffer(rows: int, K: int, device) -> torch.Tensor:
+    kw = B.words_per_row(K)
+    ld = _round_up(kw, 4)
+    buf = torch.zeros((rows, ld), dtype=torch.int32, device=device)
+    return buf[:, :kw] if ld != kw else buf
+
+
+class BinaryMLP:
+    """Fully binarized MLP: Sign+pack the real input, then per hidden layer
+    XnorDotProduct -> Sign(BatchNorm) (Alg. 4, step 2); the last layer emits the
+    int32 pre-activations.
+
+    weights_real: list of float32 device tensors W_l [N_l][K_l] (row n = output unit n);
+        they are binarized with Eq. (1) and packed once, on the device.
+    bns: per hidden layer (gamma, beta, mean, var) as numpy float32 [N_l]; folded once on the host.
+    """
+
+    def __init__(self, weights_real, bns, eps: float, batch: int, keep_preacts: bool = True):
+        assert len(bns) == len(weights_real) - 1
+        dev = weights_real[0].device
+        self.device = dev
+        self.batch = batch
+        self.K = [int(w.shape[1]) for w in weights_real]
+        self.N = [int(w.shape[0]) for w in weights_real]
+        self.w_bits = []
+        for w in weights_real:
+            buf = _packed_buffer(w.shape[0], w.shape[1], dev)
+            B.pack_sign(w, out=buf)
+            self.w_bits.append(buf)
+        self.thr, self.flip = [], []
+        for l, bn in enumerate(bns):
+            thr, flip = B.bn_fold(*bn, eps, self.K[l])
+            self.thr.append(torch.from_numpy(thr).to(dev))
+            self.flip.append(torch.from_numpy(flip.view(np.int32)).to(dev))
+        # Activations a^b_l (packed) and pre-activations s_l (int32), allocated once.
+        self.a_bits = [_packed_buffer(batch, self.K[0], dev)]
+        for l in range(len(bns)):
+            self.a_bits.append(_packed_buffer(batch, self.N[l], dev))
+        self.keep_preacts = keep_preacts
+        if keep_preacts:
+            self.s = [torch.empty((batch, n), dtype=torch.int32, device=dev) for n in self.N]
+        else:
+            # One scratch buffer reused by every hidden layer, plus the score buffer.
+            scratch = torch.empty((batch, max(self.N[:-1])), dtype=torch.int32, device=dev)
+            self.s = [scratch[:, :n] if n != scratch.shape[1] else scratch for n in self.N[:-1]]
+            self.s.append(torch.empty((batch, self.N[-1]), dtype=torch.int32, device=dev))
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        """x: float32 device tensor [batch][K_0].  Returns the int32 scores [batch][N_last]."""
+        B.pack_sign(x, out=self.a_bits[0])
+        n_layers = len(self.w_bits)
+        for l in range(n_layers):
+            B.xnor_gemm(self.a_bits[l], self.w_bits[l], self.K[l], out=self.s[l])
+            if l + 1 < n_layers:
+                B.bn_sign_pack(self.s[l], self.thr[l], self.flip[l], out=self.a_bits[l + 1])
+        return self.s[-1]
+
+
+class BinaryConvLayer:
+    """One binary 3x3 (or kh x kw) convolution layer lowered to the binary GEMM:
+    im2col on packed NHWC bits -> XnorDotProduct -> Sign(BatchNorm) -> packed NHWC bits.
+
+    weight_real: float32 device tensor [Cout][kh][kw][Cin], binarized by Eq. (1) on the device.
+    """
+
+    def __init__(self, weight_real, bn, eps: float, batch: int, H: int, W: int, stride: int = 1, pad: int = 1):
+        dev = weight_real.device
+        self.Cout, self.kh, self.kw, self.Cin = (int(d) for d in weight_real.shape)
+        self.stride, self.pad = stride, pad
+        self.B, self.H, self.W = batch, H, W
+        self.Ho = (H + 2 * pad - self.kh) // stride + 1
+        self.Wo = (W + 2 * pad - self.kw) // stride + 1
+        self.K = self.kh * self.kw * self.Cin
+        self.M = batch * self.Ho * self.Wo
+        if self.Cin % 32 == 0:
+            w2d = weight_real.reshape(self.Cout, self.K)
+        else:
+            raise ValueError("BinaryConvLayer packs weights per row; Cin must be a multiple of 32 here")
+        self.w_bits = _packed_buffer(self.Cout, self.K, dev)
+        B.pack_sign(w2d, out=self.w_bits)
+        thr, flip = B.bn_fold(*bn, eps, self.K)
+        self.thr = torch.from_numpy(thr).to(dev)
+        self.flip = torch.from_numpy(flip.view(np.int32)).to(dev)
+        self.cols = _packed_buffer(self.M, self.K, dev)
+        self.s = torch.empty((self.M, self.Cout), dtype=torch.int32, device=dev)
+        self.out_bits = torch.empty((self.M, B.words_per_row(self.Cout)), dtype=torch.int32, device=dev)
+
+    def forward(self, x_bits: torch.Tensor) -> torch.Tensor:
+        """x_bits: packed NHWC int32 [B][H][W][Cin/32].  Returns packed NHWC [B][Ho][Wo][ceil(Cout/32)]."""
+        B.conv_im2col_pack(x_bits, self.Cin, self.kh, self.kw, self.stride, self.pad, out=self.cols)
+        B.xnor_gemm(self.cols, self.w_bits, self.K, out=self.s)
+        B.bn_sign_pack(self.s, self.thr, self.flip, out=self.out_bits)
+        return self.out_bits.view(self.B, self.Ho, self.Wo, -1)

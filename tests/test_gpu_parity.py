@@ -1,0 +1,370 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, bit for bit,
+on the same seeded inputs.  All int32 results and all packed words must be
+equal; there is no tolerance anywhere."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1602_02830_amd as bnn
+from workloads import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+EPS = oracle.EPS_DEFAULT
+GEMM_KERNELS = {
+    "auto": bnn.KERNEL_AUTO,
+    "naive": bnn.KERNEL_NAIVE,
+    "tiled128": bnn.KERNEL_TILED128,
+    "ksplit": bnn.KERNEL_KSPLIT,
+    "tiled64": bnn.KERNEL_TILED64,
+}
+
+
+def words_to_dev(w: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(w).view(np.int32)).to(DEV)
+
+
+def words_to_host(t: torch.Tensor) -> np.ndarray:
+    return t.contiguous().cpu().numpy().view(np.uint32)
+
+
+def poison_pad_bits(words: np.ndarray, K: int) -> np.ndarray:
+    """Sets every pad bit of the last word of each row to 1."""
+    out = words.copy()
+    r = K % 32
+    if r and out.shape[1] > 0:
+        out[:, -1] |= np.uint32((0xFFFFFFFF << r) & 0xFFFFFFFF)
+    return out
+
+
+def strided_words(w: np.ndarray, ld: int, fill=0x5A5A5A5A) -> torch.Tensor:
+    """Device copy of packed rows with leading dimension ld > row length (pad words = junk)."""
+    rows, kw = w.shape
+    buf = np.full((rows, ld), fill, np.uint32)
+    buf[:, :kw] = w
+    return words_to_dev(buf)[:, :kw]
+
+
+# ------------------------------------------------------------------ pack_sign
+
+def test_pack_sign_table(golden_dir):
+    bits, want = [], []
+    for line in open(os.path.join(golden_dir, "sign_table.txt")):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            h, _n, s = line.split()
+            bits.append(int(h, 16))
+            want.append(int(s))
+    x = np.array(bits, np.uint32).view(np.float32)[None, :]
+    got = words_to_host(bnn.pack_sign(torch.from_numpy(x).to(DEV)))
+    want_words = oracle.pack_bits(np.array(want, np.int8)[None, :])
+    assert (got == want_words).all()
+    assert (oracle.pack_bits(oracle.sign(x)) == got).all()
+
+
+@pytest.mark.parametrize("rows,cols", [(1, 1), (3, 31), (5, 32), (7, 33), (64, 1024), (33, 784),
+                                       (2, 4099), (1000, 100), (129, 4096)])
+def test_pack_sign_shapes(rows, cols):
+    rng = np.random.default_rng(rows * 10007 + cols)
+    x = synth.real_input(rng, (rows, cols))
+    x[rng.random((rows, cols)) < 0.05] = 0.0
+    x[rng.random((rows, cols)) < 0.02] = -0.0
+    want = oracle.pack_bits(oracle.sign(x))
+    got = words_to_host(bnn.pack_sign(torch.from_numpy(x).to(DEV)))
+    assert (got == want).all()
+
+
+def test_pack_sign_unaligned_and_strided():
+    rng = np.random.default_rng(77)
+    rows, cols = 37, 203
+    big = synth.real_input(rng, (rows, cols + 9))
+    xd = torch.from_numpy(big).to(DEV)[:, 3:3 + cols]        # ld_x = cols+9, base 12 bytes off
+    want = oracle.pack_bits(oracle.sign(big[:, 3:3 + cols]))
+    kw = want.shape[1]
+    out = torch.full((rows, kw + 3), 0x12345678, dtype=torch.int32, device=DEV)
+    bnn.pack_sign(xd, out=out[:, :kw])
+    host = words_to_host(out)
+    assert (host[:, :kw] == want).all()
+    assert (host[:, kw:] == 0x12345678).all()                # words past the row untouched
+
+
+def test_pack_sign_large_streaming_shape():
+    rng = np.random.default_rng(78)
+    x = synth.real_input(rng, (4096, 8192))
+    want = oracle.pack_bits(oracle.sign(x))
+    got = words_to_host(bnn.pack_sign(torch.from_numpy(x).to(DEV)))
+    assert (got == want).all()
+
+
+# ------------------------------------------------------------------ xnor_gemm
+
+def _gemm_case(A, Bm, kernel, poison=False, ld_extra=0):
+    M, K = A.shape
+    N = Bm.shape[1]
+    want = oracle.matmul_pm1(A, Bm)
+    pa = oracle.pack_bits(A)
+    pb = oracle.pack_bits(np.ascontiguousarray(Bm.T))
+    if poison:
+        pa, pb = poison_pad_bits(pa, K), poison_pad_bits(pb, K)
+    if ld_extra:
+        da = strided_words(pa, pa.shape[1] + ld_extra)
+        db = strided_words(pb, pb.shape[1] + ld_extra)
+    else:
+        da, db = words_to_dev(pa), words_to_dev(pb)
+    got = bnn.xnor_gemm(da, db, K, kernel=kernel).cpu().numpy()
+    assert got.shape == want.shape
+    bad = np.argwhere(got != want)
+    assert bad.size == 0, f"M={M} N={N} K={K} first mismatch at {bad[0]}: got {got[tuple(bad[0])]} want {want[tuple(bad[0])]}"
+    assert (np.abs(got) <= K).all() and ((got - K) % 2 == 0).all()
+
+
+@pytest.mark.parametrize("kernel", list(GEMM_KERNELS))
+def test_xnor_gemm_ragged_sweep(kernel):
+    """All 336 ragged cases (M, N in {1,7,33,1000}; K in {1,31,32,33,63,65,4097};
+    P(+1) in {.05,.5,.95}), once with zero pad bits and once with poisoned ones."""
+    cases = synth.ragged_cases()
+    assert len(cases) == 336
+    for idx, (M, N, K, p) in enumerate(cases):
+        A, Bm = synth.config_ragged(idx)
+        _gemm_case(A, Bm, GEMM_KERNELS[kernel], poison=False)
+        _gemm_case(A, Bm, GEMM_KERNELS[kernel], poison=True)
+
+
+@pytest.mark.parametrize("kernel", ["auto", "tiled128", "tiled64", "naive", "ksplit"])
+def test_xnor_gemm_odd_leading_dimensions(kernel):
+    rng = np.random.default_rng(5)
+    for (M, N, K) in [(130, 70, 1000), (17, 300, 129), (256, 256, 2048)]:
+        A, Bm = synth.pm1(rng, (M, K)), synth.pm1(rng, (K, N))
+        for extra in (1, 3, 4):
+            _gemm_case(A, Bm, GEMM_KERNELS[kernel], poison=True, ld_extra=extra)
+
+
+@pytest.mark.parametrize("kernel", ["auto", "tiled128", "tiled64"])
+def test_xnor_gemm_multi_tile_shapes(kernel):
+    rng = np.random.default_rng(6)
+    for (M, N, K) in [(64, 1024, 1024), (300, 520, 784), (1024, 10, 4096), (513, 129, 96), (2, 2048, 640)]:
+        _gemm_case(synth.pm1(rng, (M, K)), synth.pm1(rng, (K, N)), GEMM_KERNELS[kernel])
+
+
+def test_xnor_gemm_ldc_and_canary():
+    rng = np.random.default_rng(7)
+    M, N, K = 100, 77, 500
+    A, Bm = synth.pm1(rng, (M, K)), synth.pm1(rng, (K, N))
+    out = torch.full((M, N + 5), -12345, dtype=torch.int32, device=DEV)
+    bnn.xnor_gemm(words_to_dev(oracle.pack_bits(A)), words_to_dev(oracle.pack_bits(np.ascontiguousarray(Bm.T))),
+                  K, out=out[:, :N])
+    host = out.cpu().numpy()
+    assert (host[:, :N] == oracle.matmul_pm1(A, Bm)).all()
+    assert (host[:, N:] == -12345).all()
+
+
+def test_xnor_gemm_empty_and_k_zero():
+    a = torch.zeros((0, 4), dtype=torch.int32, device=DEV)
+    b = torch.zeros((5, 4), dtype=torch.int32, device=DEV)
+    assert bnn.xnor_gemm(a, b, 100).shape == (0, 5)
+    a1 = torch.zeros((3, 1), dtype=torch.int32, device=DEV)
+    c = bnn.xnor_gemm(a1, b[:, :1], 0)
+    assert (c.cpu().numpy() == 0).all()
+
+
+@pytest.mark.parametrize("kernel", ["auto", "tiled128"])
+def test_xnor_gemm_dense_layer_config(kernel):
+    """Config: A 64x1024, B 1024x1024, K = 1024."""
+    A, Bm, _ = synth.config_dense()
+    _gemm_case(A, Bm, GEMM_KERNELS[kernel])
+
+
+def test_xnor_gemm_large_square_hadamard_and_sampled_rows():
+    """8192^3 in the launch configuration the benchmark times.  (i) Sylvester-Hadamard
+    operands: the full 8192 x 8192 result must be 8192 * I (closed form, checked on
+    every element).  (ii) random +-1 operands: 256 sampled rows and a band of columns
+    against the oracle."""
+    n = synth.GEMM_LARGE
+    H = synth.hadamard(n)
+    hb = words_to_dev(oracle.pack_bits(H))
+    C = bnn.xnor_gemm(hb, hb, n)
+    assert torch.equal(C, n * torch.eye(n, dtype=torch.int32, device=DEV))
+    del C
+    A, Bm = synth.config_gemm_square(n)
+    da = words_to_dev(oracle.pack_bits(A))
+    db = words_to_dev(oracle.pack_bits(np.ascontiguousarray(Bm.T)))
+    C = bnn.xnor_gemm(da, db, n).cpu().numpy()
+    rows = np.random.default_rng(1).choice(n, 256, replace=False)
+    assert (C[rows] == oracle.matmul_pm1(A[rows], Bm)).all()
+    cols = np.arange(4000, 4128)
+    assert (C[:, cols] == oracle.matmul_pm1(A, np.ascontiguousarray(Bm[:, cols]))).all()
+    assert (np.abs(C) <= n).all() and (C % 2 == 0).all()
+
+
+# ------------------------------------------------------------------ bn_sign_pack
+
+def _fold_to_dev(bn, K):
+    thr, flip = bnn.bn_fold(*bn, EPS, K)
+    return torch.from_numpy(thr).to(DEV), torch.from_numpy(flip.view(np.int32)).to(DEV)
+
+
+@pytest.mark.parametrize("M,N,K,adv", [(64, 1024, 1024, False), (64, 1024, 1024, True), (5, 1, 40, True),
+                                       (33, 31, 64, True), (100, 33, 784, True), (7, 1000, 4096, True),
+                                       (300, 4096, 4096, False)])
+def test_bn_sign_pack_matches_float_bn_then_sign(M, N, K, adv):
+    rng = np.random.default_rng(M + N + K)
+    bn = synth.bn_params(rng, N, K, adversarial=adv)
+    # pre-activations on the lattice {-K, -K+2, ..., K}, concentrated near the thresholds
+    S = np.clip(2 * np.rint(rng.normal(0, np.sqrt(K) / 2, (M, N))) + (K % 2), -K, K).astype(np.int32)
+    want = oracle.pack_bits(oracle.bn_sign(S, *bn, eps=EPS))
+    thr, flip = _fold_to_dev(bn, K)
+    got = words_to_host(bnn.bn_sign_pack(torch.from_numpy(S).to(DEV), thr, flip))
+    assert (got == want).all()
+
+
+def test_bn_sign_pack_strided_unaligned_and_canary():
+    rng = np.random.default_rng(9)
+    M, N, K = 50, 77, 300
+    bn = synth.bn_params(rng, N, K, adversarial=True)
+    S = (2 * rng.integers(0, K + 1, (M, N)) - K).astype(np.int32)
+    big = torch.zeros((M, N + 3), dtype=torch.int32, device=DEV)
+    big[:, 1:N + 1] = torch.from_numpy(S).to(DEV)
+    thr, flip = _fold_to_dev(bn, K)
+    nw = (N + 31) // 32
+    out = torch.full((M, nw + 2), 0x0BADBEEF, dtype=torch.int32, device=DEV)
+    bnn.bn_sign_pack(big[:, 1:N + 1], thr, flip, out=out[:, :nw])
+    host = words_to_host(out)
+    assert (host[:, :nw] == oracle.pack_bits(oracle.bn_sign(S, *bn, eps=EPS))).all()
+    assert (host[:, nw:] == 0x0BADBEEF).all()
+
+
+# ------------------------------------------------------------------ conv_im2col_pack
+
+def _pack_nhwc(x: np.ndarray) -> np.ndarray:
+    B, H, W, C = x.shape
+    return oracle.pack_bits(x.reshape(-1, C)).reshape(B, H, W, -1)
+
+
+@pytest.mark.parametrize("shape", [
+    # B, H, W, Cin, kh, kw, stride, pad
+    (2, 8, 8, 128, 3, 3, 1, 1),
+    (3, 5, 7, 32, 3, 3, 1, 1),
+    (2, 6, 6, 64, 3, 3, 2, 1),
+    (1, 9, 4, 96, 1, 1, 1, 0),
+    (2, 5, 5, 3, 3, 3, 1, 1),
+    (1, 7, 6, 40, 3, 3, 1, 1),
+    (2, 4, 4, 33, 5, 3, 1, 2),
+    (1, 32, 32, 128, 3, 3, 1, 1),
+])
+def test_im2col_pack_matches_oracle_lowering(shape):
+    B, H, W, Cin, kh, kw, stride, pad = shape
+    rng = np.random.default_rng(sum(shape))
+    x = synth.pm1(rng, (B, H, W, Cin))
+    want = oracle.pack_bits(oracle.im2col(x, kh, kw, stride, pad))
+    xb = _pack_nhwc(x)
+    if Cin % 32:
+        xb[..., -1] |= np.uint32((0xFFFFFFFF << (Cin % 32)) & 0xFFFFFFFF)    # poisoned channel pad bits
+    got = words_to_host(bnn.conv_im2col_pack(words_to_dev(xb.reshape(-1, xb.shape[-1])).view(B, H, W, -1),
+                                             Cin, kh, kw, stride, pad))
+    assert got.shape == want.shape
+    assert (got == want).all()
+
+
+def test_conv_layers_end_to_end_small_batch():
+    """The three conv layer shapes (128@32x32, 256@16x16, 512@8x8), batch 2:
+    im2col -> XNOR GEMM -> BN+Sign against direct convolution + float BN + Sign."""
+    for layer in range(3):
+        x, Wt, bn = synth.config_conv(layer, batch=2, adversarial=(layer == 1))
+        S_want, a_want = oracle.conv_layer(x, Wt, bn, eps=EPS)
+        B, H, W, C = x.shape
+        conv = bnn.BinaryConvLayer(torch.from_numpy(Wt.astype(np.float32)).to(DEV), bn, EPS, B, H, W)
+        xb = words_to_dev(_pack_nhwc(x).reshape(-1, C // 32)).view(B, H, W, C // 32)
+        out = conv.forward(xb)
+        assert (conv.s.cpu().numpy().reshape(S_want.shape) == S_want).all()
+        assert (words_to_host(out.reshape(-1, out.shape[-1])) == oracle.pack_bits(a_want.reshape(-1, C))).all()
+
+
+def test_conv_layers_full_batch_sampled_images():
+    """Batch 256 as benchmarked; the oracle checks a sample of whole images (images are independent)."""
+    for layer in range(3):
+        x, Wt, bn = synth.config_conv(layer)
+        B, H, W, C = x.shape
+        conv = bnn.BinaryConvLayer(torch.from_numpy(Wt.astype(np.float32)).to(DEV), bn, EPS, B, H, W)
+        xb = words_to_dev(_pack_nhwc(x).reshape(-1, C // 32)).view(B, H, W, C // 32)
+        out = words_to_host(conv.forward(xb).reshape(B, H * W, -1))
+        s = conv.s.cpu().numpy().reshape(B, H, W, C)
+        for img in (0, 101, 255):
+            S_want, a_want = oracle.conv_layer(x[img:img + 1], Wt, bn, eps=EPS)
+            assert (s[img] == S_want[0]).all()
+            assert (out[img] == oracle.pack_bits(a_want.reshape(-1, C))).all()
+
+
+# ------------------------------------------------------------------ MLP chain
+
+def _mlp_on_gpu(x, weights, bns, batch):
+    wr = [torch.from_numpy(np.ascontiguousarray(w.T).astype(np.float32)).to(DEV) for w in weights]
+    net = bnn.BinaryMLP(wr, bns, EPS, batch)
+    net.forward(torch.from_numpy(x).to(DEV))
+    torch.cuda.synchronize()
+    return net
+
+
+def test_mlp_chain_every_intermediate_small_batch():
+    x, weights, bns = synth.config_mlp(batch=200, adversarial=True)
+    tr = oracle.mlp_forward(x, weights, bns, eps=EPS)
+    net = _mlp_on_gpu(x, weights, bns, 200)
+    for l in range(len(weights)):
+        assert (words_to_host(net.a_bits[l]) == oracle.pack_bits(tr["a"][l])).all(), f"a^b_{l}"
+        assert (net.s[l].cpu().numpy() == tr["s"][l]).all(), f"s_{l}"
+
+
+def test_mlp_full_batch_sampled_rows():
+    """Batch 10000 as benchmarked; samples (rows) are independent, so the oracle runs on 500 of them."""
+    x, weights, bns = synth.config_mlp()
+    net = _mlp_on_gpu(x, weights, bns, synth.MLP_BATCH)
+    rows = np.sort(np.random.default_rng(2).choice(synth.MLP_BATCH, 500, replace=False))
+    rows[0], rows[-1] = 0, synth.MLP_BATCH - 1
+    tr = oracle.mlp_forward(x[rows], weights, bns, eps=EPS)
+    for l in range(len(weights)):
+        assert (words_to_host(net.a_bits[l])[rows] == oracle.pack_bits(tr["a"][l])).all(), f"a^b_{l}"
+        assert (net.s[l].cpu().numpy()[rows] == tr["s"][l]).all(), f"s_{l}"
+
+
+# ------------------------------------------------------------------ int8 MFMA variant
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (7, 33, 31), (33, 7, 65), (128, 128, 64), (130, 200, 1000),
+                                   (1000, 1000, 4097), (64, 1024, 1024), (513, 129, 96)])
+def test_gemm_i8_mfma_matches_oracle(M, N, K):
+    rng = np.random.default_rng(M * 31 + N * 7 + K)
+    A, Bm = synth.pm1(rng, (M, K)), synth.pm1(rng, (K, N))
+    want = oracle.matmul_pm1(A, Bm)
+    ld = (K + 15) // 16 * 16
+    a = torch.full((M, ld), 77, dtype=torch.int8, device=DEV)       # junk in the row padding
+    b = torch.full((N, ld), 77, dtype=torch.int8, device=DEV)
+    a[:, :K] = torch.from_numpy(A).to(DEV)
+    b[:, :K] = torch.from_numpy(np.ascontiguousarray(Bm.T)).to(DEV)
+    got = bnn.gemm_i8_mfma(a[:, :K], b[:, :K]).cpu().numpy()
+    assert (got == want).all()
+
+
+def test_unpack_i8_then_mfma_equals_xnor_path():
+    rng = np.random.default_rng(11)
+    M, N, K = 300, 260, 1000
+    A, Bm = synth.pm1(rng, (M, K)), synth.pm1(rng, (K, N))
+    pa = words_to_dev(poison_pad_bits(oracle.pack_bits(A), K))
+    pb = words_to_dev(poison_pad_bits(oracle.pack_bits(np.ascontiguousarray(Bm.T)), K))
+    a8, b8 = bnn.unpack_i8(pa, K), bnn.unpack_i8(pb, K)
+    assert (a8.cpu().numpy() == A).all()
+    assert (b8.cpu().numpy() == Bm.T).all()
+    assert (bnn.gemm_i8_mfma(a8, b8).cpu().numpy() == oracle.matmul_pm1(A, Bm)).all()
+
+
+def test_gemm_i8_mfma_large_square_sampled():
+    n = synth.GEMM_LARGE
+    A, Bm = synth.config_gemm_square(n)
+    a = torch.from_numpy(A).to(DEV)
+    b = torch.from_numpy(np.ascontiguousarray(Bm.T)).to(DEV)
+    C = bnn.gemm_i8_mfma(a, b).cpu().numpy()
+    rows = np.random.default_rng(3).choice(n, 128, replace=False)
+    assert (C[rows] == oracle.matmul_pm1(A[rows], Bm)).all()
+    H = torch.from_numpy(synth.hadamard(n)).to(DEV)
+    assert torch.equal(bnn.gemm_i8_mfma(H, H), n * torch.eye(n, dtype=torch.int32, device=DEV))
