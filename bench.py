@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the binarized forward hot path on one MI355X.
+
+One step = one forward pass of the fully binarized MNIST-shaped MLP
+(784 -> 4096 -> 4096 -> 4096 -> 10, batch 10000) through the library:
+Sign+pack of the real input, four XNOR-popcount GEMMs, three BatchNorm+Sign
+epilogues.  Inputs, weights and thresholds are resident in HBM before the timed
+region; the value is images/s.  The same run also reports, outside the timed
+region, the 8192^3 binary GEMM (XNOR kernel and int8-MFMA variant) in binary
+TOP/s (2*M*N*K per second), the streaming kernels in GB/s, the conv layers,
+and the CPU oracle timed on the host cores on a bounded sample.
+
+Prints exactly one JSON line on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# Peak 32-bit integer vector-ALU rate: 256 compute units x 64 lanes x 2.4 GHz
+# lane-operations per second.  One 32-bit word of K per output costs two lane
+# operations (xor, popcount-accumulate) and is 64 binary operations in the
+# 2*M*N*K count, so the ceiling of the XNOR kernel is 32 x the lane-op rate.
+PEAK_LANE_OPS = 256 * 64 * 2.4e9
+PEAK_BINARY_TOPS = PEAK_LANE_OPS / 2 * 64 / 1e12          # ~1258.3
+PEAK_HBM_GBS = 8000.0
+PEAK_I8_MFMA_TOPS = 5000.0                                # dense int8, 2*M*N*K counting
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_launches(fn, iters, warmup=2):
+    """Average duration in ms of fn() measured with events on the current stream."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    evs = []
+    for _ in range(iters):
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        fn()
+        e.record()
+        evs.append((s, e))
+    torch.cuda.synchronize()
+    t = [s.elapsed_time(e) for s, e in evs]
+    return float(np.mean(t)), float(np.min(t))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--skip-extras", action="store_true", help="only the timed MLP region and the CPU baseline")
+    ap.add_argument("--cpu-sample", type=int, default=2500, help="images the CPU oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+        sys.exit(2)
+
+    import torch
+
+    import paper_1602_02830_amd as bnn
+    from workloads import synth
+
+    bnn.load_library()                      # raises if the HIP library is not built
+    if not torch.cuda.is_available():
+        raise RuntimeError("bench.py needs a GPU; there is no CPU fallback")
+    dev = "cuda:0"
+    eps = 1e-4
+
+    # ---------------- workload: MNIST-shaped MLP, batch 10000, synthetic -------------
+    x, weights, bns = synth.config_mlp()
+    batch = x.shape[0]
+    wr = [torch.from_numpy(np.ascontiguousarray(w.T).astype(np.float32)).to(dev) for w in weights]
+    net = bnn.BinaryMLP(wr, bns, eps, batch)
+    del wr
+    xd = torch.from_numpy(x).to(dev)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        net.forward(xd)
+    torch.cuda.synchronize()
+    dominant_layers = [1, 2]                # the two 4096 x 4096 layers: same kernel, same shape
+    events = {l: [] for l in dominant_layers}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        net.forward(xd, gemm_events=events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    images_per_s = batch / (ms_per_step * 1e-3)
+    gemm_ms = float(np.mean([s.elapsed_time(e) for l in dominant_layers for s, e in events[l]]))
+    M, N, K = batch, 4096, 4096
+    ops_per_launch = 2.0 * M * N * K
+    achieved_tops = ops_per_launch / (gemm_ms * 1e-3) / 1e12
+    log(f"MLP step {ms_per_step:.3f} ms  {images_per_s:,.0f} images/s; 4096-layer GEMM {gemm_ms:.3f} ms "
+        f"= {achieved_tops:.1f} binary TOP/s")
+    scores = net.s[-1].cpu().numpy()
+
+    result = {
+        "metric": "images/s, 3x4096 BNN MLP forward (784-4096-4096-4096-10), batch 10000",
+        "value": images_per_s,
+        "unit": "images/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+        "config": {"workload": "mlp_784-4096x3-10_batch10000", "batch": batch,
+                   "kernels": "pack_sign + 4 x xnor_gemm + 3 x bn_sign_pack"},
+        "roofline": {
+            "bound": "alu",
+            "kernel": "xnor_gemm_tiled_kernel<8,8,16> M=10000 N=4096 K=4096",
+            "achieved": achieved_tops,
+            "peak": PEAK_BINARY_TOPS,
+            "unit": "binary TOP/s (2*M*N*K/s; peak = 256 CU x 64 lanes x 2.4 GHz / 2 lane-ops per word x 64)",
+            "frac": achieved_tops / PEAK_BINARY_TOPS,
+            "avg_launch_ms": gemm_ms,
+            "traffic": None,
+        },
+    }
+
+    # ---------------- CPU oracle on the host cores, bounded sample --------------------
+    import oracle
+    n_cpu = min(args.cpu_sample, batch)
+    rows = np.arange(n_cpu)
+    c0 = time.perf_counter()
+    tr = oracle.mlp_forward(x[rows], weights, bns, eps=eps)
+    c1 = time.perf_counter()
+    parity = bool((tr["s"][-1] == scores[rows]).all())
+    result["cpu_baseline"] = {
+        "value": n_cpu / (c1 - c0),
+        "unit": "images/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": f"first {n_cpu} of the {batch} images, whole MLP forward, {c1 - c0:.2f} s wall",
+        "scores_equal_gpu": parity,
+    }
+    log(f"oracle: {n_cpu} images in {c1 - c0:.2f} s on {oracle.num_threads()} threads; scores equal GPU: {parity}")
+    if not parity:
+        raise RuntimeError("GPU scores differ from the oracle")
+
+    # ---------------- extras, outside the timed region --------------------------------
+    if not args.skip_extras:
+        del net
+        extras = {}
+        n = synth.GEMM_LARGE
+        rng = np.random.default_rng(synth.seed_for(4, 0))
+        a_f = torch.from_numpy(rng.standard_normal((n, n), dtype=np.float32)).to(dev)
+        b_f = torch.from_numpy(rng.standard_normal((n, n), dtype=np.float32)).to(dev)
+        a_bits, b_bits = bnn.pack_sign(a_f), bnn.pack_sign(b_f)
+        c = torch.empty((n, n), dtype=torch.int32, device=dev)
+        ops = 2.0 * n * n * n
+        ms, ms_min = time_launches(lambda: bnn.xnor_gemm(a_bits, b_bits, n, out=c), 20)
+        extras["xnor_gemm_8192"] = {"ms": ms, "ms_min": ms_min, "binary_tops": ops / ms / 1e9,
+                                    "frac_of_valu_peak": ops / ms / 1e9 / PEAK_BINARY_TOPS}
+        log(f"xnor_gemm 8192^3: {ms:.3f} ms = {ops / ms / 1e9:.1f} binary TOP/s "
+            f"({ops / ms / 1e9 / PEAK_BINARY_TOPS:.1%} of VALU peak)")
+        a8, b8 = bnn.unpack_i8(a_bits, n), bnn.unpack_i8(b_bits, n)
+        c2 = torch.empty((n, n), dtype=torch.int32, device=dev)
+        ms, ms_min = time_launches(lambda: bnn.gemm_i8_mfma(a8, b8, out=c2), 20)
+        extras["gemm_i8_mfma_8192"] = {"ms": ms, "ms_min": ms_min, "binary_tops": ops / ms / 1e9,
+                                       "frac_of_i8_mfma_peak": ops / ms / 1e9 / PEAK_I8_MFMA_TOPS,
+                                       "equal_to_xnor": bool(torch.equal(c, c2))}
+        log(f"gemm_i8_mfma 8192^3: {ms:.3f} ms = {ops / ms / 1e9:.1f} TOP/s; equal to xnor result: "
+            f"{extras['gemm_i8_mfma_8192']['equal_to_xnor']}")
+        del a8, b8, c2
+        ms, _ = time_launches(lambda: bnn.pack_sign(a_f, out=a_bits), 20)
+        bytes_ = n * n * 4 + n * n / 8
+        extras["pack_sign_8192x8192"] = {"ms": ms, "GBps": bytes_ / ms / 1e6, "frac_of_hbm_peak": bytes_ / ms / 1e6 / PEAK_HBM_GBS}
+        log(f"pack_sign 8192x8192: {ms:.3f} ms = {bytes_ / ms / 1e6:.0f} GB/s")
+        thr = torch.zeros(n, dtype=torch.int32, device=dev)
+        flip = torch.zeros(n // 32, dtype=torch.int32, device=dev)
+        ms, _ = time_launches(lambda: bnn.bn_sign_pack(c, thr, flip, out=a_bits), 20)
+        extras["bn_sign_pack_8192x8192"] = {"ms": ms, "GBps": bytes_ / ms / 1e6, "frac_of_hbm_peak": bytes_ / ms / 1e6 / PEAK_HBM_GBS}
+        log(f"bn_sign_pack 8192x8192: {ms:.3f} ms = {bytes_ / ms / 1e6:.0f} GB/s")
+        del a_f, b_f, c, a_bits, b_bits
+
+        conv = {}
+        for layer, (ch, hw) in enumerate(synth.CONV_LAYERS):
+            xc, Wt, bn = synth.config_conv(layer)
+            B = xc.shape[0]
+            cl = bnn.BinaryConvLayer(torch.from_numpy(Wt.astype(np.float32)).to(dev), bn, eps, B, hw, hw)
+            xb = bnn.pack_sign(torch.from_numpy(xc.reshape(-1, ch).astype(np.float32)).to(dev)).view(B, hw, hw, ch // 32)
+            ms, _ = time_launches(lambda: cl.forward(xb), 20)
+            ms_i, _ = time_launches(lambda: bnn.conv_im2col_pack(xb, ch, out=cl.cols), 20)
+            ms_g, _ = time_launches(lambda: bnn.xnor_gemm(cl.cols, cl.w_bits, cl.K, out=cl.s), 20)
+            wbytes = cl.M * cl.K / 8
+            conv[f"{ch}ch_{hw}x{hw}"] = {
+                "layer_ms": ms, "images_per_s": B / ms * 1e3, "im2col_ms": ms_i,
+                "im2col_write_GBps": wbytes / ms_i / 1e6, "gemm_ms": ms_g,
+                "gemm_binary_tops": 2.0 * cl.M * cl.K * cl.Cout / ms_g / 1e9}
+            log(f"conv {ch}ch {hw}x{hw} batch {B}: layer {ms:.3f} ms, im2col {ms_i:.3f} ms, gemm {ms_g:.3f} ms "
+                f"({conv[f'{ch}ch_{hw}x{hw}']['gemm_binary_tops']:.0f} TOP/s)")
+            del cl, xb
+        extras["conv_layers_batch256"] = conv
+        result["extras"] = extras
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -64,12 +64,23 @@ class BinaryMLP:
             self.s = [scratch[:, :n] if n != scratch.shape[1] else scratch for n in self.N[:-1]]
             self.s.append(torch.empty((batch, self.N[-1]), dtype=torch.int32, device=dev))
 
-    def forward(self, x: torch.Tensor) -> torch.Tensor:
-        """x: float32 device tensor [batch][K_0].  Returns the int32 scores [batch][N_last]."""
+    def forward(self, x: torch.Tensor, gemm_events=None) -> torch.Tensor:
+        """x: float32 device tensor [batch][K_0].  Returns the int32 scores [batch][N_last].
+
+        gemm_events: optional dict layer -> list; for those layers a (start, end) pair of
+        events is recorded on the current stream around the GEMM launch and appended.
+        """
         B.pack_sign(x, out=self.a_bits[0])
         n_layers = len(self.w_bits)
         for l in range(n_layers):
+            timed = gemm_events is not None and l in gemm_events
+            if timed:
+                start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                start.record()
             B.xnor_gemm(self.a_bits[l], self.w_bits[l], self.K[l], out=self.s[l])
+            if timed:
+                end.record()
+                gemm_events[l].append((start, end))
             if l + 1 < n_layers:
                 B.bn_sign_pack(self.s[l], self.thr[l], self.flip[l], out=self.a_bits[l + 1])
         return self.s[-1]
