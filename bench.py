@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--skip-extras", action="store_true", help="only the timed MLP region and the CPU baseline")
     ap.add_argument("--cpu-sample", type=int, default=2500, help="images the CPU oracle is timed on")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (known traffic, for scaling profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -135,6 +137,14 @@ def main():
             "traffic": None,
         },
     }
+
+    if args.calibration_copy:
+        src = torch.zeros(256 * 1024 * 1024, dtype=torch.int32, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---------------- CPU oracle on the host cores, bounded sample --------------------
     import oracle
