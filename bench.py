@@ -62,6 +62,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--unfused", action="store_true",
+                    help="hidden layers as separate GEMM and BN+Sign launches (int32 pre-activations through HBM)")
     ap.add_argument("--skip-extras", action="store_true", help="only the timed MLP region and the CPU baseline")
     ap.add_argument("--cpu-sample", type=int, default=2500, help="images the CPU oracle is timed on")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -86,7 +88,8 @@ def main():
     x, weights, bns = synth.config_mlp()
     batch = x.shape[0]
     wr = [torch.from_numpy(np.ascontiguousarray(w.T).astype(np.float32)).to(dev) for w in weights]
-    net = bnn.BinaryMLP(wr, bns, eps, batch)
+    fused = not args.unfused
+    net = bnn.BinaryMLP(wr, bns, eps, batch, fused=fused)
     del wr
     xd = torch.from_numpy(x).to(dev)
     torch.cuda.synchronize()
@@ -125,10 +128,12 @@ def main():
         "dtype": "u32",
         "data": "synthetic",
         "config": {"workload": "mlp_784-4096x3-10_batch10000", "batch": batch,
-                   "kernels": "pack_sign + 4 x xnor_gemm + 3 x bn_sign_pack"},
+                   "kernels": ("pack_sign + 3 x xnor_gemm_bn_sign_pack + xnor_gemm" if fused else
+                               "pack_sign + 4 x xnor_gemm + 3 x bn_sign_pack")},
         "roofline": {
             "bound": "alu",
-            "kernel": "xnor_gemm_tiled_kernel<8,8,16> M=10000 N=4096 K=4096",
+            "kernel": ("xnor_gemm_tiled_kernel<8,8,16,fused BN+Sign epilogue>" if fused else
+                       "xnor_gemm_tiled_kernel<8,8,16>") + " M=10000 N=4096 K=4096",
             "achieved": achieved_tops,
             "peak": PEAK_BINARY_TOPS,
             "unit": "binary TOP/s (2*M*N*K/s; peak = 256 CU x 64 lanes x 2.4 GHz / 2 lane-ops per word x 64)",

@@ -128,6 +128,24 @@ int bnn_bn_sign_pack(const int32_t *C, int64_t ldc, int64_t M, int64_t N,
                      int64_t ld_out, void *stream);
 
 /*
+ * One hidden layer of Alg. 4 in a single launch:
+ *     a_k   = XnorDotProduct(a^b_{k-1}, W^b_k)
+ *     a^b_k = Sign(BatchNorm(a_k, theta_k))
+ * i.e. bnn_xnor_gemm followed by bnn_bn_sign_pack with the int32
+ * pre-activations kept in registers (they never reach memory):
+ *   out[m][n/32] bit (n%32) = (C[m][n] >= thr[n]) XOR flip[n],
+ *   C[m][n] = K - 2 * sum_w popcount(A[m][w] ^ B[n][w]).
+ * Arguments as in those two calls (A [M][lda], B [N][ldb] packed rows of K bits;
+ * thr [N], flip_bits [ceil(N/32)] device arrays from bnn_bn_fold;
+ * out [M][ld_out], ld_out >= ceil(N/32), pad bits 0, words beyond untouched).
+ * The result is bit-identical to the two-call sequence.
+ */
+int bnn_xnor_gemm_bn_sign_pack(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb,
+                               int64_t M, int64_t N, int64_t K, const int32_t *thr,
+                               const uint32_t *flip_bits, uint32_t *out, int64_t ld_out,
+                               void *stream);
+
+/*
  * Lowers a binary kh x kw convolution (3 x 3 in the paper's nets, Sec. 3.3) to
  * the matrix product above: row m = (b*Ho + oy)*Wo + ox of `out` holds the
  * receptive field of output pixel (b, oy, ox) as K = kh*kw*Cin bits,

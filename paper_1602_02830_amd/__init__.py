@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     xnor_gemm,
     bn_fold,
     bn_sign_pack,
+    xnor_gemm_bn_sign_pack,
     conv_im2col_pack,
     gemm_i8_mfma,
     unpack_i8,

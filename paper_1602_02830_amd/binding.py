@@ -30,6 +30,7 @@ _SIGNATURES = {
     "bnn_pack_sign": (_int, [_ptr, _i64, _i64, _i64, _ptr, _i64, _ptr]),
     "bnn_xnor_gemm": (_int, [_ptr, _i64, _ptr, _i64, _ptr, _i64, _i64, _i64, _i64, _ptr]),
     "bnn_xnor_gemm_kernel": (_int, [_ptr, _i64, _ptr, _i64, _ptr, _i64, _i64, _i64, _i64, _int, _ptr]),
+    "bnn_xnor_gemm_bn_sign_pack": (_int, [_ptr, _i64, _ptr, _i64, _i64, _i64, _i64, _ptr, _ptr, _ptr, _i64, _ptr]),
     "bnn_bn_fold": (_int, [_ptr, _ptr, _ptr, _ptr, _f32, _i64, _i64, _ptr, _ptr]),
     "bnn_bn_sign_pack": (_int, [_ptr, _i64, _i64, _i64, _ptr, _ptr, _ptr, _i64, _ptr]),
     "bnn_conv_im2col_pack": (_int, [_ptr, _i64, _i64, _i64, _i64, _int, _int, _int, _int, _ptr, _i64, _ptr]),
@@ -181,6 +182,30 @@ def bn_sign_pack(C: torch.Tensor, thr: torch.Tensor, flip_bits: torch.Tensor,
     _dev(out, torch.int32, "out")
     _check("bnn_bn_sign_pack", lib.bnn_bn_sign_pack(C.data_ptr(), _ld(C), M, N, thr.data_ptr(),
                                                    flip_bits.data_ptr(), out.data_ptr(), _ld(out), _stream()))
+    return out
+
+
+def xnor_gemm_bn_sign_pack(A: torch.Tensor, B: torch.Tensor, K: int, thr: torch.Tensor, flip_bits: torch.Tensor,
+                           out: torch.Tensor | None = None, ld_out: int | None = None) -> torch.Tensor:
+    """bnn_xnor_gemm_bn_sign_pack: packed A [M][Kw], packed B [N][Kw], thresholds -> packed bits [M][ceil(N/32)]."""
+    lib = load_library()
+    _dev(A, torch.int32, "A")
+    _dev(B, torch.int32, "B")
+    M, N = A.shape[0], B.shape[0]
+    kw = words_per_row(K)
+    nw = words_per_row(N)
+    if A.shape[1] < kw or B.shape[1] < kw:
+        raise ValueError("packed operands have fewer words per row than K needs")
+    if thr.dtype != torch.int32 or flip_bits.dtype != torch.int32 or not thr.is_cuda or not flip_bits.is_cuda:
+        raise ValueError("thr and flip_bits must be int32 device tensors")
+    if thr.numel() != N or flip_bits.numel() != nw or not thr.is_contiguous() or not flip_bits.is_contiguous():
+        raise ValueError("thr must be [N] and flip_bits [ceil(N/32)], contiguous")
+    if out is None:
+        out = _alloc_words(M, nw, A.device, ld_out)
+    _dev(out, torch.int32, "out")
+    _check("bnn_xnor_gemm_bn_sign_pack",
+           lib.bnn_xnor_gemm_bn_sign_pack(A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), M, N, K, thr.data_ptr(),
+                                          flip_bits.data_ptr(), out.data_ptr(), _ld(out), _stream()))
     return out
 
 

@@ -113,10 +113,19 @@ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, int& tm,
     tm = band * kBand + (in_band - tn * rows_in_band);
 }
 
-template <int TM, int TN, int KT, bool VEC>
+// Arguments of the fused epilogue (Alg. 4: a^b_k = Sign(BatchNorm(a_k, theta_k)) on folded
+// thresholds), used when FUSED: the tile's pre-activations never leave registers.
+struct BnSignArgs {
+    const int32_t* thr;        // [N]
+    const uint32_t* flip_bits; // [ceil(N/32)]
+    uint32_t* out;             // [M][ld_out] packed bits
+    int64_t ld_out;
+};
+
+template <int TM, int TN, int KT, bool VEC, bool FUSED>
 __global__ __launch_bounds__(256) void xnor_gemm_tiled_kernel(
     const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B, int64_t ldb,
-    int32_t* __restrict__ C, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n) {
+    int32_t* __restrict__ C, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n, BnSignArgs bn) {
     using Cfg = TileCfg<TM, TN, KT>;
     __shared__ uint4 lds_a[2][Cfg::SLOTS_A];
     __shared__ uint4 lds_b[2][Cfg::SLOTS_B];
@@ -195,16 +204,50 @@ __global__ __launch_bounds__(256) void xnor_gemm_tiled_kernel(
         __syncthreads();
     }
 
+    if (!FUSED) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int m = row0 + ty + 16 * i;
-        if (m < M) {
-            int32_t* crow = C + int64_t(m) * ldc;
+        for (int i = 0; i < TM; ++i) {
+            const int m = row0 + ty + 16 * i;
+            if (m < M) {
+                int32_t* crow = C + int64_t(m) * ldc;
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int n = col0 + tx + 16 * j;
-                if (n < N) crow[n] = K - 2 * int(acc[i][j]);
+                for (int j = 0; j < TN; ++j) {
+                    const int n = col0 + tx + 16 * j;
+                    if (n < N) crow[n] = K - 2 * int(acc[i][j]);
+                }
             }
+        }
+    } else {
+        // bit(m, n) = (K - 2*acc >= thr[n]) XOR flip[n].  Column tx + 16*j of this lane is bit
+        // (tx + 16*(j&1)) of word j/2 of the tile row, so a wavefront ballot over column slot j
+        // holds, in its 16-bit field q, the half word of tile row 4*wave + q + 16*i.
+        static_assert(TN % 2 == 0, "a tile row must be whole 32-bit words");
+        int thr[TN];
+        bool flip[TN], live[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = col0 + tx + 16 * j;
+            live[j] = n < N;
+            thr[j] = live[j] ? bn.thr[n] : 0;
+            flip[j] = live[j] ? ((bn.flip_bits[n >> 5] >> (n & 31)) & 1u) != 0u : false;
+        }
+        const int q = (tid >> 4) & 3;                  // row group of this lane inside its wavefront
+        const int64_t nw = (int64_t(N) + 31) >> 5;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            uint32_t mine = 0u;                        // word kept by the lane with tx == word index
+#pragma unroll
+            for (int jh = 0; jh < TN / 2; ++jh) {
+                const bool p0 = live[2 * jh] && ((K - 2 * int(acc[i][2 * jh]) >= thr[2 * jh]) != flip[2 * jh]);
+                const bool p1 = live[2 * jh + 1] &&
+                                ((K - 2 * int(acc[i][2 * jh + 1]) >= thr[2 * jh + 1]) != flip[2 * jh + 1]);
+                const uint64_t m0 = __ballot(p0), m1 = __ballot(p1);
+                const uint32_t word = uint32_t((m0 >> (16 * q)) & 0xFFFFu) | (uint32_t((m1 >> (16 * q)) & 0xFFFFu) << 16);
+                if (tx == jh) mine = word;
+            }
+            const int m = row0 + ty + 16 * i;
+            const int64_t w = int64_t(tile_n) * (TN / 2) + tx;
+            if (tx < TN / 2 && m < M && w < nw) bn.out[int64_t(m) * bn.ld_out + w] = mine;
         }
     }
 }
@@ -260,20 +303,20 @@ __global__ __launch_bounds__(256) void xnor_gemm_ksplit_kernel(
 // ----------------------------------------------------------------------------
 enum { KERNEL_AUTO = 0, KERNEL_NAIVE = 1, KERNEL_TILED128 = 2, KERNEL_KSPLIT = 3, KERNEL_TILED64 = 4 };
 
-template <int TM, int TN, int KT>
+template <int TM, int TN, int KT, bool FUSED>
 static void launch_tiled(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
-                         int64_t ldc, int M, int N, int K, hipStream_t s) {
+                         int64_t ldc, int M, int N, int K, BnSignArgs bn, hipStream_t s) {
     using Cfg = TileCfg<TM, TN, KT>;
     const int tiles_m = int(ceil_div(M, Cfg::BM));
     const int tiles_n = int(ceil_div(N, Cfg::BN));
     const bool vec = aligned_to(A, 16) && aligned_to(B, 16) && lda % 4 == 0 && ldb % 4 == 0;
     const dim3 grid(unsigned(int64_t(tiles_m) * tiles_n));
     if (vec)
-        hipLaunchKernelGGL((xnor_gemm_tiled_kernel<TM, TN, KT, true>), grid, dim3(256), 0, s, A, lda, B,
-                           ldb, C, ldc, M, N, K, tiles_m, tiles_n);
+        hipLaunchKernelGGL((xnor_gemm_tiled_kernel<TM, TN, KT, true, FUSED>), grid, dim3(256), 0, s, A, lda,
+                           B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, bn);
     else
-        hipLaunchKernelGGL((xnor_gemm_tiled_kernel<TM, TN, KT, false>), grid, dim3(256), 0, s, A, lda, B,
-                           ldb, C, ldc, M, N, K, tiles_m, tiles_n);
+        hipLaunchKernelGGL((xnor_gemm_tiled_kernel<TM, TN, KT, false, FUSED>), grid, dim3(256), 0, s, A, lda,
+                           B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, bn);
 }
 
 static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
@@ -311,10 +354,10 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
             break;
         }
         case KERNEL_TILED128:
-            launch_tiled<8, 8, 16>(A, lda, B, ldb, C, ldc, m, n, k, s);
+            launch_tiled<8, 8, 16, false>(A, lda, B, ldb, C, ldc, m, n, k, BnSignArgs{}, s);
             break;
         case KERNEL_TILED64:
-            launch_tiled<4, 4, 16>(A, lda, B, ldb, C, ldc, m, n, k, s);
+            launch_tiled<4, 4, 16, false>(A, lda, B, ldb, C, ldc, m, n, k, BnSignArgs{}, s);
             break;
         case KERNEL_KSPLIT: {
             constexpr int RS = 2, CS = 4;
@@ -331,7 +374,37 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
     return check_launch();
 }
 
+static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb,
+                                           int64_t M, int64_t N, int64_t K, const int32_t* thr,
+                                           const uint32_t* flip_bits, uint32_t* out, int64_t ld_out,
+                                           void* stream) {
+    if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return BNN_ERR_INVALID_ARG;
+    const int64_t kw = ceil_div(K, 32);
+    if (lda < kw || ldb < kw || ld_out < ceil_div(N, 32)) return BNN_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return BNN_OK;
+    if (!thr || !flip_bits || !out || (K > 0 && (!A || !B))) return BNN_ERR_INVALID_ARG;
+    if (!aligned_to(A, 4) || !aligned_to(B, 4) || !aligned_to(thr, 4) || !aligned_to(flip_bits, 4) ||
+        !aligned_to(out, 4))
+        return BNN_ERR_ALIGNMENT;
+    if (ceil_div(M, 16) * ceil_div(N, 16) > kMaxDim) return BNN_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const BnSignArgs bn{thr, flip_bits, out, ld_out};
+    const int64_t tiles128 = ceil_div(M, 128) * ceil_div(N, 128);
+    if (tiles128 >= 512)
+        launch_tiled<8, 8, 16, true>(A, lda, B, ldb, nullptr, 0, int(M), int(N), int(K), bn, s);
+    else
+        launch_tiled<4, 4, 16, true>(A, lda, B, ldb, nullptr, 0, int(M), int(N), int(K), bn, s);
+    return check_launch();
+}
+
 }  // namespace bnn
+
+extern "C" int bnn_xnor_gemm_bn_sign_pack(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb,
+                                          int64_t M, int64_t N, int64_t K, const int32_t* thr,
+                                          const uint32_t* flip_bits, uint32_t* out, int64_t ld_out,
+                                          void* stream) {
+    return bnn::xnor_gemm_bn_sign_pack_dispatch(A, lda, B, ldb, M, N, K, thr, flip_bits, out, ld_out, stream);
+}
 
 extern "C" int bnn_xnor_gemm(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
                              int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream) {

@@ -34,11 +34,13 @@ class BinaryMLP:
     bns: per hidden layer (gamma, beta, mean, var) as numpy float32 [N_l]; folded once on the host.
     """
 
-    def __init__(self, weights_real, bns, eps: float, batch: int, keep_preacts: bool = True):
+    def __init__(self, weights_real, bns, eps: float, batch: int, keep_preacts: bool = True,
+                 fused: bool = False):
         assert len(bns) == len(weights_real) - 1
         dev = weights_real[0].device
         self.device = dev
         self.batch = batch
+        self.fused = fused          # hidden layers as one launch each; their int32 pre-activations are not produced
         self.K = [int(w.shape[1]) for w in weights_real]
         self.N = [int(w.shape[0]) for w in weights_real]
         self.w_bits = []
@@ -56,7 +58,10 @@ class BinaryMLP:
         for l in range(len(bns)):
             self.a_bits.append(_packed_buffer(batch, self.N[l], dev))
         self.keep_preacts = keep_preacts
-        if keep_preacts:
+        if fused:
+            self.s = [None] * (len(weights_real) - 1)
+            self.s.append(torch.empty((batch, self.N[-1]), dtype=torch.int32, device=dev))
+        elif keep_preacts:
             self.s = [torch.empty((batch, n), dtype=torch.int32, device=dev) for n in self.N]
         else:
             # One scratch buffer reused by every hidden layer, plus the score buffer.
@@ -77,11 +82,16 @@ class BinaryMLP:
             if timed:
                 start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 start.record()
-            B.xnor_gemm(self.a_bits[l], self.w_bits[l], self.K[l], out=self.s[l])
+            hidden = l + 1 < n_layers
+            if self.fused and hidden:
+                B.xnor_gemm_bn_sign_pack(self.a_bits[l], self.w_bits[l], self.K[l], self.thr[l], self.flip[l],
+                                         out=self.a_bits[l + 1])
+            else:
+                B.xnor_gemm(self.a_bits[l], self.w_bits[l], self.K[l], out=self.s[l])
             if timed:
                 end.record()
                 gemm_events[l].append((start, end))
-            if l + 1 < n_layers:
+            if hidden and not self.fused:
                 B.bn_sign_pack(self.s[l], self.thr[l], self.flip[l], out=self.a_bits[l + 1])
         return self.s[-1]
 

@@ -237,6 +237,44 @@ def test_bn_sign_pack_strided_unaligned_and_canary():
     assert (host[:, nw:] == 0x0BADBEEF).all()
 
 
+# ------------------------------------------------------------------ fused GEMM + BN + Sign
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (7, 33, 31), (33, 7, 65), (64, 1024, 1024), (130, 200, 1000),
+                                   (1000, 1000, 4097), (300, 4096, 784), (2000, 4096, 4096), (129, 95, 96)])
+def test_fused_layer_matches_float_bn_then_sign(M, N, K):
+    """Alg. 4 hidden layer in one launch == oracle product, float BatchNorm, Sign, pack."""
+    rng = np.random.default_rng(M * 3 + N * 5 + K * 7)
+    A, Bm = synth.pm1(rng, (M, K)), synth.pm1(rng, (K, N))
+    bn = synth.bn_params(rng, N, K, adversarial=True)
+    _s, a_next = oracle.dense_layer(A, Bm, bn, eps=EPS)
+    want = oracle.pack_bits(a_next)
+    thr, flip = _fold_to_dev(bn, K)
+    pa = words_to_dev(poison_pad_bits(oracle.pack_bits(A), K))
+    pb = words_to_dev(poison_pad_bits(oracle.pack_bits(np.ascontiguousarray(Bm.T)), K))
+    nw = (N + 31) // 32
+    out = torch.full((M, nw + 1), 0x0BADF00D, dtype=torch.int32, device=DEV)
+    bnn.xnor_gemm_bn_sign_pack(pa, pb, K, thr, flip, out=out[:, :nw])
+    host = words_to_host(out)
+    assert (host[:, :nw] == want).all()
+    assert (host[:, nw:] == 0x0BADF00D).all()
+    # and bit-identical to the two-call sequence
+    two = bnn.bn_sign_pack(bnn.xnor_gemm(pa, pb, K), thr, flip)
+    assert torch.equal(two, out[:, :nw])
+
+
+def test_fused_mlp_full_batch_sampled_rows():
+    x, weights, bns = synth.config_mlp(adversarial=True)
+    wr = [torch.from_numpy(np.ascontiguousarray(w.T).astype(np.float32)).to(DEV) for w in weights]
+    net = bnn.BinaryMLP(wr, bns, EPS, synth.MLP_BATCH, fused=True)
+    scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
+    rows = np.sort(np.random.default_rng(4).choice(synth.MLP_BATCH, 400, replace=False))
+    rows[0], rows[-1] = 0, synth.MLP_BATCH - 1
+    tr = oracle.mlp_forward(x[rows], weights, bns, eps=EPS)
+    for l in range(len(weights)):
+        assert (words_to_host(net.a_bits[l])[rows] == oracle.pack_bits(tr["a"][l])).all(), f"a^b_{l}"
+    assert (scores[rows] == tr["s"][-1]).all()
+
+
 # ------------------------------------------------------------------ conv_im2col_pack
 
 def _pack_nhwc(x: np.ndarray) -> np.ndarray:
