@@ -87,9 +87,11 @@ int bnn_xnor_gemm(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb
 
 /* Same contract, with the kernel chosen by the caller (for tests and
  * profiling): 0 = automatic (what bnn_xnor_gemm does), 1 = one thread per
- * output, 2 = 128x128 LDS-tiled register-blocked kernel, 3 = K-split kernel
- * with wavefront reduction (skinny outputs), 4 = 64x64 tiled kernel.
- * Unknown ids give BNN_ERR_INVALID_ARG. */
+ * output, 2 = 128x128 LDS-tiled register-blocked XNOR-popcount kernel,
+ * 3 = K-split kernel with wavefront reduction (skinny outputs), 4 = 64x64
+ * tiled XNOR-popcount kernel, 5 = bits-in / matrix-engine-inside kernel (bits
+ * widened to 4-bit floats in registers, MFMA; needs K <= 2^24, else
+ * BNN_ERR_UNSUPPORTED).  Unknown ids give BNN_ERR_INVALID_ARG. */
 int bnn_xnor_gemm_kernel(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb,
                          int32_t *C, int64_t ldc, int64_t M, int64_t N, int64_t K,
                          int kernel_id, void *stream);
@@ -144,6 +146,13 @@ int bnn_xnor_gemm_bn_sign_pack(const uint32_t *A, int64_t lda, const uint32_t *B
                                int64_t M, int64_t N, int64_t K, const int32_t *thr,
                                const uint32_t *flip_bits, uint32_t *out, int64_t ld_out,
                                void *stream);
+
+/* Same contract with the kernel chosen by the caller: 0 = automatic, 2, 4, 5 as
+ * in bnn_xnor_gemm_kernel (the other kernels have no fused form). */
+int bnn_xnor_gemm_bn_sign_pack_kernel(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb,
+                                      int64_t M, int64_t N, int64_t K, const int32_t *thr,
+                                      const uint32_t *flip_bits, uint32_t *out, int64_t ld_out,
+                                      int kernel_id, void *stream);
 
 /*
  * Lowers a binary kh x kw convolution (3 x 3 in the paper's nets, Sec. 3.3) to

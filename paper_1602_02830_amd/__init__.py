@@ -25,5 +25,6 @@ from .binding import (  # noqa: F401
     KERNEL_TILED128,
     KERNEL_KSPLIT,
     KERNEL_TILED64,
+    KERNEL_MFMA,
 )
 from .network import BinaryMLP, BinaryConvLayer  # noqa: F401

@@ -16,7 +16,7 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libbnn_hip.so")
 
-KERNEL_AUTO, KERNEL_NAIVE, KERNEL_TILED128, KERNEL_KSPLIT, KERNEL_TILED64 = range(5)
+KERNEL_AUTO, KERNEL_NAIVE, KERNEL_TILED128, KERNEL_KSPLIT, KERNEL_TILED64, KERNEL_MFMA = range(6)
 
 _i64 = ctypes.c_int64
 _int = ctypes.c_int
@@ -31,6 +31,8 @@ _SIGNATURES = {
     "bnn_xnor_gemm": (_int, [_ptr, _i64, _ptr, _i64, _ptr, _i64, _i64, _i64, _i64, _ptr]),
     "bnn_xnor_gemm_kernel": (_int, [_ptr, _i64, _ptr, _i64, _ptr, _i64, _i64, _i64, _i64, _int, _ptr]),
     "bnn_xnor_gemm_bn_sign_pack": (_int, [_ptr, _i64, _ptr, _i64, _i64, _i64, _i64, _ptr, _ptr, _ptr, _i64, _ptr]),
+    "bnn_xnor_gemm_bn_sign_pack_kernel": (_int, [_ptr, _i64, _ptr, _i64, _i64, _i64, _i64, _ptr, _ptr, _ptr, _i64,
+                                                 _int, _ptr]),
     "bnn_bn_fold": (_int, [_ptr, _ptr, _ptr, _ptr, _f32, _i64, _i64, _ptr, _ptr]),
     "bnn_bn_sign_pack": (_int, [_ptr, _i64, _i64, _i64, _ptr, _ptr, _ptr, _i64, _ptr]),
     "bnn_conv_im2col_pack": (_int, [_ptr, _i64, _i64, _i64, _i64, _int, _int, _int, _int, _ptr, _i64, _ptr]),
@@ -186,7 +188,8 @@ def bn_sign_pack(C: torch.Tensor, thr: torch.Tensor, flip_bits: torch.Tensor,
 
 
 def xnor_gemm_bn_sign_pack(A: torch.Tensor, B: torch.Tensor, K: int, thr: torch.Tensor, flip_bits: torch.Tensor,
-                           out: torch.Tensor | None = None, ld_out: int | None = None) -> torch.Tensor:
+                           out: torch.Tensor | None = None, ld_out: int | None = None,
+                           kernel: int = KERNEL_AUTO) -> torch.Tensor:
     """bnn_xnor_gemm_bn_sign_pack: packed A [M][Kw], packed B [N][Kw], thresholds -> packed bits [M][ceil(N/32)]."""
     lib = load_library()
     _dev(A, torch.int32, "A")
@@ -203,9 +206,14 @@ def xnor_gemm_bn_sign_pack(A: torch.Tensor, B: torch.Tensor, K: int, thr: torch.
     if out is None:
         out = _alloc_words(M, nw, A.device, ld_out)
     _dev(out, torch.int32, "out")
-    _check("bnn_xnor_gemm_bn_sign_pack",
-           lib.bnn_xnor_gemm_bn_sign_pack(A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), M, N, K, thr.data_ptr(),
-                                          flip_bits.data_ptr(), out.data_ptr(), _ld(out), _stream()))
+    if kernel == KERNEL_AUTO:
+        st = lib.bnn_xnor_gemm_bn_sign_pack(A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), M, N, K, thr.data_ptr(),
+                                            flip_bits.data_ptr(), out.data_ptr(), _ld(out), _stream())
+    else:
+        st = lib.bnn_xnor_gemm_bn_sign_pack_kernel(A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), M, N, K,
+                                                   thr.data_ptr(), flip_bits.data_ptr(), out.data_ptr(),
+                                                   _ld(out), kernel, _stream())
+    _check("bnn_xnor_gemm_bn_sign_pack", st)
     return out
 
 

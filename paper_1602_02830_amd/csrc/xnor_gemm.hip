@@ -18,6 +18,7 @@
 //             are combined with DPP / cross-lane adds.
 //   naive   - one thread per output, for tiny problems and as a cross-check.
 #include "bnn_internal.h"
+#include "gemm_staging.h"
 
 namespace bnn {
 
@@ -67,63 +68,10 @@ struct TileCfg {
     static_assert(BM * KQ % 256 == 0 && BN * KQ % 256 == 0, "tile must divide among 256 threads");
 };
 
-// Loads words [4*quad, 4*quad+4) of row `row` (quad counted from the matrix's
-// first word), zero where the row or word does not exist, pad bits masked.
-template <bool VEC>
-__device__ inline uint4 load_quad(const uint32_t* __restrict__ P, int64_t ld, int rows, int kw,
-                                  uint32_t tmask, int row, int quad) {
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    const int w0 = quad * 4;
-    if (row < rows && w0 < kw) {
-        const uint32_t* p = P + int64_t(row) * ld + w0;
-        if (VEC && w0 + 4 <= kw) {
-            v = *reinterpret_cast<const uint4*>(p);
-        } else {
-            v.x = p[0];
-            if (w0 + 1 < kw) v.y = p[1];
-            if (w0 + 2 < kw) v.z = p[2];
-            if (w0 + 3 < kw) v.w = p[3];
-        }
-        const int last = kw - 1 - w0;     // position of the row's last word inside this quad
-        if (last == 0) v.x &= tmask;
-        else if (last == 1) v.y &= tmask;
-        else if (last == 2) v.z &= tmask;
-        else if (last == 3) v.w &= tmask;
-    }
-    return v;
-}
-
-// Maps the hardware's round-robin placement of consecutive workgroups on the 8
-// accelerator dies (each with its own L2) to compact panels of tiles: die d
-// gets the contiguous range [d*per, (d+1)*per) of logical tile ids, and
-// logical ids walk the tile grid in column-major bands of 8 tile-rows, so the
-// tiles resident on one die at a time share a few A panels and B panels.
-__device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
-    const int total = tiles_m * tiles_n;
-    constexpr int kDies = 8;
-    int logical = bid;
-    const int per = total / kDies;
-    if (bid < per * kDies) logical = (bid % kDies) * per + bid / kDies;
-    constexpr int kBand = 8;
-    const int band_tiles = kBand * tiles_n;
-    const int band = logical / band_tiles;
-    const int in_band = logical - band * band_tiles;
-    const int rows_in_band = min(kBand, tiles_m - band * kBand);
-    tn = in_band / rows_in_band;
-    tm = band * kBand + (in_band - tn * rows_in_band);
-}
-
-// Arguments of the fused epilogue (Alg. 4: a^b_k = Sign(BatchNorm(a_k, theta_k)) on folded
-// thresholds), used when FUSED: the tile's pre-activations never leave registers.
-struct BnSignArgs {
-    const int32_t* thr;        // [N]
-    const uint32_t* flip_bits; // [ceil(N/32)]
-    uint32_t* out;             // [M][ld_out] packed bits
-    int64_t ld_out;
-};
-
+// Three workgroups per compute unit (3 wavefronts per SIMD) keep the vector ALU fed while
+// other wavefronts wait on LDS; the bound caps the kernel at 168 VGPRs.
 template <int TM, int TN, int KT, bool VEC, bool FUSED>
-__global__ __launch_bounds__(256) void xnor_gemm_tiled_kernel(
+__global__ __launch_bounds__(256, 3) void xnor_gemm_tiled_kernel(
     const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B, int64_t ldb,
     int32_t* __restrict__ C, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n, BnSignArgs bn) {
     using Cfg = TileCfg<TM, TN, KT>;
@@ -147,23 +95,49 @@ __global__ __launch_bounds__(256) void xnor_gemm_tiled_kernel(
     const int st_r = tid / Cfg::KQ;
     constexpr int ST_ROWS = 256 / Cfg::KQ;
 
+    // K-tiles whose every word is complete and unmasked take branch-free loads (row index
+    // clamped into the matrix, result zeroed at staging if the row does not exist); only the
+    // last, partial K-tile goes through the checked, masking loader.
+    const int n_full_ktiles = (K >> 5) / KT;
+    const uint32_t* pa[Cfg::LOADS_A];
+    const uint32_t* pb[Cfg::LOADS_B];
+    bool live_a[Cfg::LOADS_A], live_b[Cfg::LOADS_B];
+#pragma unroll
+    for (int l = 0; l < Cfg::LOADS_A; ++l) {
+        const int r = row0 + st_r + l * ST_ROWS;
+        live_a[l] = r < M;
+        pa[l] = A + int64_t(min(r, M - 1)) * lda;
+    }
+#pragma unroll
+    for (int l = 0; l < Cfg::LOADS_B; ++l) {
+        const int r = col0 + st_r + l * ST_ROWS;
+        live_b[l] = r < N;
+        pb[l] = B + int64_t(min(r, N - 1)) * ldb;
+    }
     uint4 ra[Cfg::LOADS_A], rb[Cfg::LOADS_B];
     auto fetch = [&](int kt) {
         const int quad = kt * Cfg::KQ + st_q;
+        if (kt < n_full_ktiles) {
 #pragma unroll
-        for (int l = 0; l < Cfg::LOADS_A; ++l)
-            ra[l] = load_quad<VEC>(A, lda, M, kw, tmask, row0 + st_r + l * ST_ROWS, quad);
+            for (int l = 0; l < Cfg::LOADS_A; ++l) ra[l] = load_quad_unchecked<VEC>(pa[l], quad);
 #pragma unroll
-        for (int l = 0; l < Cfg::LOADS_B; ++l)
-            rb[l] = load_quad<VEC>(B, ldb, N, kw, tmask, col0 + st_r + l * ST_ROWS, quad);
+            for (int l = 0; l < Cfg::LOADS_B; ++l) rb[l] = load_quad_unchecked<VEC>(pb[l], quad);
+        } else {
+#pragma unroll
+            for (int l = 0; l < Cfg::LOADS_A; ++l)
+                ra[l] = load_quad<VEC>(A, lda, M, kw, tmask, row0 + st_r + l * ST_ROWS, quad);
+#pragma unroll
+            for (int l = 0; l < Cfg::LOADS_B; ++l)
+                rb[l] = load_quad<VEC>(B, ldb, N, kw, tmask, col0 + st_r + l * ST_ROWS, quad);
+        }
     };
     auto stage = [&](int buf) {
 #pragma unroll
         for (int l = 0; l < Cfg::LOADS_A; ++l)
-            lds_a[buf][st_q * Cfg::PLANE_A + st_r + l * ST_ROWS] = ra[l];
+            lds_a[buf][st_q * Cfg::PLANE_A + st_r + l * ST_ROWS] = zero_unless(live_a[l], ra[l]);
 #pragma unroll
         for (int l = 0; l < Cfg::LOADS_B; ++l)
-            lds_b[buf][st_q * Cfg::PLANE_B + st_r + l * ST_ROWS] = rb[l];
+            lds_b[buf][st_q * Cfg::PLANE_B + st_r + l * ST_ROWS] = zero_unless(live_b[l], rb[l]);
     };
 
     uint32_t acc[TM][TN];
@@ -301,7 +275,15 @@ __global__ __launch_bounds__(256) void xnor_gemm_ksplit_kernel(
 // ----------------------------------------------------------------------------
 // host side
 // ----------------------------------------------------------------------------
-enum { KERNEL_AUTO = 0, KERNEL_NAIVE = 1, KERNEL_TILED128 = 2, KERNEL_KSPLIT = 3, KERNEL_TILED64 = 4 };
+enum { KERNEL_AUTO = 0, KERNEL_NAIVE = 1, KERNEL_TILED128 = 2, KERNEL_KSPLIT = 3, KERNEL_TILED64 = 4,
+       KERNEL_MFMA = 5, KERNEL_LAST = KERNEL_MFMA };
+
+// Matrix-engine variant, defined in xnor_gemm_mfma.hip.
+bool mfma_path_supports(int64_t K);
+int launch_xnor_gemm_mfma(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
+                          int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream);
+int launch_xnor_gemm_mfma_fused(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M,
+                                int64_t N, int64_t K, BnSignArgs bn, void* stream);
 
 template <int TM, int TN, int KT, bool FUSED>
 static void launch_tiled(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
@@ -323,7 +305,8 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
                               int64_t ldc, int64_t M, int64_t N, int64_t K, int kernel_id,
                               void* stream) {
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return BNN_ERR_INVALID_ARG;
-    if (kernel_id < KERNEL_AUTO || kernel_id > KERNEL_TILED64) return BNN_ERR_INVALID_ARG;
+    if (kernel_id < KERNEL_AUTO || kernel_id > KERNEL_LAST) return BNN_ERR_INVALID_ARG;
+    if (kernel_id == KERNEL_MFMA && !mfma_path_supports(K)) return BNN_ERR_UNSUPPORTED;
     const int64_t kw = ceil_div(K, 32);
     if (lda < kw || ldb < kw || ldc < N) return BNN_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return BNN_OK;
@@ -368,6 +351,8 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
                                dim3(256), 0, s, A, lda, B, ldb, C, ldc, m, n, k, tiles_n, n_tiles);
             break;
         }
+        case KERNEL_MFMA:
+            return launch_xnor_gemm_mfma(A, lda, B, ldb, C, ldc, M, N, K, stream);
         default:
             return BNN_ERR_INVALID_ARG;
     }
@@ -377,8 +362,12 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
 static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb,
                                            int64_t M, int64_t N, int64_t K, const int32_t* thr,
                                            const uint32_t* flip_bits, uint32_t* out, int64_t ld_out,
-                                           void* stream) {
+                                           int kernel_id, void* stream) {
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return BNN_ERR_INVALID_ARG;
+    if (kernel_id != KERNEL_AUTO && kernel_id != KERNEL_TILED128 && kernel_id != KERNEL_TILED64 &&
+        kernel_id != KERNEL_MFMA)
+        return BNN_ERR_INVALID_ARG;
+    if (kernel_id == KERNEL_MFMA && !mfma_path_supports(K)) return BNN_ERR_UNSUPPORTED;
     const int64_t kw = ceil_div(K, 32);
     if (lda < kw || ldb < kw || ld_out < ceil_div(N, 32)) return BNN_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return BNN_OK;
@@ -389,8 +378,10 @@ static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const
     if (ceil_div(M, 16) * ceil_div(N, 16) > kMaxDim) return BNN_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const BnSignArgs bn{thr, flip_bits, out, ld_out};
-    const int64_t tiles128 = ceil_div(M, 128) * ceil_div(N, 128);
-    if (tiles128 >= 512)
+    if (kernel_id == KERNEL_AUTO)
+        kernel_id = ceil_div(M, 128) * ceil_div(N, 128) >= 512 ? KERNEL_TILED128 : KERNEL_TILED64;
+    if (kernel_id == KERNEL_MFMA) return launch_xnor_gemm_mfma_fused(A, lda, B, ldb, M, N, K, bn, stream);
+    if (kernel_id == KERNEL_TILED128)
         launch_tiled<8, 8, 16, true>(A, lda, B, ldb, nullptr, 0, int(M), int(N), int(K), bn, s);
     else
         launch_tiled<4, 4, 16, true>(A, lda, B, ldb, nullptr, 0, int(M), int(N), int(K), bn, s);
@@ -403,7 +394,16 @@ extern "C" int bnn_xnor_gemm_bn_sign_pack(const uint32_t* A, int64_t lda, const 
                                           int64_t M, int64_t N, int64_t K, const int32_t* thr,
                                           const uint32_t* flip_bits, uint32_t* out, int64_t ld_out,
                                           void* stream) {
-    return bnn::xnor_gemm_bn_sign_pack_dispatch(A, lda, B, ldb, M, N, K, thr, flip_bits, out, ld_out, stream);
+    return bnn::xnor_gemm_bn_sign_pack_dispatch(A, lda, B, ldb, M, N, K, thr, flip_bits, out, ld_out,
+                                                bnn::KERNEL_AUTO, stream);
+}
+
+extern "C" int bnn_xnor_gemm_bn_sign_pack_kernel(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb,
+                                                 int64_t M, int64_t N, int64_t K, const int32_t* thr,
+                                                 const uint32_t* flip_bits, uint32_t* out, int64_t ld_out,
+                                                 int kernel_id, void* stream) {
+    return bnn::xnor_gemm_bn_sign_pack_dispatch(A, lda, B, ldb, M, N, K, thr, flip_bits, out, ld_out, kernel_id,
+                                                stream);
 }
 
 extern "C" int bnn_xnor_gemm(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,

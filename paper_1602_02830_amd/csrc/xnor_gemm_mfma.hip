@@ -1,0 +1,253 @@
+// Bits-in, matrix-engine-inside variant of the binary product of Sec. 4 / Alg. 4.
+//
+// Operands stay packed 32 per word in HBM and LDS (the 32x smaller footprint
+// the paper argues for); only inside registers is each bit widened to a 4-bit
+// float (E2M1: code 0b0010 = 1.0, 0b0000 = 0.0) and fed to
+// v_mfma_scale_f32_32x32x64_f8f6f4, whose fp32 accumulation of 0/1 products is
+// exact for K < 2^24.  With a, b in {0,1} standing for -1/+1:
+//
+//   sum_k (2a-1)(2b-1) = K - 2*popcount(A_m) - 2*popcount(B_n) + 4 * sum_k a*b
+//
+// so the +-1 product of Eq. (5) is the matrix-engine sum S plus per-row and
+// per-column popcounts, which the staging threads gather for free while they
+// copy the tile.  Pad bits and rows outside the matrix are zeroed at staging
+// and therefore contribute to neither S nor the popcounts.
+//
+// Widening costs 7 vector-ALU operations per 32 elements per lane: with
+// M = 0x22222222, the four operand registers are (w<<1)&M, w&M, (w>>1)&M,
+// (w>>2)&M - element k of the word lands in register k%4, nibble k/4.  A and B
+// use the same assignment, and the sum over k does not depend on its order.
+//
+// Workgroup = 256 threads = 2 x 2 wavefronts; a wavefront owns WM x WN blocks
+// of 32 x 32 outputs (fp32 accumulators).  K advances 8 words (256 bits) per
+// staged tile = 4 MFMA steps of 64 bits: lane (row r = l%32, half h = l/32) of
+// a fragment owns words [4h, 4h+4) of its row, read with one ds_read_b128.
+#include "bnn_internal.h"
+#include "gemm_staging.h"
+
+namespace bnn {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int kMfmaKT = 8;          // words of K per staged tile
+constexpr int kMfmaKQ = kMfmaKT / 4;  // 16-byte quads per row per tile (= lane halves)
+constexpr int64_t kMfmaMaxK = int64_t(1) << 24;   // exact fp32 accumulation of 0/1 products
+
+__device__ inline v8i widen_fp4(uint32_t w) {
+    constexpr uint32_t M = 0x22222222u;
+    v8i f = {int((w << 1) & M), int(w & M), int((w >> 1) & M), int((w >> 2) & M), 0, 0, 0, 0};
+    return f;
+}
+
+__device__ inline int popc4(uint4 v) { return __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w); }
+
+template <int WM, int WN, bool VEC, bool FUSED>
+__global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
+    const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B, int64_t ldb,
+    int32_t* __restrict__ C, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n, BnSignArgs bn) {
+    constexpr int BM = 64 * WM, BN = 64 * WN;          // 2 x 2 wavefronts
+    constexpr int PLANE_A = BM + 2, PLANE_B = BN + 2;  // 16-byte slots per quad plane (2 pad slots)
+    constexpr int ST_ROWS = 256 / kMfmaKQ;             // rows covered by one staging pass
+    constexpr int LOADS_A = BM / ST_ROWS, LOADS_B = BN / ST_ROWS;
+    static_assert(BM % ST_ROWS == 0 && BN % ST_ROWS == 0, "tile rows must divide among the staging threads");
+    __shared__ uint4 lds_a[2][kMfmaKQ * PLANE_A];
+    __shared__ uint4 lds_b[2][kMfmaKQ * PLANE_B];
+    __shared__ int pop_a[BM];
+    __shared__ int pop_b[BN];
+
+    int tile_m, tile_n;
+    tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+    const int row0 = tile_m * BM, col0 = tile_n * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int fr = lane & 31, fh = lane >> 5;
+    const int kw = (K + 31) >> 5;
+    const uint32_t tmask = tail_mask(K);
+    const int n_ktiles = (kw + kMfmaKT - 1) / kMfmaKT;
+
+    const int st_q = tid % kMfmaKQ, st_r = tid / kMfmaKQ;
+    // Complete K-tiles take branch-free loads (row clamped into the matrix, zeroed at staging
+    // if it does not exist); the last, partial K-tile goes through the checked, masking loader.
+    const int n_full_ktiles = (K >> 5) / kMfmaKT;
+    const uint32_t* pa[LOADS_A];
+    const uint32_t* pb[LOADS_B];
+    bool live_a[LOADS_A], live_b[LOADS_B];
+#pragma unroll
+    for (int l = 0; l < LOADS_A; ++l) {
+        const int r = row0 + st_r + l * ST_ROWS;
+        live_a[l] = r < M;
+        pa[l] = A + int64_t(min(r, M - 1)) * lda;
+    }
+#pragma unroll
+    for (int l = 0; l < LOADS_B; ++l) {
+        const int r = col0 + st_r + l * ST_ROWS;
+        live_b[l] = r < N;
+        pb[l] = B + int64_t(min(r, N - 1)) * ldb;
+    }
+    uint4 ra[LOADS_A], rb[LOADS_B];
+    int cnt_a[LOADS_A], cnt_b[LOADS_B];
+#pragma unroll
+    for (int l = 0; l < LOADS_A; ++l) cnt_a[l] = 0;
+#pragma unroll
+    for (int l = 0; l < LOADS_B; ++l) cnt_b[l] = 0;
+    auto fetch = [&](int kt) {
+        const int quad = kt * kMfmaKQ + st_q;
+        if (kt < n_full_ktiles) {
+#pragma unroll
+            for (int l = 0; l < LOADS_A; ++l) ra[l] = load_quad_unchecked<VEC>(pa[l], quad);
+#pragma unroll
+            for (int l = 0; l < LOADS_B; ++l) rb[l] = load_quad_unchecked<VEC>(pb[l], quad);
+        } else {
+#pragma unroll
+            for (int l = 0; l < LOADS_A; ++l)
+                ra[l] = load_quad<VEC>(A, lda, M, kw, tmask, row0 + st_r + l * ST_ROWS, quad);
+#pragma unroll
+            for (int l = 0; l < LOADS_B; ++l)
+                rb[l] = load_quad<VEC>(B, ldb, N, kw, tmask, col0 + st_r + l * ST_ROWS, quad);
+        }
+    };
+    // Writes the fetched quads to LDS and adds their set bits to this thread's row popcounts.
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int l = 0; l < LOADS_A; ++l) {
+            const uint4 v = zero_unless(live_a[l], ra[l]);
+            cnt_a[l] += popc4(v);
+            lds_a[buf][st_q * PLANE_A + st_r + l * ST_ROWS] = v;
+        }
+#pragma unroll
+        for (int l = 0; l < LOADS_B; ++l) {
+            const uint4 v = zero_unless(live_b[l], rb[l]);
+            cnt_b[l] += popc4(v);
+            lds_b[buf][st_q * PLANE_B + st_r + l * ST_ROWS] = v;
+        }
+    };
+
+    v16f acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    if (n_ktiles > 0) {
+        fetch(0);
+        stage(0);
+    }
+    __syncthreads();
+
+    constexpr int kScaleOne = 0x7f7f7f7f;      // E8M0 exponent 127 = scale 1.0 in every byte
+    for (int kt = 0; kt < n_ktiles; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < n_ktiles) fetch(kt + 1);
+
+        uint4 aw[WM], bw[WN];
+#pragma unroll
+        for (int i = 0; i < WM; ++i) aw[i] = lds_a[buf][fh * PLANE_A + wm * 32 * WM + i * 32 + fr];
+#pragma unroll
+        for (int j = 0; j < WN; ++j) bw[j] = lds_b[buf][fh * PLANE_B + wn * 32 * WN + j * 32 + fr];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            v8i fa[WM], fb[WN];
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+                fa[i] = widen_fp4(s == 0 ? aw[i].x : s == 1 ? aw[i].y : s == 2 ? aw[i].z : aw[i].w);
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
+                fb[j] = widen_fp4(s == 0 ? bw[j].x : s == 1 ? bw[j].y : s == 2 ? bw[j].z : bw[j].w);
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int j = 0; j < WN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        fa[i], fb[j], acc[i][j], 4 /* A: fp4 */, 4 /* B: fp4 */, 0, kScaleOne, 0, kScaleOne);
+        }
+
+        if (kt + 1 < n_ktiles) stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // Row popcounts: the kMfmaKQ threads that staged the quads of one row are neighbouring lanes.
+#pragma unroll
+    for (int l = 0; l < LOADS_A; ++l) {
+        int c = cnt_a[l];
+        c += __builtin_amdgcn_update_dpp(0, c, 0xB1, 0xF, 0xF, true);       // lane ^ 1
+        if (st_q == 0) pop_a[st_r + l * ST_ROWS] = c;
+    }
+#pragma unroll
+    for (int l = 0; l < LOADS_B; ++l) {
+        int c = cnt_b[l];
+        c += __builtin_amdgcn_update_dpp(0, c, 0xB1, 0xF, 0xF, true);
+        if (st_q == 0) pop_b[st_r + l * ST_ROWS] = c;
+    }
+    __syncthreads();
+
+    // Accumulator register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32 of its 32x32 block.
+#pragma unroll
+    for (int j = 0; j < WN; ++j) {
+        const int nl = wn * 32 * WN + j * 32 + fr;
+        const int n = col0 + nl;
+        const int base_n = K - 2 * pop_b[nl];
+        int thr = 0;
+        bool flip = false;
+        if (FUSED && n < N) {
+            thr = bn.thr[n];
+            flip = ((bn.flip_bits[n >> 5] >> (n & 31)) & 1u) != 0u;
+        }
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int ml = wm * 32 * WM + i * 32 + 8 * (v / 4) + 4 * fh + (v % 4);
+                const int m = row0 + ml;
+                const int dot = base_n - 2 * pop_a[ml] + 4 * int(acc[i][j][v]);
+                if (!FUSED) {
+                    if (m < M && n < N) C[int64_t(m) * ldc + n] = dot;
+                } else {
+                    // Lanes 0-31 hold one row, lanes 32-63 the row 4 below: the ballot's two
+                    // halves are the two rows' words for columns [n - fr, n - fr + 32).
+                    const bool p = n < N && ((dot >= thr) != flip);
+                    const uint64_t mask = __ballot(p);
+                    const int64_t w = (int64_t(col0) + wn * 32 * WN + j * 32) >> 5;
+                    if (fr == 0 && m < M && w < ((int64_t(N) + 31) >> 5))
+                        bn.out[int64_t(m) * bn.ld_out + w] = fh ? uint32_t(mask >> 32) : uint32_t(mask);
+                }
+            }
+    }
+}
+
+template <bool FUSED>
+static int launch_mfma(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc,
+                       int64_t M, int64_t N, int64_t K, BnSignArgs bn, void* stream) {
+    constexpr int WM = 4, WN = 2;
+    const int64_t tiles_m = ceil_div(M, 64 * WM), tiles_n = ceil_div(N, 64 * WN);
+    if (tiles_m * tiles_n > kMaxDim) return BNN_ERR_UNSUPPORTED;
+    const bool vec = aligned_to(A, 16) && aligned_to(B, 16) && lda % 4 == 0 && ldb % 4 == 0;
+    const dim3 grid{unsigned(tiles_m * tiles_n)};
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (vec)
+        hipLaunchKernelGGL((xnor_gemm_mfma_kernel<WM, WN, true, FUSED>), grid, dim3(256), 0, s, A, lda, B, ldb, C,
+                           ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn);
+    else
+        hipLaunchKernelGGL((xnor_gemm_mfma_kernel<WM, WN, false, FUSED>), grid, dim3(256), 0, s, A, lda, B, ldb,
+                           C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn);
+    return check_launch();
+}
+
+// Entry points used by the dispatcher in xnor_gemm.hip.  The caller has validated the arguments.
+bool mfma_path_supports(int64_t K) { return K <= kMfmaMaxK; }
+
+int launch_xnor_gemm_mfma(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
+                          int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream) {
+    return launch_mfma<false>(A, lda, B, ldb, C, ldc, M, N, K, BnSignArgs{}, stream);
+}
+
+int launch_xnor_gemm_mfma_fused(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M,
+                                int64_t N, int64_t K, BnSignArgs bn, void* stream) {
+    return launch_mfma<true>(A, lda, B, ldb, nullptr, 0, M, N, K, bn, stream);
+}
+
+}  // namespace bnn

@@ -21,6 +21,7 @@ GEMM_KERNELS = {
     "tiled128": bnn.KERNEL_TILED128,
     "ksplit": bnn.KERNEL_KSPLIT,
     "tiled64": bnn.KERNEL_TILED64,
+    "mfma": bnn.KERNEL_MFMA,
 }
 
 
@@ -134,7 +135,7 @@ def test_xnor_gemm_ragged_sweep(kernel):
         _gemm_case(A, Bm, GEMM_KERNELS[kernel], poison=True)
 
 
-@pytest.mark.parametrize("kernel", ["auto", "tiled128", "tiled64", "naive", "ksplit"])
+@pytest.mark.parametrize("kernel", ["auto", "tiled128", "tiled64", "naive", "ksplit", "mfma"])
 def test_xnor_gemm_odd_leading_dimensions(kernel):
     rng = np.random.default_rng(5)
     for (M, N, K) in [(130, 70, 1000), (17, 300, 129), (256, 256, 2048)]:
@@ -143,7 +144,7 @@ def test_xnor_gemm_odd_leading_dimensions(kernel):
             _gemm_case(A, Bm, GEMM_KERNELS[kernel], poison=True, ld_extra=extra)
 
 
-@pytest.mark.parametrize("kernel", ["auto", "tiled128", "tiled64"])
+@pytest.mark.parametrize("kernel", ["auto", "tiled128", "tiled64", "mfma"])
 def test_xnor_gemm_multi_tile_shapes(kernel):
     rng = np.random.default_rng(6)
     for (M, N, K) in [(64, 1024, 1024), (300, 520, 784), (1024, 10, 4096), (513, 129, 96), (2, 2048, 640)]:
@@ -171,14 +172,15 @@ def test_xnor_gemm_empty_and_k_zero():
     assert (c.cpu().numpy() == 0).all()
 
 
-@pytest.mark.parametrize("kernel", ["auto", "tiled128"])
+@pytest.mark.parametrize("kernel", ["auto", "tiled128", "mfma"])
 def test_xnor_gemm_dense_layer_config(kernel):
     """Config: A 64x1024, B 1024x1024, K = 1024."""
     A, Bm, _ = synth.config_dense()
     _gemm_case(A, Bm, GEMM_KERNELS[kernel])
 
 
-def test_xnor_gemm_large_square_hadamard_and_sampled_rows():
+@pytest.mark.parametrize("kernel", ["auto", "tiled128", "mfma"])
+def test_xnor_gemm_large_square_hadamard_and_sampled_rows(kernel):
     """8192^3 in the launch configuration the benchmark times.  (i) Sylvester-Hadamard
     operands: the full 8192 x 8192 result must be 8192 * I (closed form, checked on
     every element).  (ii) random +-1 operands: 256 sampled rows and a band of columns
@@ -186,13 +188,13 @@ def test_xnor_gemm_large_square_hadamard_and_sampled_rows():
     n = synth.GEMM_LARGE
     H = synth.hadamard(n)
     hb = words_to_dev(oracle.pack_bits(H))
-    C = bnn.xnor_gemm(hb, hb, n)
+    C = bnn.xnor_gemm(hb, hb, n, kernel=GEMM_KERNELS[kernel])
     assert torch.equal(C, n * torch.eye(n, dtype=torch.int32, device=DEV))
     del C
     A, Bm = synth.config_gemm_square(n)
     da = words_to_dev(oracle.pack_bits(A))
     db = words_to_dev(oracle.pack_bits(np.ascontiguousarray(Bm.T)))
-    C = bnn.xnor_gemm(da, db, n).cpu().numpy()
+    C = bnn.xnor_gemm(da, db, n, kernel=GEMM_KERNELS[kernel]).cpu().numpy()
     rows = np.random.default_rng(1).choice(n, 256, replace=False)
     assert (C[rows] == oracle.matmul_pm1(A[rows], Bm)).all()
     cols = np.arange(4000, 4128)
@@ -241,7 +243,8 @@ def test_bn_sign_pack_strided_unaligned_and_canary():
 
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (7, 33, 31), (33, 7, 65), (64, 1024, 1024), (130, 200, 1000),
                                    (1000, 1000, 4097), (300, 4096, 784), (2000, 4096, 4096), (129, 95, 96)])
-def test_fused_layer_matches_float_bn_then_sign(M, N, K):
+@pytest.mark.parametrize("kernel", ["auto", "tiled128", "tiled64", "mfma"])
+def test_fused_layer_matches_float_bn_then_sign(M, N, K, kernel):
     """Alg. 4 hidden layer in one launch == oracle product, float BatchNorm, Sign, pack."""
     rng = np.random.default_rng(M * 3 + N * 5 + K * 7)
     A, Bm = synth.pm1(rng, (M, K)), synth.pm1(rng, (K, N))
@@ -253,7 +256,7 @@ def test_fused_layer_matches_float_bn_then_sign(M, N, K):
     pb = words_to_dev(poison_pad_bits(oracle.pack_bits(np.ascontiguousarray(Bm.T)), K))
     nw = (N + 31) // 32
     out = torch.full((M, nw + 1), 0x0BADF00D, dtype=torch.int32, device=DEV)
-    bnn.xnor_gemm_bn_sign_pack(pa, pb, K, thr, flip, out=out[:, :nw])
+    bnn.xnor_gemm_bn_sign_pack(pa, pb, K, thr, flip, out=out[:, :nw], kernel=GEMM_KERNELS[kernel])
     host = words_to_host(out)
     assert (host[:, :nw] == want).all()
     assert (host[:, nw:] == 0x0BADF00D).all()
