@@ -57,6 +57,36 @@ def time_launches(fn, iters, warmup=2):
     return float(np.mean(t)), float(np.min(t))
 
 
+def gemm_only(args, bnn, torch, dev):
+    """One GEMM shape, one kernel: W warm-up launches, K timed launches, one JSON line."""
+    M, N, K = (int(v) for v in args.gemm.split(","))
+    kw = (K + 31) // 32
+    ld = (kw + 3) // 4 * 4
+    g = torch.Generator(device=dev)
+    g.manual_seed(160202830)
+    a = torch.randint(-2 ** 31, 2 ** 31 - 1, (M, ld), dtype=torch.int32, device=dev, generator=g)[:, :kw]
+    b = torch.randint(-2 ** 31, 2 ** 31 - 1, (N, ld), dtype=torch.int32, device=dev, generator=g)[:, :kw]
+    kid = {"auto": bnn.KERNEL_AUTO, "naive": bnn.KERNEL_NAIVE, "tiled128": bnn.KERNEL_TILED128,
+           "ksplit": bnn.KERNEL_KSPLIT, "tiled64": bnn.KERNEL_TILED64, "mfma": bnn.KERNEL_MFMA}.get(args.kernel)
+    if args.kernel == "i8":
+        a8, b8 = bnn.unpack_i8(a, K), bnn.unpack_i8(b, K)
+        c = torch.empty((M, N), dtype=torch.int32, device=dev)
+        fn = lambda: bnn.gemm_i8_mfma(a8, b8, out=c)
+    elif args.fused:
+        thr = torch.zeros(N, dtype=torch.int32, device=dev)
+        flip = torch.zeros((N + 31) // 32, dtype=torch.int32, device=dev)
+        out = torch.empty((M, (N + 31) // 32), dtype=torch.int32, device=dev)
+        fn = lambda: bnn.xnor_gemm_bn_sign_pack(a, b, K, thr, flip, out=out, kernel=kid)
+    else:
+        c = torch.empty((M, N), dtype=torch.int32, device=dev)
+        fn = lambda: bnn.xnor_gemm(a, b, K, out=c, kernel=kid)
+    ms, ms_min = time_launches(fn, args.steps, warmup=args.warmup)
+    ops = 2.0 * M * N * K
+    print(json.dumps({"workload": f"xnor_gemm_{M}x{N}x{K}", "kernel": args.kernel, "fused": bool(args.fused),
+                      "steps": args.steps, "warmup": args.warmup, "avg_launch_ms": ms, "min_launch_ms": ms_min,
+                      "binary_tops": ops / ms / 1e9}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -68,6 +98,11 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=2500, help="images the CPU oracle is timed on")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic, for scaling profiler byte counters)")
+    ap.add_argument("--gemm", default=None, metavar="M,N,K",
+                    help="time only bnn_xnor_gemm on random packed operands of this shape (for profiler runs)")
+    ap.add_argument("--kernel", default="auto", choices=["auto", "naive", "tiled128", "ksplit", "tiled64", "mfma", "i8"],
+                    help="kernel for --gemm (i8 = the int8 MFMA variant on unpacked operands)")
+    ap.add_argument("--fused", action="store_true", help="with --gemm: the fused BN+Sign entry point instead")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -83,6 +118,10 @@ def main():
         raise RuntimeError("bench.py needs a GPU; there is no CPU fallback")
     dev = "cuda:0"
     eps = 1e-4
+
+    if args.gemm:
+        gemm_only(args, bnn, torch, dev)
+        return
 
     # ---------------- workload: MNIST-shaped MLP, batch 10000, synthetic -------------
     x, weights, bns = synth.config_mlp()

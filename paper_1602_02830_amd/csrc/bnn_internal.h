@@ -7,6 +7,10 @@
 
 #include "bnn.h"
 
+// v_writelane_b32 through its LLVM intrinsic (this compiler exposes no __builtin for it):
+// returns `old` with lane `lane` replaced by the wavefront-uniform `value`.
+extern "C" __device__ int bnn_llvm_writelane(int value, int lane, int old) __asm("llvm.amdgcn.writelane.i32");
+
 namespace bnn {
 
 constexpr int kWave = 64;

@@ -19,9 +19,11 @@
 // use the same assignment, and the sum over k does not depend on its order.
 //
 // Workgroup = 256 threads = 2 x 2 wavefronts; a wavefront owns WM x WN blocks
-// of 32 x 32 outputs (fp32 accumulators).  K advances 8 words (256 bits) per
-// staged tile = 4 MFMA steps of 64 bits: lane (row r = l%32, half h = l/32) of
-// a fragment owns words [4h, 4h+4) of its row, read with one ds_read_b128.
+// of 32 x 32 outputs (fp32 accumulators).  K advances 16 words (512 bits) per
+// staged tile = 8 MFMA steps of 64 bits: lane (row r = l%32, half h = l/32) of
+// a fragment owns words [8h, 8h+8) of its row, read with two ds_read_b128.
+// The tile is long enough that the global loads of the next tile, issued
+// before the MFMA steps, have landed when they are staged.
 #include "bnn_internal.h"
 #include "gemm_staging.h"
 
@@ -30,8 +32,9 @@ namespace bnn {
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-constexpr int kMfmaKT = 8;          // words of K per staged tile
-constexpr int kMfmaKQ = kMfmaKT / 4;  // 16-byte quads per row per tile (= lane halves)
+constexpr int kMfmaKT = 16;         // words of K per staged tile
+constexpr int kMfmaKQ = kMfmaKT / 4;  // 16-byte quads per row per tile
+constexpr int kMfmaSteps = kMfmaKT / 2;  // MFMA steps per tile (each consumes one word from each lane half)
 constexpr int64_t kMfmaMaxK = int64_t(1) << 24;   // exact fp32 accumulation of 0/1 products
 
 __device__ inline v8i widen_fp4(uint32_t w) {
@@ -51,10 +54,11 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
     constexpr int ST_ROWS = 256 / kMfmaKQ;             // rows covered by one staging pass
     constexpr int LOADS_A = BM / ST_ROWS, LOADS_B = BN / ST_ROWS;
     static_assert(BM % ST_ROWS == 0 && BN % ST_ROWS == 0, "tile rows must divide among the staging threads");
+    static_assert(kMfmaKQ == 4, "the row-popcount reduction below assumes 4 staging lanes per row");
     __shared__ uint4 lds_a[2][kMfmaKQ * PLANE_A];
     __shared__ uint4 lds_b[2][kMfmaKQ * PLANE_B];
-    __shared__ int pop_a[BM];
-    __shared__ int pop_b[BN];
+    __shared__ __attribute__((aligned(16))) int pop_a[BM];
+    __shared__ __attribute__((aligned(16))) int pop_b[BN];
 
     int tile_m, tile_n;
     tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
@@ -140,30 +144,34 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
     __syncthreads();
 
     constexpr int kScaleOne = 0x7f7f7f7f;      // E8M0 exponent 127 = scale 1.0 in every byte
+    auto word_of = [](const uint4& q, int s) { return s == 0 ? q.x : s == 1 ? q.y : s == 2 ? q.z : q.w; };
+
     for (int kt = 0; kt < n_ktiles; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < n_ktiles) fetch(kt + 1);
 
-        uint4 aw[WM], bw[WN];
+        // The lane's 8 words are quads 2*fh and 2*fh+1 of its tile row; each quad feeds 4 steps.
 #pragma unroll
-        for (int i = 0; i < WM; ++i) aw[i] = lds_a[buf][fh * PLANE_A + wm * 32 * WM + i * 32 + fr];
+        for (int hq = 0; hq < 2; ++hq) {
+            uint4 aw[WM], bw[WN];
 #pragma unroll
-        for (int j = 0; j < WN; ++j) bw[j] = lds_b[buf][fh * PLANE_B + wn * 32 * WN + j * 32 + fr];
+            for (int i = 0; i < WM; ++i) aw[i] = lds_a[buf][(2 * fh + hq) * PLANE_A + wm * 32 * WM + i * 32 + fr];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            v8i fa[WM], fb[WN];
+            for (int j = 0; j < WN; ++j) bw[j] = lds_b[buf][(2 * fh + hq) * PLANE_B + wn * 32 * WN + j * 32 + fr];
 #pragma unroll
-            for (int i = 0; i < WM; ++i)
-                fa[i] = widen_fp4(s == 0 ? aw[i].x : s == 1 ? aw[i].y : s == 2 ? aw[i].z : aw[i].w);
+            for (int s = 0; s < 4; ++s) {
+                v8i fa[WM], fb[WN];
 #pragma unroll
-            for (int j = 0; j < WN; ++j)
-                fb[j] = widen_fp4(s == 0 ? bw[j].x : s == 1 ? bw[j].y : s == 2 ? bw[j].z : bw[j].w);
+                for (int i = 0; i < WM; ++i) fa[i] = widen_fp4(word_of(aw[i], s));
 #pragma unroll
-            for (int i = 0; i < WM; ++i)
+                for (int j = 0; j < WN; ++j) fb[j] = widen_fp4(word_of(bw[j], s));
 #pragma unroll
-                for (int j = 0; j < WN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                        fa[i], fb[j], acc[i][j], 4 /* A: fp4 */, 4 /* B: fp4 */, 0, kScaleOne, 0, kScaleOne);
+                for (int i = 0; i < WM; ++i)
+#pragma unroll
+                    for (int j = 0; j < WN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                            fa[i], fb[j], acc[i][j], 4 /* A: fp4 */, 4 /* B: fp4 */, 0, kScaleOne, 0, kScaleOne);
+            }
         }
 
         if (kt + 1 < n_ktiles) stage(buf ^ 1);
@@ -175,47 +183,86 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
     for (int l = 0; l < LOADS_A; ++l) {
         int c = cnt_a[l];
         c += __builtin_amdgcn_update_dpp(0, c, 0xB1, 0xF, 0xF, true);       // lane ^ 1
-        if (st_q == 0) pop_a[st_r + l * ST_ROWS] = c;
+        c += __builtin_amdgcn_update_dpp(0, c, 0x4E, 0xF, 0xF, true);       // lane ^ 2
+        if (st_q == 0) pop_a[st_r + l * ST_ROWS] = 2 * c;
     }
 #pragma unroll
     for (int l = 0; l < LOADS_B; ++l) {
         int c = cnt_b[l];
         c += __builtin_amdgcn_update_dpp(0, c, 0xB1, 0xF, 0xF, true);
-        if (st_q == 0) pop_b[st_r + l * ST_ROWS] = c;
+        c += __builtin_amdgcn_update_dpp(0, c, 0x4E, 0xF, 0xF, true);
+        if (st_q == 0) pop_b[st_r + l * ST_ROWS] = 2 * c;
     }
     __syncthreads();
 
     // Accumulator register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32 of its 32x32 block.
+    // pop_a / pop_b hold twice the popcounts from here on.
+    if (!FUSED) {
 #pragma unroll
-    for (int j = 0; j < WN; ++j) {
-        const int nl = wn * 32 * WN + j * 32 + fr;
-        const int n = col0 + nl;
-        const int base_n = K - 2 * pop_b[nl];
-        int thr = 0;
-        bool flip = false;
-        if (FUSED && n < N) {
-            thr = bn.thr[n];
-            flip = ((bn.flip_bits[n >> 5] >> (n & 31)) & 1u) != 0u;
+        for (int j = 0; j < WN; ++j) {
+            const int nl = wn * 32 * WN + j * 32 + fr;
+            const int n = col0 + nl;
+            const int base_n = K - pop_b[nl];
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int ml = wm * 32 * WM + i * 32 + 8 * vq + 4 * fh;
+                    const int4 pa2 = *reinterpret_cast<const int4*>(&pop_a[ml]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int m = row0 + ml + e;
+                        const int pa = e == 0 ? pa2.x : e == 1 ? pa2.y : e == 2 ? pa2.z : pa2.w;
+                        const int dot = base_n - pa + 4 * int(acc[i][j][4 * vq + e]);
+                        if (m < M && n < N) C[int64_t(m) * ldc + n] = dot;
+                    }
+                }
         }
+    } else {
+        // bit(m, n) = (dot >= thr[n]) XOR flip[n] with dot = K - 2pa - 2pb + 4S, i.e.
+        // S >= ceil((thr - K + 2pb + 2pa) / 4) = (thr - K + 2pb + 3 + 2pa) >> 2.
+        // A ballot over one accumulator register gives, in its low half, the 32-column word of
+        // the row held by lanes 0-31 and, in its high half, that of the row 4 below.  The words
+        // of one 32-row block are gathered with v_writelane so that lane r (block j = 0) and
+        // lane 32 + r (block j = 1) end up holding row r's two words: one store per block row.
+        static_assert(WN == 2, "the fused epilogue pairs the two column blocks with the two lane halves");
+        int u3[WN];
+        uint64_t flip_mask[WN], live_mask[WN];
 #pragma unroll
-        for (int i = 0; i < WM; ++i)
+        for (int j = 0; j < WN; ++j) {
+            const int nl = wn * 32 * WN + j * 32 + fr;
+            const int n = col0 + nl;
+            const bool live = n < N;
+            const int thr = live ? bn.thr[n] : 0;
+            const bool flip = live && ((bn.flip_bits[n >> 5] >> (n & 31)) & 1u) != 0u;
+            u3[j] = thr - K + pop_b[nl] + 3;
+            flip_mask[j] = __ballot(flip);
+            live_mask[j] = __ballot(live);
+        }
+        const int64_t nw = (int64_t(N) + 31) >> 5;
+        const int64_t w = ((int64_t(col0) + wn * 32 * WN) >> 5) + fh;       // word column of this lane
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int ml = wm * 32 * WM + i * 32 + 8 * (v / 4) + 4 * fh + (v % 4);
-                const int m = row0 + ml;
-                const int dot = base_n - 2 * pop_a[ml] + 4 * int(acc[i][j][v]);
-                if (!FUSED) {
-                    if (m < M && n < N) C[int64_t(m) * ldc + n] = dot;
-                } else {
-                    // Lanes 0-31 hold one row, lanes 32-63 the row 4 below: the ballot's two
-                    // halves are the two rows' words for columns [n - fr, n - fr + 32).
-                    const bool p = n < N && ((dot >= thr) != flip);
-                    const uint64_t mask = __ballot(p);
-                    const int64_t w = (int64_t(col0) + wn * 32 * WN + j * 32) >> 5;
-                    if (fr == 0 && m < M && w < ((int64_t(N) + 31) >> 5))
-                        bn.out[int64_t(m) * bn.ld_out + w] = fh ? uint32_t(mask >> 32) : uint32_t(mask);
+        for (int i = 0; i < WM; ++i) {
+            int words = 0;
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const int ml = wm * 32 * WM + i * 32 + 8 * vq + 4 * fh;
+                const int4 pa2 = *reinterpret_cast<const int4*>(&pop_a[ml]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int pa = e == 0 ? pa2.x : e == 1 ? pa2.y : e == 2 ? pa2.z : pa2.w;
+#pragma unroll
+                    for (int j = 0; j < WN; ++j) {
+                        const bool p = int(acc[i][j][4 * vq + e]) >= ((u3[j] + pa) >> 2);
+                        const uint64_t mask = (__ballot(p) ^ flip_mask[j]) & live_mask[j];
+                        words = bnn_llvm_writelane(int(uint32_t(mask)), 32 * j + 8 * vq + e, words);
+                        words = bnn_llvm_writelane(int(uint32_t(mask >> 32)), 32 * j + 8 * vq + 4 + e, words);
+                    }
                 }
             }
+            const int m = row0 + wm * 32 * WM + i * 32 + fr;
+            if (m < M && w < nw) bn.out[int64_t(m) * bn.ld_out + w] = uint32_t(words);
+        }
     }
 }
 
