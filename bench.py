@@ -34,6 +34,7 @@ PEAK_LANE_OPS = 256 * 64 * 2.4e9
 PEAK_BINARY_TOPS = PEAK_LANE_OPS / 2 * 64 / 1e12          # ~1258.3
 PEAK_HBM_GBS = 8000.0
 PEAK_I8_MFMA_TOPS = 5000.0                                # dense int8, 2*M*N*K counting
+PEAK_FP4_MFMA_TFLOPS = 10100.0                            # dense fp4/fp6 MFMA, 2*M*N*K counting
 
 
 def log(*a):
@@ -94,6 +95,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--unfused", action="store_true",
                     help="hidden layers as separate GEMM and BN+Sign launches (int32 pre-activations through HBM)")
+    ap.add_argument("--valu", action="store_true",
+                    help="force the vector-ALU XNOR-popcount GEMM kernel in the hidden layers "
+                         "(default: the library's choice, the bits-in / MFMA-inside kernel at these sizes)")
     ap.add_argument("--skip-extras", action="store_true", help="only the timed MLP region and the CPU baseline")
     ap.add_argument("--cpu-sample", type=int, default=2500, help="images the CPU oracle is timed on")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -128,7 +132,8 @@ def main():
     batch = x.shape[0]
     wr = [torch.from_numpy(np.ascontiguousarray(w.T).astype(np.float32)).to(dev) for w in weights]
     fused = not args.unfused
-    net = bnn.BinaryMLP(wr, bns, eps, batch, fused=fused)
+    net = bnn.BinaryMLP(wr, bns, eps, batch, fused=fused,
+                        kernel=bnn.KERNEL_TILED128 if args.valu else bnn.KERNEL_AUTO)
     del wr
     xd = torch.from_numpy(x).to(dev)
     torch.cuda.synchronize()
@@ -169,18 +174,19 @@ def main():
         "config": {"workload": "mlp_784-4096x3-10_batch10000", "batch": batch,
                    "kernels": ("pack_sign + 3 x xnor_gemm_bn_sign_pack + xnor_gemm" if fused else
                                "pack_sign + 4 x xnor_gemm + 3 x bn_sign_pack")},
-        "roofline": {
-            "bound": "alu",
-            "kernel": ("xnor_gemm_tiled_kernel<8,8,16,fused BN+Sign epilogue>" if fused else
-                       "xnor_gemm_tiled_kernel<8,8,16>") + " M=10000 N=4096 K=4096",
-            "achieved": achieved_tops,
-            "peak": PEAK_BINARY_TOPS,
-            "unit": "binary TOP/s (2*M*N*K/s; peak = 256 CU x 64 lanes x 2.4 GHz / 2 lane-ops per word x 64)",
-            "frac": achieved_tops / PEAK_BINARY_TOPS,
-            "avg_launch_ms": gemm_ms,
-            "traffic": None,
-        },
     }
+    kname = ("xnor_gemm_tiled_kernel<8,8,16>" if args.valu else "xnor_gemm_mfma_kernel<4,2>") + \
+            (" + fused BN+Sign epilogue" if fused else "") + " M=10000 N=4096 K=4096"
+    if args.valu:
+        result["roofline"] = {
+            "bound": "alu", "kernel": kname, "achieved": achieved_tops, "peak": PEAK_BINARY_TOPS,
+            "unit": "binary TOP/s (2*M*N*K/s; peak = 256 CU x 64 lanes x 2.4 GHz / 2 lane-ops per word x 64)",
+            "frac": achieved_tops / PEAK_BINARY_TOPS, "avg_launch_ms": gemm_ms, "traffic": None}
+    else:
+        result["roofline"] = {
+            "bound": "mfma", "kernel": kname, "achieved": achieved_tops, "peak": PEAK_FP4_MFMA_TFLOPS,
+            "unit": "TFLOP/s (fp4 MFMA, 2*M*N*K per launch)",
+            "frac": achieved_tops / PEAK_FP4_MFMA_TFLOPS, "avg_launch_ms": gemm_ms, "traffic": None}
 
     if args.calibration_copy:
         src = torch.zeros(256 * 1024 * 1024, dtype=torch.int32, device=dev)      # 1 GiB read + 1 GiB written
@@ -222,10 +228,21 @@ def main():
         c = torch.empty((n, n), dtype=torch.int32, device=dev)
         ops = 2.0 * n * n * n
         ms, ms_min = time_launches(lambda: bnn.xnor_gemm(a_bits, b_bits, n, out=c), 20)
-        extras["xnor_gemm_8192"] = {"ms": ms, "ms_min": ms_min, "binary_tops": ops / ms / 1e9,
-                                    "frac_of_valu_peak": ops / ms / 1e9 / PEAK_BINARY_TOPS}
-        log(f"xnor_gemm 8192^3: {ms:.3f} ms = {ops / ms / 1e9:.1f} binary TOP/s "
-            f"({ops / ms / 1e9 / PEAK_BINARY_TOPS:.1%} of VALU peak)")
+        extras["xnor_gemm_8192"] = {"kernel": "auto (bits-in / MFMA-inside)", "ms": ms, "ms_min": ms_min,
+                                    "binary_tops": ops / ms / 1e9,
+                                    "frac_of_fp4_mfma_peak": ops / ms / 1e9 / PEAK_FP4_MFMA_TFLOPS,
+                                    "vs_valu_roof": ops / ms / 1e9 / PEAK_BINARY_TOPS}
+        log(f"xnor_gemm 8192^3 (auto = MFMA-inside): {ms:.3f} ms = {ops / ms / 1e9:.1f} binary TOP/s "
+            f"({ops / ms / 1e9 / PEAK_FP4_MFMA_TFLOPS:.1%} of fp4 MFMA peak)")
+        c_valu = torch.empty((n, n), dtype=torch.int32, device=dev)
+        ms, ms_min = time_launches(lambda: bnn.xnor_gemm(a_bits, b_bits, n, out=c_valu, kernel=bnn.KERNEL_TILED128), 20)
+        extras["xnor_gemm_8192_valu"] = {"kernel": "tiled128 (v_xor + v_bcnt)", "ms": ms, "ms_min": ms_min,
+                                         "binary_tops": ops / ms / 1e9,
+                                         "frac_of_valu_peak": ops / ms / 1e9 / PEAK_BINARY_TOPS,
+                                         "equal_to_auto": bool(torch.equal(c, c_valu))}
+        log(f"xnor_gemm 8192^3 (vector-ALU XNOR-popcount): {ms:.3f} ms = {ops / ms / 1e9:.1f} binary TOP/s "
+            f"({ops / ms / 1e9 / PEAK_BINARY_TOPS:.1%} of VALU peak); equal: {extras['xnor_gemm_8192_valu']['equal_to_auto']}")
+        del c_valu
         a8, b8 = bnn.unpack_i8(a_bits, n), bnn.unpack_i8(b_bits, n)
         c2 = torch.empty((n, n), dtype=torch.int32, device=dev)
         ms, ms_min = time_launches(lambda: bnn.gemm_i8_mfma(a8, b8, out=c2), 20)
@@ -250,15 +267,15 @@ def main():
         for layer, (ch, hw) in enumerate(synth.CONV_LAYERS):
             xc, Wt, bn = synth.config_conv(layer)
             B = xc.shape[0]
-            cl = bnn.BinaryConvLayer(torch.from_numpy(Wt.astype(np.float32)).to(dev), bn, eps, B, hw, hw)
+            cl = bnn.BinaryConvLayer(torch.from_numpy(Wt.astype(np.float32)).to(dev), bn, eps, B, hw, hw, fused=True)
             xb = bnn.pack_sign(torch.from_numpy(xc.reshape(-1, ch).astype(np.float32)).to(dev)).view(B, hw, hw, ch // 32)
             ms, _ = time_launches(lambda: cl.forward(xb), 20)
             ms_i, _ = time_launches(lambda: bnn.conv_im2col_pack(xb, ch, out=cl.cols), 20)
-            ms_g, _ = time_launches(lambda: bnn.xnor_gemm(cl.cols, cl.w_bits, cl.K, out=cl.s), 20)
+            ms_g, _ = time_launches(lambda: bnn.xnor_gemm_bn_sign_pack(cl.cols, cl.w_bits, cl.K, cl.thr, cl.flip, out=cl.out_bits), 20)
             wbytes = cl.M * cl.K / 8
             conv[f"{ch}ch_{hw}x{hw}"] = {
                 "layer_ms": ms, "images_per_s": B / ms * 1e3, "im2col_ms": ms_i,
-                "im2col_write_GBps": wbytes / ms_i / 1e6, "gemm_ms": ms_g,
+                "im2col_write_GBps": wbytes / ms_i / 1e6, "fused_gemm_ms": ms_g,
                 "gemm_binary_tops": 2.0 * cl.M * cl.K * cl.Cout / ms_g / 1e9}
             log(f"conv {ch}ch {hw}x{hw} batch {B}: layer {ms:.3f} ms, im2col {ms_i:.3f} ms, gemm {ms_g:.3f} ms "
                 f"({conv[f'{ch}ch_{hw}x{hw}']['gemm_binary_tops']:.0f} TOP/s)")

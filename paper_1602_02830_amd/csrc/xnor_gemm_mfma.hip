@@ -13,10 +13,14 @@
 // copy the tile.  Pad bits and rows outside the matrix are zeroed at staging
 // and therefore contribute to neither S nor the popcounts.
 //
-// Widening costs 7 vector-ALU operations per 32 elements per lane: with
-// M = 0x22222222, the four operand registers are (w<<1)&M, w&M, (w>>1)&M,
-// (w>>2)&M - element k of the word lands in register k%4, nibble k/4.  A and B
-// use the same assignment, and the sum over k does not depend on its order.
+// Widening: element k of a word lands in operand register k%4, nibble k/4, for
+// both operands (the sum over k does not depend on its order).  The E2M1 codes
+// 0b0001, 0b0010, 0b0100 are 0.5, 1.0, 2.0, so most registers are a bare mask of
+// the word and only the product of the two sides has to be 1:
+//   register   0               1             2               3
+//   A side     w & 0x1111.. (0.5)  w & 0x2222.. (1)  w & 0x4444.. (2)  (w>>2) & 0x2222.. (1)
+//   B side     (w<<2) & 0x4444.. (2)  w & 0x2222.. (1)  (w>>2) & 0x1111.. (0.5)  (w>>2) & 0x2222.. (1)
+// i.e. 5 vector-ALU operations per 32 elements on the A side, 6 on the B side.
 //
 // Workgroup = 256 threads = 2 x 2 wavefronts; a wavefront owns WM x WN blocks
 // of 32 x 32 outputs (fp32 accumulators).  K advances 16 words (512 bits) per
@@ -37,9 +41,16 @@ constexpr int kMfmaKQ = kMfmaKT / 4;  // 16-byte quads per row per tile
 constexpr int kMfmaSteps = kMfmaKT / 2;  // MFMA steps per tile (each consumes one word from each lane half)
 constexpr int64_t kMfmaMaxK = int64_t(1) << 24;   // exact fp32 accumulation of 0/1 products
 
-__device__ inline v8i widen_fp4(uint32_t w) {
-    constexpr uint32_t M = 0x22222222u;
-    v8i f = {int((w << 1) & M), int(w & M), int((w >> 1) & M), int((w >> 2) & M), 0, 0, 0, 0};
+__device__ inline v8i widen_fp4_a(uint32_t w) {
+    v8i f = {int(w & 0x11111111u), int(w & 0x22222222u), int(w & 0x44444444u), int((w >> 2) & 0x22222222u),
+             0, 0, 0, 0};
+    return f;
+}
+
+__device__ inline v8i widen_fp4_b(uint32_t w) {
+    const uint32_t r = w >> 2;
+    v8i f = {int((w << 2) & 0x44444444u), int(w & 0x22222222u), int(r & 0x11111111u), int(r & 0x22222222u),
+             0, 0, 0, 0};
     return f;
 }
 
@@ -162,9 +173,9 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
             for (int s = 0; s < 4; ++s) {
                 v8i fa[WM], fb[WN];
 #pragma unroll
-                for (int i = 0; i < WM; ++i) fa[i] = widen_fp4(word_of(aw[i], s));
+                for (int i = 0; i < WM; ++i) fa[i] = widen_fp4_a(word_of(aw[i], s));
 #pragma unroll
-                for (int j = 0; j < WN; ++j) fb[j] = widen_fp4(word_of(bw[j], s));
+                for (int j = 0; j < WN; ++j) fb[j] = widen_fp4_b(word_of(bw[j], s));
 #pragma unroll
                 for (int i = 0; i < WM; ++i)
 #pragma unroll

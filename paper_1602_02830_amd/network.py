@@ -35,12 +35,13 @@ class BinaryMLP:
     """
 
     def __init__(self, weights_real, bns, eps: float, batch: int, keep_preacts: bool = True,
-                 fused: bool = False):
+                 fused: bool = False, kernel: int = B.KERNEL_AUTO):
         assert len(bns) == len(weights_real) - 1
         dev = weights_real[0].device
         self.device = dev
         self.batch = batch
         self.fused = fused          # hidden layers as one launch each; their int32 pre-activations are not produced
+        self.kernel = kernel        # GEMM kernel of the hidden layers (KERNEL_AUTO = the library's choice)
         self.K = [int(w.shape[1]) for w in weights_real]
         self.N = [int(w.shape[0]) for w in weights_real]
         self.w_bits = []
@@ -85,9 +86,10 @@ class BinaryMLP:
             hidden = l + 1 < n_layers
             if self.fused and hidden:
                 B.xnor_gemm_bn_sign_pack(self.a_bits[l], self.w_bits[l], self.K[l], self.thr[l], self.flip[l],
-                                         out=self.a_bits[l + 1])
+                                         out=self.a_bits[l + 1], kernel=self.kernel)
             else:
-                B.xnor_gemm(self.a_bits[l], self.w_bits[l], self.K[l], out=self.s[l])
+                B.xnor_gemm(self.a_bits[l], self.w_bits[l], self.K[l], out=self.s[l],
+                            kernel=self.kernel if hidden else B.KERNEL_AUTO)
             if timed:
                 end.record()
                 gemm_events[l].append((start, end))
@@ -103,8 +105,10 @@ class BinaryConvLayer:
     weight_real: float32 device tensor [Cout][kh][kw][Cin], binarized by Eq. (1) on the device.
     """
 
-    def __init__(self, weight_real, bn, eps: float, batch: int, H: int, W: int, stride: int = 1, pad: int = 1):
+    def __init__(self, weight_real, bn, eps: float, batch: int, H: int, W: int, stride: int = 1, pad: int = 1,
+                 fused: bool = False):
         dev = weight_real.device
+        self.fused = fused      # GEMM and BN+Sign in one launch; the int32 pre-activations are not produced
         self.Cout, self.kh, self.kw, self.Cin = (int(d) for d in weight_real.shape)
         self.stride, self.pad = stride, pad
         self.B, self.H, self.W = batch, H, W
@@ -122,12 +126,15 @@ class BinaryConvLayer:
         self.thr = torch.from_numpy(thr).to(dev)
         self.flip = torch.from_numpy(flip.view(np.int32)).to(dev)
         self.cols = _packed_buffer(self.M, self.K, dev)
-        self.s = torch.empty((self.M, self.Cout), dtype=torch.int32, device=dev)
+        self.s = None if fused else torch.empty((self.M, self.Cout), dtype=torch.int32, device=dev)
         self.out_bits = torch.empty((self.M, B.words_per_row(self.Cout)), dtype=torch.int32, device=dev)
 
     def forward(self, x_bits: torch.Tensor) -> torch.Tensor:
         """x_bits: packed NHWC int32 [B][H][W][Cin/32].  Returns packed NHWC [B][Ho][Wo][ceil(Cout/32)]."""
         B.conv_im2col_pack(x_bits, self.Cin, self.kh, self.kw, self.stride, self.pad, out=self.cols)
-        B.xnor_gemm(self.cols, self.w_bits, self.K, out=self.s)
-        B.bn_sign_pack(self.s, self.thr, self.flip, out=self.out_bits)
+        if self.fused:
+            B.xnor_gemm_bn_sign_pack(self.cols, self.w_bits, self.K, self.thr, self.flip, out=self.out_bits)
+        else:
+            B.xnor_gemm(self.cols, self.w_bits, self.K, out=self.s)
+            B.bn_sign_pack(self.s, self.thr, self.flip, out=self.out_bits)
         return self.out_bits.view(self.B, self.Ho, self.Wo, -1)

@@ -324,18 +324,20 @@ def test_conv_layers_end_to_end_small_batch():
         assert (words_to_host(out.reshape(-1, out.shape[-1])) == oracle.pack_bits(a_want.reshape(-1, C))).all()
 
 
-def test_conv_layers_full_batch_sampled_images():
+@pytest.mark.parametrize("fused", [False, True])
+def test_conv_layers_full_batch_sampled_images(fused):
     """Batch 256 as benchmarked; the oracle checks a sample of whole images (images are independent)."""
     for layer in range(3):
-        x, Wt, bn = synth.config_conv(layer)
+        x, Wt, bn = synth.config_conv(layer, adversarial=fused)
         B, H, W, C = x.shape
-        conv = bnn.BinaryConvLayer(torch.from_numpy(Wt.astype(np.float32)).to(DEV), bn, EPS, B, H, W)
+        conv = bnn.BinaryConvLayer(torch.from_numpy(Wt.astype(np.float32)).to(DEV), bn, EPS, B, H, W, fused=fused)
         xb = words_to_dev(_pack_nhwc(x).reshape(-1, C // 32)).view(B, H, W, C // 32)
         out = words_to_host(conv.forward(xb).reshape(B, H * W, -1))
-        s = conv.s.cpu().numpy().reshape(B, H, W, C)
+        s = None if fused else conv.s.cpu().numpy().reshape(B, H, W, C)
         for img in (0, 101, 255):
             S_want, a_want = oracle.conv_layer(x[img:img + 1], Wt, bn, eps=EPS)
-            assert (s[img] == S_want[0]).all()
+            if not fused:
+                assert (s[img] == S_want[0]).all()
             assert (out[img] == oracle.pack_bits(a_want.reshape(-1, C))).all()
 
 
