@@ -35,6 +35,9 @@ PEAK_BINARY_TOPS = PEAK_LANE_OPS / 2 * 64 / 1e12          # ~1258.3
 PEAK_HBM_GBS = 8000.0
 PEAK_I8_MFMA_TOPS = 5000.0                                # dense int8, 2*M*N*K counting
 PEAK_FP4_MFMA_TFLOPS = 10100.0                            # dense fp4/fp6 MFMA, 2*M*N*K counting
+# HBM bytes per launch of the dominant kernel (fetched + written), from the FETCH_SIZE / WRITE_SIZE counter
+# runs summarised in profiles/xnor_gemm_mfma_mlp_batch10000.txt and profiles/xnor_gemm_tiled128_mlp_batch10000.txt.
+PROFILED_TRAFFIC_BYTES = {("mfma", True): 23.2e6 + 13.0e6, ("valu", False): 32.9e6 + 166.4e6}
 
 
 def log(*a):
@@ -177,16 +180,17 @@ def main():
     }
     kname = ("xnor_gemm_tiled_kernel<8,8,16>" if args.valu else "xnor_gemm_mfma_kernel<4,2>") + \
             (" + fused BN+Sign epilogue" if fused else "") + " M=10000 N=4096 K=4096"
+    traffic = PROFILED_TRAFFIC_BYTES.get(("valu" if args.valu else "mfma", fused))
     if args.valu:
         result["roofline"] = {
             "bound": "alu", "kernel": kname, "achieved": achieved_tops, "peak": PEAK_BINARY_TOPS,
             "unit": "binary TOP/s (2*M*N*K/s; peak = 256 CU x 64 lanes x 2.4 GHz / 2 lane-ops per word x 64)",
-            "frac": achieved_tops / PEAK_BINARY_TOPS, "avg_launch_ms": gemm_ms, "traffic": None}
+            "frac": achieved_tops / PEAK_BINARY_TOPS, "avg_launch_ms": gemm_ms, "traffic": traffic}
     else:
         result["roofline"] = {
             "bound": "mfma", "kernel": kname, "achieved": achieved_tops, "peak": PEAK_FP4_MFMA_TFLOPS,
             "unit": "TFLOP/s (fp4 MFMA, 2*M*N*K per launch)",
-            "frac": achieved_tops / PEAK_FP4_MFMA_TFLOPS, "avg_launch_ms": gemm_ms, "traffic": None}
+            "frac": achieved_tops / PEAK_FP4_MFMA_TFLOPS, "avg_launch_ms": gemm_ms, "traffic": traffic}
 
     if args.calibration_copy:
         src = torch.zeros(256 * 1024 * 1024, dtype=torch.int32, device=dev)      # 1 GiB read + 1 GiB written
