@@ -155,6 +155,35 @@ int bnn_xnor_gemm_bn_sign_pack_kernel(const uint32_t *A, int64_t lda, const uint
                                       int kernel_id, void *stream);
 
 /*
+ * First layer on 8-bit fixed-point inputs (Sec. 1.6; Alg. 4 step 1):
+ *     a_1 = sum_{n=1..8} 2^(n-1) * <a_0^n, W^b_1>,   a_0^n in {0,1} the n-th bit plane.
+ *
+ * bnn_pack_bitplanes splits uint8 inputs into packed bit planes:
+ *   out[r][8*w + p] bit j = bit p (p = 0 least significant, the paper's n = p+1) of x[r][32*w + j]
+ *   x   [rows][ld_x] uint8, ld_x >= cols
+ *   out [rows][ld_out] uint32, ld_out >= 8*ceil(cols/32); elements >= cols read as 0; words beyond
+ *       8*ceil(cols/32) untouched.  Fast path when x is 4-byte aligned and ld_x % 4 == 0.
+ *
+ * bnn_bitplane_gemm:  C[m][n] = sum_k x[m][k] * w[n][k],  x in [0,255] given as bit planes (layout
+ *   above, Xp [M][ldx], ldx >= 8*ceil(K/32)), w in {-1,+1} given as packed rows B [N][ldb] as in
+ *   bnn_xnor_gemm; C [M][ldc] int32.  Computed plane by plane on the matrix engine with the plane
+ *   weight 2^(n-1) as block scale; exact while 255*K < 2^24, larger K gives BNN_ERR_UNSUPPORTED.
+ *   Pad bits of the last K-word of either operand are ignored.
+ *
+ * bnn_bitplane_gemm_bn_sign_pack: the same product followed by Sign(BatchNorm(a_1, theta_1)) on
+ *   folded thresholds (bnn_bn_fold with 255*K as the range argument), written as packed bits:
+ *   out[m][n/32] bit (n%32) = (C[m][n] >= thr[n]) XOR flip[n]; out as in bnn_bn_sign_pack.
+ */
+int bnn_pack_bitplanes(const uint8_t *x, int64_t rows, int64_t cols, int64_t ld_x,
+                       uint32_t *out, int64_t ld_out, void *stream);
+int bnn_bitplane_gemm(const uint32_t *Xp, int64_t ldx, const uint32_t *B, int64_t ldb,
+                      int32_t *C, int64_t ldc, int64_t M, int64_t N, int64_t K, void *stream);
+int bnn_bitplane_gemm_bn_sign_pack(const uint32_t *Xp, int64_t ldx, const uint32_t *B, int64_t ldb,
+                                   int64_t M, int64_t N, int64_t K, const int32_t *thr,
+                                   const uint32_t *flip_bits, uint32_t *out, int64_t ld_out,
+                                   void *stream);
+
+/*
  * Lowers a binary kh x kw convolution (3 x 3 in the paper's nets, Sec. 3.3) to
  * the matrix product above: row m = (b*Ho + oy)*Wo + ox of `out` holds the
  * receptive field of output pixel (b, oy, ox) as K = kh*kw*Cin bits,

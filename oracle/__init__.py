@@ -20,6 +20,7 @@ from .bnn_oracle import (  # noqa: F401
     first_layer_bitplanes,
     dense_layer,
     mlp_forward,
+    mlp_forward_uint8,
     conv_layer,
     EPS_DEFAULT,
 )

@@ -210,6 +210,22 @@ def mlp_forward(x_real, weights, bns, eps=EPS_DEFAULT):
     return trace
 
 
+def mlp_forward_uint8(x_u8, weights, bns, eps=EPS_DEFAULT):
+    """Alg. 4 as printed: 8-bit inputs, first layer as the sum over bit planes weighted 2^(n-1)
+    (step 1), hidden layers XnorDotProduct -> Sign(BatchNorm) (step 2), last layer's int32
+    pre-activations.  Same return structure as mlp_forward; a[0] is the raw uint8 input."""
+    assert len(bns) == len(weights) - 1
+    trace = {"a": [np.asarray(x_u8)], "s": []}
+    a = None
+    for l, Wb in enumerate(weights):
+        s = first_layer_bitplanes(x_u8, Wb) if l == 0 else matmul_pm1(a, Wb)
+        trace["s"].append(s)
+        if l < len(bns):
+            a = bn_sign(s, *bns[l], eps=eps)
+            trace["a"].append(a)
+    return trace
+
+
 def conv_layer(x_b, Wt, bn, stride=1, pad=1, eps=EPS_DEFAULT):
     """Binary conv layer: direct convolution, then Sign(BatchNorm) per output channel.
 

@@ -18,6 +18,9 @@ from .binding import (  # noqa: F401
     bn_sign_pack,
     xnor_gemm_bn_sign_pack,
     conv_im2col_pack,
+    pack_bitplanes,
+    bitplane_gemm,
+    bitplane_gemm_bn_sign_pack,
     gemm_i8_mfma,
     unpack_i8,
     KERNEL_AUTO,

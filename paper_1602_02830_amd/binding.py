@@ -33,6 +33,9 @@ _SIGNATURES = {
     "bnn_xnor_gemm_bn_sign_pack": (_int, [_ptr, _i64, _ptr, _i64, _i64, _i64, _i64, _ptr, _ptr, _ptr, _i64, _ptr]),
     "bnn_xnor_gemm_bn_sign_pack_kernel": (_int, [_ptr, _i64, _ptr, _i64, _i64, _i64, _i64, _ptr, _ptr, _ptr, _i64,
                                                  _int, _ptr]),
+    "bnn_pack_bitplanes": (_int, [_ptr, _i64, _i64, _i64, _ptr, _i64, _ptr]),
+    "bnn_bitplane_gemm": (_int, [_ptr, _i64, _ptr, _i64, _ptr, _i64, _i64, _i64, _i64, _ptr]),
+    "bnn_bitplane_gemm_bn_sign_pack": (_int, [_ptr, _i64, _ptr, _i64, _i64, _i64, _i64, _ptr, _ptr, _ptr, _i64, _ptr]),
     "bnn_bn_fold": (_int, [_ptr, _ptr, _ptr, _ptr, _f32, _i64, _i64, _ptr, _ptr]),
     "bnn_bn_sign_pack": (_int, [_ptr, _i64, _i64, _i64, _ptr, _ptr, _ptr, _i64, _ptr]),
     "bnn_conv_im2col_pack": (_int, [_ptr, _i64, _i64, _i64, _i64, _int, _int, _int, _int, _ptr, _i64, _ptr]),
@@ -214,6 +217,56 @@ def xnor_gemm_bn_sign_pack(A: torch.Tensor, B: torch.Tensor, K: int, thr: torch.
                                                    thr.data_ptr(), flip_bits.data_ptr(), out.data_ptr(),
                                                    _ld(out), kernel, _stream())
     _check("bnn_xnor_gemm_bn_sign_pack", st)
+    return out
+
+
+def pack_bitplanes(x: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """bnn_pack_bitplanes: uint8 [rows][cols] -> packed planes int32 [rows][8*ceil(cols/32)] (word 8*w + p)."""
+    lib = load_library()
+    _dev(x, torch.uint8, "x")
+    rows, cols = x.shape
+    kw8 = 8 * words_per_row(cols)
+    if out is None:
+        out = torch.empty((rows, kw8), dtype=torch.int32, device=x.device)
+    _dev(out, torch.int32, "out")
+    _check("bnn_pack_bitplanes", lib.bnn_pack_bitplanes(x.data_ptr(), rows, cols, _ld(x), out.data_ptr(), _ld(out),
+                                                       _stream()))
+    return out
+
+
+def bitplane_gemm(Xp: torch.Tensor, B: torch.Tensor, K: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """bnn_bitplane_gemm: bit planes Xp [M][8*Kw], packed +-1 rows B [N][Kw] -> int32 [M][N] = x @ w^T."""
+    lib = load_library()
+    _dev(Xp, torch.int32, "Xp")
+    _dev(B, torch.int32, "B")
+    M, N = Xp.shape[0], B.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=Xp.device)
+    _dev(out, torch.int32, "out")
+    _check("bnn_bitplane_gemm", lib.bnn_bitplane_gemm(Xp.data_ptr(), _ld(Xp), B.data_ptr(), _ld(B), out.data_ptr(),
+                                                     _ld(out), M, N, K, _stream()))
+    return out
+
+
+def bitplane_gemm_bn_sign_pack(Xp: torch.Tensor, B: torch.Tensor, K: int, thr: torch.Tensor, flip_bits: torch.Tensor,
+                               out: torch.Tensor | None = None, ld_out: int | None = None) -> torch.Tensor:
+    """bnn_bitplane_gemm_bn_sign_pack: first layer on 8-bit inputs, fused with Sign(BatchNorm)."""
+    lib = load_library()
+    _dev(Xp, torch.int32, "Xp")
+    _dev(B, torch.int32, "B")
+    M, N = Xp.shape[0], B.shape[0]
+    nw = words_per_row(N)
+    if thr.dtype != torch.int32 or flip_bits.dtype != torch.int32 or not thr.is_cuda or not flip_bits.is_cuda:
+        raise ValueError("thr and flip_bits must be int32 device tensors")
+    if thr.numel() != N or flip_bits.numel() != nw or not thr.is_contiguous() or not flip_bits.is_contiguous():
+        raise ValueError("thr must be [N] and flip_bits [ceil(N/32)], contiguous")
+    if out is None:
+        out = _alloc_words(M, nw, Xp.device, ld_out)
+    _dev(out, torch.int32, "out")
+    _check("bnn_bitplane_gemm_bn_sign_pack",
+           lib.bnn_bitplane_gemm_bn_sign_pack(Xp.data_ptr(), _ld(Xp), B.data_ptr(), _ld(B), M, N, K,
+                                              thr.data_ptr(), flip_bits.data_ptr(), out.data_ptr(), _ld(out),
+                                              _stream()))
     return out
 
 

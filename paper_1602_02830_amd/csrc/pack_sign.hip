@@ -62,7 +62,70 @@ __global__ __launch_bounds__(kPackThreads) void pack_sign_kernel(
     }
 }
 
+// ----------------------------------------------------------------------------
+// bnn_pack_bitplanes: 8-bit inputs of the first layer (Sec. 1.6, Alg. 4 step 1) as eight
+// packed bit planes.  out[r][8*w + p] holds bit p of x[r][32*w .. 32*w + 31].
+//
+// Same split as the Sign packer: 8 lanes per 32 elements, 4 bytes per lane.  For plane p the
+// lane's four bits sit at bit p of each byte; a multiply gathers them into a nibble
+// ((d >> p) & 0x01010101) * 0x10204080 >> 28, the group ORs the shifted nibbles, and lane p
+// of the group keeps plane p, so the group's store is 32 contiguous bytes.
+// ----------------------------------------------------------------------------
+template <bool VEC>
+__global__ __launch_bounds__(kPackThreads) void pack_bitplanes_kernel(
+    const uint8_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ld_x,
+    uint32_t* __restrict__ out, int64_t ld_out, int64_t kw, int64_t n_groups) {
+    const int q = threadIdx.x & 7;
+    const int64_t groups_per_pass = int64_t(gridDim.x) * (kPackThreads / 8);
+    for (int64_t g = int64_t(blockIdx.x) * (kPackThreads / 8) + (threadIdx.x >> 3); g < n_groups;
+         g += groups_per_pass) {
+        const int64_t row = g / kw;
+        const int64_t w = g - row * kw;
+        const int64_t c0 = w * 32 + q * 4;
+        const uint8_t* p = x + row * ld_x + c0;
+        uint32_t d = 0u;                                  // out-of-range elements read as 0: all planes 0
+        if (VEC && c0 + 3 < cols) {
+            d = *reinterpret_cast<const uint32_t*>(p);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (c0 + e < cols) d |= uint32_t(p[e]) << (8 * e);
+        }
+        uint32_t mine = 0u;
+#pragma unroll
+        for (int pl = 0; pl < 8; ++pl) {
+            const uint32_t nib = (((d >> pl) & 0x01010101u) * 0x10204080u) >> 28;
+            const uint32_t word = or_reduce8(nib << (4 * q));
+            if (q == pl) mine = word;
+        }
+        out[row * ld_out + 8 * w + q] = mine;
+    }
+}
+
 }  // namespace bnn
+
+extern "C" int bnn_pack_bitplanes(const uint8_t* x, int64_t rows, int64_t cols, int64_t ld_x, uint32_t* out,
+                                  int64_t ld_out, void* stream) {
+    using namespace bnn;
+    if (rows < 0 || cols < 0 || rows > kMaxDim || cols > kMaxDim) return BNN_ERR_INVALID_ARG;
+    const int64_t kw = ceil_div(cols, 32);
+    if (ld_x < cols || ld_out < 8 * kw) return BNN_ERR_INVALID_ARG;
+    if (rows == 0 || cols == 0) return BNN_OK;
+    if (!x || !out) return BNN_ERR_INVALID_ARG;
+    if (!aligned_to(out, 4)) return BNN_ERR_ALIGNMENT;
+    const int64_t n_groups = rows * kw;
+    int64_t blocks = ceil_div(n_groups, kPackThreads / 8);
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    const bool vec = aligned_to(x, 4) && (ld_x % 4 == 0);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (vec)
+        hipLaunchKernelGGL(pack_bitplanes_kernel<true>, dim3(unsigned(blocks)), dim3(kPackThreads), 0, s, x, rows,
+                           cols, ld_x, out, ld_out, kw, n_groups);
+    else
+        hipLaunchKernelGGL(pack_bitplanes_kernel<false>, dim3(unsigned(blocks)), dim3(kPackThreads), 0, s, x, rows,
+                           cols, ld_x, out, ld_out, kw, n_groups);
+    return check_launch();
+}
 
 extern "C" int bnn_pack_sign(const float* x, int64_t rows, int64_t cols, int64_t ld_x,
                              uint32_t* out, int64_t ld_out, void* stream) {

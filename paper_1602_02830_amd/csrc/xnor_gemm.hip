@@ -284,6 +284,11 @@ int launch_xnor_gemm_mfma(const uint32_t* A, int64_t lda, const uint32_t* B, int
                           int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream);
 int launch_xnor_gemm_mfma_fused(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M,
                                 int64_t N, int64_t K, BnSignArgs bn, void* stream);
+bool mfma_planes_path_supports(int64_t K);
+int launch_bitplane_gemm_mfma(const uint32_t* Xp, int64_t ldx, const uint32_t* B, int64_t ldb, int32_t* C,
+                              int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream);
+int launch_bitplane_gemm_mfma_fused(const uint32_t* Xp, int64_t ldx, const uint32_t* B, int64_t ldb, int64_t M,
+                                    int64_t N, int64_t K, BnSignArgs bn, void* stream);
 
 template <int TM, int TN, int KT, bool FUSED>
 static void launch_tiled(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
@@ -390,7 +395,46 @@ static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const
     return check_launch();
 }
 
+// First layer on 8-bit inputs (Alg. 4 step 1): argument checks shared by the plain and fused calls.
+static int bitplane_gemm_check(const uint32_t* Xp, int64_t ldx, const uint32_t* B, int64_t ldb, int64_t M,
+                               int64_t N, int64_t K) {
+    if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return BNN_ERR_INVALID_ARG;
+    const int64_t kw = ceil_div(K, 32);
+    if (ldx < 8 * kw || ldb < kw) return BNN_ERR_INVALID_ARG;
+    if (M > 0 && N > 0 && K > 0 && (!Xp || !B)) return BNN_ERR_INVALID_ARG;
+    if (!aligned_to(Xp, 4) || !aligned_to(B, 4)) return BNN_ERR_ALIGNMENT;
+    if (!mfma_planes_path_supports(K)) return BNN_ERR_UNSUPPORTED;
+    return BNN_OK;
+}
+
 }  // namespace bnn
+
+extern "C" int bnn_bitplane_gemm(const uint32_t* Xp, int64_t ldx, const uint32_t* B, int64_t ldb, int32_t* C,
+                                 int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream) {
+    using namespace bnn;
+    const int st = bitplane_gemm_check(Xp, ldx, B, ldb, M, N, K);
+    if (st != BNN_OK) return st;
+    if (ldc < N) return BNN_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return BNN_OK;
+    if (!C) return BNN_ERR_INVALID_ARG;
+    if (!aligned_to(C, 4)) return BNN_ERR_ALIGNMENT;
+    return launch_bitplane_gemm_mfma(Xp, ldx, B, ldb, C, ldc, M, N, K, stream);
+}
+
+extern "C" int bnn_bitplane_gemm_bn_sign_pack(const uint32_t* Xp, int64_t ldx, const uint32_t* B, int64_t ldb,
+                                              int64_t M, int64_t N, int64_t K, const int32_t* thr,
+                                              const uint32_t* flip_bits, uint32_t* out, int64_t ld_out,
+                                              void* stream) {
+    using namespace bnn;
+    const int st = bitplane_gemm_check(Xp, ldx, B, ldb, M, N, K);
+    if (st != BNN_OK) return st;
+    if (ld_out < ceil_div(N, 32)) return BNN_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return BNN_OK;
+    if (!thr || !flip_bits || !out) return BNN_ERR_INVALID_ARG;
+    if (!aligned_to(thr, 4) || !aligned_to(flip_bits, 4) || !aligned_to(out, 4)) return BNN_ERR_ALIGNMENT;
+    return launch_bitplane_gemm_mfma_fused(Xp, ldx, B, ldb, M, N, K, BnSignArgs{thr, flip_bits, out, ld_out},
+                                           stream);
+}
 
 extern "C" int bnn_xnor_gemm_bn_sign_pack(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb,
                                           int64_t M, int64_t N, int64_t K, const int32_t* thr,

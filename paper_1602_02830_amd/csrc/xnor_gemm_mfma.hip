@@ -1,31 +1,41 @@
-// Bits-in, matrix-engine-inside variant of the binary product of Sec. 4 / Alg. 4.
+// Bits-in, matrix-engine-inside kernels for the products of Alg. 4:
 //
-// Operands stay packed 32 per word in HBM and LDS (the 32x smaller footprint
-// the paper argues for); only inside registers is each bit widened to a 4-bit
-// float (E2M1: code 0b0010 = 1.0, 0b0000 = 0.0) and fed to
-// v_mfma_scale_f32_32x32x64_f8f6f4, whose fp32 accumulation of 0/1 products is
-// exact for K < 2^24.  With a, b in {0,1} standing for -1/+1:
+//   binary  (PLANES = false)  a_k = XnorDotProduct(a^b_{k-1}, W^b_k), Sec. 4 Eq. (5)
+//   planes  (PLANES = true)   a_1 = sum_{n=1..8} 2^(n-1) * <a_0^n, W^b_1>, Alg. 4 step 1 /
+//                             Sec. 1.6: 8-bit inputs as eight bit planes a_0^n in {0,1}
 //
-//   sum_k (2a-1)(2b-1) = K - 2*popcount(A_m) - 2*popcount(B_n) + 4 * sum_k a*b
+// Operands stay packed 32 per word in HBM and LDS (the 32x smaller footprint the
+// paper argues for); only inside registers is each bit widened to a 4-bit float
+// and fed to v_mfma_scale_f32_32x32x64_f8f6f4, whose fp32 accumulation of small
+// integers is exact below 2^24.  With a, b in {0,1} standing for -1/+1:
 //
-// so the +-1 product of Eq. (5) is the matrix-engine sum S plus per-row and
-// per-column popcounts, which the staging threads gather for free while they
-// copy the tile.  Pad bits and rows outside the matrix are zeroed at staging
-// and therefore contribute to neither S nor the popcounts.
+//   binary:  sum_k (2a-1)(2b-1) = K - 2*popcount(A_m) - 2*popcount(B_n) + 4 * sum_k a*b
+//   planes:  sum_n 2^(n-1) sum_k x^n (2b-1) = 2 * sum_n 2^(n-1) sum_k x^n b  -  sum_k x[m][k]
+//
+// so each product is the matrix-engine sum S plus row (and column) popcounts, which
+// the staging threads gather for free while they copy the tile.  In the planes
+// kernel the weight 2^(n-1) is the MFMA's block scale of the A operand (E8M0
+// exponent 127 + n - 1), so all eight planes accumulate into the same registers.
+// Pad bits and rows outside the matrix are zeroed at staging and therefore
+// contribute to neither S nor the popcounts.
 //
 // Widening: element k of a word lands in operand register k%4, nibble k/4, for
 // both operands (the sum over k does not depend on its order).  The E2M1 codes
 // 0b0001, 0b0010, 0b0100 are 0.5, 1.0, 2.0, so most registers are a bare mask of
 // the word and only the product of the two sides has to be 1:
-//   register   0               1             2               3
-//   A side     w & 0x1111.. (0.5)  w & 0x2222.. (1)  w & 0x4444.. (2)  (w>>2) & 0x2222.. (1)
-//   B side     (w<<2) & 0x4444.. (2)  w & 0x2222.. (1)  (w>>2) & 0x1111.. (0.5)  (w>>2) & 0x2222.. (1)
+//   register   0                      1                  2                        3
+//   A side     w & 0x1111.. (0.5)     w & 0x2222.. (1)   w & 0x4444.. (2)         (w>>2) & 0x2222.. (1)
+//   B side     (w<<2) & 0x4444.. (2)  w & 0x2222.. (1)   (w>>2) & 0x1111.. (0.5)  (w>>2) & 0x2222.. (1)
 // i.e. 5 vector-ALU operations per 32 elements on the A side, 6 on the B side.
 //
 // Workgroup = 256 threads = 2 x 2 wavefronts; a wavefront owns WM x WN blocks
-// of 32 x 32 outputs (fp32 accumulators).  K advances 16 words (512 bits) per
-// staged tile = 8 MFMA steps of 64 bits: lane (row r = l%32, half h = l/32) of
-// a fragment owns words [8h, 8h+8) of its row, read with two ds_read_b128.
+// of 32 x 32 outputs (fp32 accumulators).  A advances 16 words per staged tile =
+// 8 MFMA steps: lane (row r = l%32, half h = l/32) of a fragment owns words
+// [8h, 8h+8) of its tile row, read with two ds_read_b128.
+//   binary: those 16 words are 512 consecutive bits of K; B is staged the same way.
+//   planes: A rows are [K/32 words][8 planes] (word index 8*w + p), so a tile is two
+//           K-words x 8 planes, lane half h owns K-word 2*kt + h, step s is plane s;
+//           B contributes one word per lane half and tile, widened once per tile.
 // The tile is long enough that the global loads of the next tile, issued
 // before the MFMA steps, have landed when they are staged.
 #include "bnn_internal.h"
@@ -36,10 +46,9 @@ namespace bnn {
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-constexpr int kMfmaKT = 16;         // words of K per staged tile
-constexpr int kMfmaKQ = kMfmaKT / 4;  // 16-byte quads per row per tile
-constexpr int kMfmaSteps = kMfmaKT / 2;  // MFMA steps per tile (each consumes one word from each lane half)
-constexpr int64_t kMfmaMaxK = int64_t(1) << 24;   // exact fp32 accumulation of 0/1 products
+constexpr int kMfmaKT = 16;              // words of A per row and staged tile
+constexpr int kMfmaKQ = kMfmaKT / 4;     // 16-byte quads per row per tile
+constexpr int64_t kMfmaMaxAcc = int64_t(1) << 24;   // exact fp32 accumulation of non-negative integers
 
 __device__ inline v8i widen_fp4_a(uint32_t w) {
     v8i f = {int(w & 0x11111111u), int(w & 0x22222222u), int(w & 0x44444444u), int((w >> 2) & 0x22222222u),
@@ -56,18 +65,29 @@ __device__ inline v8i widen_fp4_b(uint32_t w) {
 
 __device__ inline int popc4(uint4 v) { return __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w); }
 
-template <int WM, int WN, bool VEC, bool FUSED>
+// Sum over k of the four plane words of a quad weighted 2^p0 .. 2^(p0+3).
+__device__ inline int popc4_weighted(uint4 v, int p0) {
+    return (__popc(v.x) + 2 * __popc(v.y) + 4 * __popc(v.z) + 8 * __popc(v.w)) << p0;
+}
+
+__device__ inline uint32_t quad_word(const uint4& q, int s) { return s == 0 ? q.x : s == 1 ? q.y : s == 2 ? q.z : q.w; }
+
+template <int WM, int WN, bool VEC, bool FUSED, bool PLANES>
 __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
     const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B, int64_t ldb,
     int32_t* __restrict__ C, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n, BnSignArgs bn) {
     constexpr int BM = 64 * WM, BN = 64 * WN;          // 2 x 2 wavefronts
     constexpr int PLANE_A = BM + 2, PLANE_B = BN + 2;  // 16-byte slots per quad plane (2 pad slots)
     constexpr int ST_ROWS = 256 / kMfmaKQ;             // rows covered by one staging pass
-    constexpr int LOADS_A = BM / ST_ROWS, LOADS_B = BN / ST_ROWS;
+    constexpr int LOADS_A = BM / ST_ROWS;
+    constexpr int LOADS_B = PLANES ? 0 : BN / ST_ROWS;
+    constexpr int NB = PLANES ? 1 : LOADS_B;           // array extent (arrays of length 0 are not allowed)
     static_assert(BM % ST_ROWS == 0 && BN % ST_ROWS == 0, "tile rows must divide among the staging threads");
     static_assert(kMfmaKQ == 4, "the row-popcount reduction below assumes 4 staging lanes per row");
+    static_assert(!PLANES || BN * 2 == 256, "the planes kernel stages one B word per thread");
     __shared__ uint4 lds_a[2][kMfmaKQ * PLANE_A];
-    __shared__ uint4 lds_b[2][kMfmaKQ * PLANE_B];
+    __shared__ uint4 lds_b[PLANES ? 1 : 2][PLANES ? 1 : kMfmaKQ * PLANE_B];
+    __shared__ uint32_t lds_bw[PLANES ? 2 : 1][PLANES ? 2 * BN : 1];     // planes: [buf][half][row]
     __shared__ __attribute__((aligned(16))) int pop_a[BM];
     __shared__ __attribute__((aligned(16))) int pop_b[BN];
 
@@ -79,64 +99,105 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int fr = lane & 31, fh = lane >> 5;
-    const int kw = (K + 31) >> 5;
+    const int kw = (K + 31) >> 5;                      // words of K per B row (and per plane of A)
+    const int kwa = PLANES ? 8 * kw : kw;              // words per A row
     const uint32_t tmask = tail_mask(K);
-    const int n_ktiles = (kw + kMfmaKT - 1) / kMfmaKT;
+    const int n_ktiles = (kwa + kMfmaKT - 1) / kMfmaKT;
+    // K-tiles made only of complete, unmasked words take branch-free loads (row index clamped
+    // into the matrix, result zeroed at staging if the row does not exist); the last, partial
+    // K-tile goes through checked, masking loads.
+    const int n_full_ktiles = PLANES ? (K >> 5) / 2 : (K >> 5) / kMfmaKT;
 
     const int st_q = tid % kMfmaKQ, st_r = tid / kMfmaKQ;
-    // Complete K-tiles take branch-free loads (row clamped into the matrix, zeroed at staging
-    // if it does not exist); the last, partial K-tile goes through the checked, masking loader.
-    const int n_full_ktiles = (K >> 5) / kMfmaKT;
     const uint32_t* pa[LOADS_A];
-    const uint32_t* pb[LOADS_B];
-    bool live_a[LOADS_A], live_b[LOADS_B];
+    bool live_a[LOADS_A];
 #pragma unroll
     for (int l = 0; l < LOADS_A; ++l) {
         const int r = row0 + st_r + l * ST_ROWS;
         live_a[l] = r < M;
         pa[l] = A + int64_t(min(r, M - 1)) * lda;
     }
+    // binary: B rows staged like A.  planes: thread t stages word (2*kt + t/BN) of B row col0 + t%BN.
+    const uint32_t* pb[NB];
+    bool live_b[NB];
+    const int bw_h = tid / BN, bw_r = tid % BN;
+    if (PLANES) {
+        live_b[0] = col0 + bw_r < N;
+        pb[0] = B + int64_t(min(col0 + bw_r, N - 1)) * ldb;
+    } else {
 #pragma unroll
-    for (int l = 0; l < LOADS_B; ++l) {
-        const int r = col0 + st_r + l * ST_ROWS;
-        live_b[l] = r < N;
-        pb[l] = B + int64_t(min(r, N - 1)) * ldb;
+        for (int l = 0; l < LOADS_B; ++l) {
+            const int r = col0 + st_r + l * ST_ROWS;
+            live_b[l] = r < N;
+            pb[l] = B + int64_t(min(r, N - 1)) * ldb;
+        }
     }
-    uint4 ra[LOADS_A], rb[LOADS_B];
-    int cnt_a[LOADS_A], cnt_b[LOADS_B];
+
+    uint4 ra[LOADS_A], rb[NB];
+    uint32_t rbw = 0u;
+    int cnt_a[LOADS_A], cnt_b[NB];
 #pragma unroll
     for (int l = 0; l < LOADS_A; ++l) cnt_a[l] = 0;
 #pragma unroll
-    for (int l = 0; l < LOADS_B; ++l) cnt_b[l] = 0;
+    for (int l = 0; l < NB; ++l) cnt_b[l] = 0;
+
+    // Checked load of an A quad in the planes layout: every plane word of the last K-word is masked.
+    auto load_quad_planes = [&](int row, int quad) {
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        const int w0 = quad * 4;
+        if (row < M && w0 < kwa) {                      // kwa is a multiple of 8: the quad is complete
+            const uint32_t* p = A + int64_t(row) * lda + w0;
+            v = VEC ? *reinterpret_cast<const uint4*>(p) : make_uint4(p[0], p[1], p[2], p[3]);
+            if ((w0 >> 3) == kw - 1) { v.x &= tmask; v.y &= tmask; v.z &= tmask; v.w &= tmask; }
+        }
+        return v;
+    };
     auto fetch = [&](int kt) {
         const int quad = kt * kMfmaKQ + st_q;
         if (kt < n_full_ktiles) {
 #pragma unroll
             for (int l = 0; l < LOADS_A; ++l) ra[l] = load_quad_unchecked<VEC>(pa[l], quad);
+            if (PLANES) {
+                rbw = pb[0][2 * kt + bw_h];
+            } else {
 #pragma unroll
-            for (int l = 0; l < LOADS_B; ++l) rb[l] = load_quad_unchecked<VEC>(pb[l], quad);
+                for (int l = 0; l < LOADS_B; ++l) rb[l] = load_quad_unchecked<VEC>(pb[l], quad);
+            }
         } else {
 #pragma unroll
-            for (int l = 0; l < LOADS_A; ++l)
-                ra[l] = load_quad<VEC>(A, lda, M, kw, tmask, row0 + st_r + l * ST_ROWS, quad);
+            for (int l = 0; l < LOADS_A; ++l) {
+                const int r = row0 + st_r + l * ST_ROWS;
+                if (PLANES) ra[l] = load_quad_planes(r, quad);
+                else ra[l] = load_quad<VEC>(A, lda, M, kw, tmask, r, quad);
+            }
+            if (PLANES) {
+                const int w = 2 * kt + bw_h;
+                rbw = w < kw ? pb[0][w] : 0u;
+                if (w == kw - 1) rbw &= tmask;
+            } else {
 #pragma unroll
-            for (int l = 0; l < LOADS_B; ++l)
-                rb[l] = load_quad<VEC>(B, ldb, N, kw, tmask, col0 + st_r + l * ST_ROWS, quad);
+                for (int l = 0; l < LOADS_B; ++l)
+                    rb[l] = load_quad<VEC>(B, ldb, N, kw, tmask, col0 + st_r + l * ST_ROWS, quad);
+            }
         }
     };
-    // Writes the fetched quads to LDS and adds their set bits to this thread's row popcounts.
+    // Writes the fetched words to LDS and adds their set bits to this thread's row sums.
     auto stage = [&](int buf) {
 #pragma unroll
         for (int l = 0; l < LOADS_A; ++l) {
             const uint4 v = zero_unless(live_a[l], ra[l]);
-            cnt_a[l] += popc4(v);
+            cnt_a[l] += PLANES ? popc4_weighted(v, 4 * (st_q & 1)) : popc4(v);
             lds_a[buf][st_q * PLANE_A + st_r + l * ST_ROWS] = v;
         }
+        if (PLANES) {
+            lds_bw[buf][bw_h * BN + bw_r] = live_b[0] ? rbw : 0u;
+        } else {
 #pragma unroll
-        for (int l = 0; l < LOADS_B; ++l) {
-            const uint4 v = zero_unless(live_b[l], rb[l]);
-            cnt_b[l] += popc4(v);
-            lds_b[buf][st_q * PLANE_B + st_r + l * ST_ROWS] = v;
+            for (int l = 0; l < LOADS_B; ++l) {
+                const uint4 v = zero_unless(live_b[l], rb[l]);
+                cnt_b[l] += popc4(v);
+                lds_b[buf][st_q * PLANE_B + st_r + l * ST_ROWS] = v;
+            }
         }
     };
 
@@ -155,33 +216,44 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
     __syncthreads();
 
     constexpr int kScaleOne = 0x7f7f7f7f;      // E8M0 exponent 127 = scale 1.0 in every byte
-    auto word_of = [](const uint4& q, int s) { return s == 0 ? q.x : s == 1 ? q.y : s == 2 ? q.z : q.w; };
 
     for (int kt = 0; kt < n_ktiles; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < n_ktiles) fetch(kt + 1);
 
+        v8i fb[WN];
+        if (PLANES) {
+#pragma unroll
+            for (int j = 0; j < WN; ++j) fb[j] = widen_fp4_b(lds_bw[buf][fh * BN + wn * 32 * WN + j * 32 + fr]);
+        }
         // The lane's 8 words are quads 2*fh and 2*fh+1 of its tile row; each quad feeds 4 steps.
 #pragma unroll
         for (int hq = 0; hq < 2; ++hq) {
             uint4 aw[WM], bw[WN];
 #pragma unroll
             for (int i = 0; i < WM; ++i) aw[i] = lds_a[buf][(2 * fh + hq) * PLANE_A + wm * 32 * WM + i * 32 + fr];
+            if (!PLANES) {
 #pragma unroll
-            for (int j = 0; j < WN; ++j) bw[j] = lds_b[buf][(2 * fh + hq) * PLANE_B + wn * 32 * WN + j * 32 + fr];
+                for (int j = 0; j < WN; ++j)
+                    bw[j] = lds_b[buf][(2 * fh + hq) * PLANE_B + wn * 32 * WN + j * 32 + fr];
+            }
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                v8i fa[WM], fb[WN];
+                v8i fa[WM];
 #pragma unroll
-                for (int i = 0; i < WM; ++i) fa[i] = widen_fp4_a(word_of(aw[i], s));
+                for (int i = 0; i < WM; ++i) fa[i] = widen_fp4_a(quad_word(aw[i], s));
+                if (!PLANES) {
 #pragma unroll
-                for (int j = 0; j < WN; ++j) fb[j] = widen_fp4_b(word_of(bw[j], s));
+                    for (int j = 0; j < WN; ++j) fb[j] = widen_fp4_b(quad_word(bw[j], s));
+                }
+                // planes: this step is plane 4*hq + s, weight 2^(4*hq + s) through the A block scale.
+                const int scale_a = PLANES ? kScaleOne + (4 * hq + s) * 0x01010101 : kScaleOne;
 #pragma unroll
                 for (int i = 0; i < WM; ++i)
 #pragma unroll
                     for (int j = 0; j < WN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                            fa[i], fb[j], acc[i][j], 4 /* A: fp4 */, 4 /* B: fp4 */, 0, kScaleOne, 0, kScaleOne);
+                            fa[i], fb[j], acc[i][j], 4 /* A: fp4 */, 4 /* B: fp4 */, 0, scale_a, 0, kScaleOne);
             }
         }
 
@@ -189,13 +261,14 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
         __syncthreads();
     }
 
-    // Row popcounts: the kMfmaKQ threads that staged the quads of one row are neighbouring lanes.
+    // Row sums: the kMfmaKQ threads that staged the quads of one row are neighbouring lanes.
+    // pop_a / pop_b hold 2*popcount (binary) or the plain row sum of the 8-bit inputs (planes).
 #pragma unroll
     for (int l = 0; l < LOADS_A; ++l) {
         int c = cnt_a[l];
         c += __builtin_amdgcn_update_dpp(0, c, 0xB1, 0xF, 0xF, true);       // lane ^ 1
         c += __builtin_amdgcn_update_dpp(0, c, 0x4E, 0xF, 0xF, true);       // lane ^ 2
-        if (st_q == 0) pop_a[st_r + l * ST_ROWS] = 2 * c;
+        if (st_q == 0) pop_a[st_r + l * ST_ROWS] = PLANES ? c : 2 * c;
     }
 #pragma unroll
     for (int l = 0; l < LOADS_B; ++l) {
@@ -206,14 +279,15 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
     }
     __syncthreads();
 
+    // Result from the matrix-engine sum S:  binary  K - 2pa - 2pb + 4S,   planes  2S - rowsum.
     // Accumulator register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32 of its 32x32 block.
-    // pop_a / pop_b hold twice the popcounts from here on.
+    constexpr int kShift = PLANES ? 1 : 2;
     if (!FUSED) {
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
             const int nl = wn * 32 * WN + j * 32 + fr;
             const int n = col0 + nl;
-            const int base_n = K - pop_b[nl];
+            const int base_n = PLANES ? 0 : K - pop_b[nl];
 #pragma unroll
             for (int i = 0; i < WM; ++i)
 #pragma unroll
@@ -224,14 +298,14 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
                     for (int e = 0; e < 4; ++e) {
                         const int m = row0 + ml + e;
                         const int pa = e == 0 ? pa2.x : e == 1 ? pa2.y : e == 2 ? pa2.z : pa2.w;
-                        const int dot = base_n - pa + 4 * int(acc[i][j][4 * vq + e]);
+                        const int dot = base_n - pa + (int(acc[i][j][4 * vq + e]) << kShift);
                         if (m < M && n < N) C[int64_t(m) * ldc + n] = dot;
                     }
                 }
         }
     } else {
-        // bit(m, n) = (dot >= thr[n]) XOR flip[n] with dot = K - 2pa - 2pb + 4S, i.e.
-        // S >= ceil((thr - K + 2pb + 2pa) / 4) = (thr - K + 2pb + 3 + 2pa) >> 2.
+        // bit(m, n) = (result >= thr[n]) XOR flip[n], i.e.
+        //   binary: S >= ceil((thr - K + 2pb + 2pa) / 4),   planes: S >= ceil((thr + rowsum) / 2).
         // A ballot over one accumulator register gives, in its low half, the 32-column word of
         // the row held by lanes 0-31 and, in its high half, that of the row 4 below.  The words
         // of one 32-row block are gathered with v_writelane so that lane r (block j = 0) and
@@ -246,7 +320,7 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
             const bool live = n < N;
             const int thr = live ? bn.thr[n] : 0;
             const bool flip = live && ((bn.flip_bits[n >> 5] >> (n & 31)) & 1u) != 0u;
-            u3[j] = thr - K + pop_b[nl] + 3;
+            u3[j] = PLANES ? thr + 1 : thr - K + pop_b[nl] + 3;
             flip_mask[j] = __ballot(flip);
             live_mask[j] = __ballot(live);
         }
@@ -264,7 +338,7 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
                     const int pa = e == 0 ? pa2.x : e == 1 ? pa2.y : e == 2 ? pa2.z : pa2.w;
 #pragma unroll
                     for (int j = 0; j < WN; ++j) {
-                        const bool p = int(acc[i][j][4 * vq + e]) >= ((u3[j] + pa) >> 2);
+                        const bool p = int(acc[i][j][4 * vq + e]) >= ((u3[j] + pa) >> kShift);
                         const uint64_t mask = (__ballot(p) ^ flip_mask[j]) & live_mask[j];
                         words = bnn_llvm_writelane(int(uint32_t(mask)), 32 * j + 8 * vq + e, words);
                         words = bnn_llvm_writelane(int(uint32_t(mask >> 32)), 32 * j + 8 * vq + 4 + e, words);
@@ -277,35 +351,47 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
     }
 }
 
-template <bool FUSED>
+template <bool FUSED, bool PLANES>
 static int launch_mfma(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc,
                        int64_t M, int64_t N, int64_t K, BnSignArgs bn, void* stream) {
     constexpr int WM = 4, WN = 2;
     const int64_t tiles_m = ceil_div(M, 64 * WM), tiles_n = ceil_div(N, 64 * WN);
     if (tiles_m * tiles_n > kMaxDim) return BNN_ERR_UNSUPPORTED;
-    const bool vec = aligned_to(A, 16) && aligned_to(B, 16) && lda % 4 == 0 && ldb % 4 == 0;
+    // The planes kernel reads B one word at a time, so only A's alignment matters there.
+    const bool vec = aligned_to(A, 16) && lda % 4 == 0 && (PLANES || (aligned_to(B, 16) && ldb % 4 == 0));
     const dim3 grid{unsigned(tiles_m * tiles_n)};
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (vec)
-        hipLaunchKernelGGL((xnor_gemm_mfma_kernel<WM, WN, true, FUSED>), grid, dim3(256), 0, s, A, lda, B, ldb, C,
-                           ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn);
+        hipLaunchKernelGGL((xnor_gemm_mfma_kernel<WM, WN, true, FUSED, PLANES>), grid, dim3(256), 0, s, A, lda, B,
+                           ldb, C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn);
     else
-        hipLaunchKernelGGL((xnor_gemm_mfma_kernel<WM, WN, false, FUSED>), grid, dim3(256), 0, s, A, lda, B, ldb,
-                           C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn);
+        hipLaunchKernelGGL((xnor_gemm_mfma_kernel<WM, WN, false, FUSED, PLANES>), grid, dim3(256), 0, s, A, lda,
+                           B, ldb, C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn);
     return check_launch();
 }
 
-// Entry points used by the dispatcher in xnor_gemm.hip.  The caller has validated the arguments.
-bool mfma_path_supports(int64_t K) { return K <= kMfmaMaxK; }
+// Entry points used by the dispatchers.  The callers have validated the arguments.
+bool mfma_path_supports(int64_t K) { return K <= kMfmaMaxAcc; }
+bool mfma_planes_path_supports(int64_t K) { return 255 * K < kMfmaMaxAcc; }
 
 int launch_xnor_gemm_mfma(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
                           int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream) {
-    return launch_mfma<false>(A, lda, B, ldb, C, ldc, M, N, K, BnSignArgs{}, stream);
+    return launch_mfma<false, false>(A, lda, B, ldb, C, ldc, M, N, K, BnSignArgs{}, stream);
 }
 
 int launch_xnor_gemm_mfma_fused(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M,
                                 int64_t N, int64_t K, BnSignArgs bn, void* stream) {
-    return launch_mfma<true>(A, lda, B, ldb, nullptr, 0, M, N, K, bn, stream);
+    return launch_mfma<true, false>(A, lda, B, ldb, nullptr, 0, M, N, K, bn, stream);
+}
+
+int launch_bitplane_gemm_mfma(const uint32_t* Xp, int64_t ldx, const uint32_t* B, int64_t ldb, int32_t* C,
+                              int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream) {
+    return launch_mfma<false, true>(Xp, ldx, B, ldb, C, ldc, M, N, K, BnSignArgs{}, stream);
+}
+
+int launch_bitplane_gemm_mfma_fused(const uint32_t* Xp, int64_t ldx, const uint32_t* B, int64_t ldb, int64_t M,
+                                    int64_t N, int64_t K, BnSignArgs bn, void* stream) {
+    return launch_mfma<true, true>(Xp, ldx, B, ldb, nullptr, 0, M, N, K, bn, stream);
 }
 
 }  // namespace bnn

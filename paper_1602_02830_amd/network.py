@@ -35,13 +35,16 @@ class BinaryMLP:
     """
 
     def __init__(self, weights_real, bns, eps: float, batch: int, keep_preacts: bool = True,
-                 fused: bool = False, kernel: int = B.KERNEL_AUTO):
+                 fused: bool = False, kernel: int = B.KERNEL_AUTO, input_uint8: bool = False):
         assert len(bns) == len(weights_real) - 1
         dev = weights_real[0].device
         self.device = dev
         self.batch = batch
         self.fused = fused          # hidden layers as one launch each; their int32 pre-activations are not produced
         self.kernel = kernel        # GEMM kernel of the hidden layers (KERNEL_AUTO = the library's choice)
+        # input_uint8: the first layer takes 8-bit inputs as eight bit planes (Alg. 4 step 1, Sec. 1.6)
+        # instead of Sign-binarizing a real input.
+        self.input_uint8 = input_uint8
         self.K = [int(w.shape[1]) for w in weights_real]
         self.N = [int(w.shape[0]) for w in weights_real]
         self.w_bits = []
@@ -51,11 +54,15 @@ class BinaryMLP:
             self.w_bits.append(buf)
         self.thr, self.flip = [], []
         for l, bn in enumerate(bns):
-            thr, flip = B.bn_fold(*bn, eps, self.K[l])
+            # The first layer's pre-activations on 8-bit inputs range over [-255 K, 255 K].
+            thr, flip = B.bn_fold(*bn, eps, self.K[l] * (255 if (input_uint8 and l == 0) else 1))
             self.thr.append(torch.from_numpy(thr).to(dev))
             self.flip.append(torch.from_numpy(flip.view(np.int32)).to(dev))
         # Activations a^b_l (packed) and pre-activations s_l (int32), allocated once.
-        self.a_bits = [_packed_buffer(batch, self.K[0], dev)]
+        if input_uint8:
+            self.a_bits = [torch.empty((batch, 8 * B.words_per_row(self.K[0])), dtype=torch.int32, device=dev)]
+        else:
+            self.a_bits = [_packed_buffer(batch, self.K[0], dev)]
         for l in range(len(bns)):
             self.a_bits.append(_packed_buffer(batch, self.N[l], dev))
         self.keep_preacts = keep_preacts
@@ -76,7 +83,10 @@ class BinaryMLP:
         gemm_events: optional dict layer -> list; for those layers a (start, end) pair of
         events is recorded on the current stream around the GEMM launch and appended.
         """
-        B.pack_sign(x, out=self.a_bits[0])
+        if self.input_uint8:
+            B.pack_bitplanes(x, out=self.a_bits[0])
+        else:
+            B.pack_sign(x, out=self.a_bits[0])
         n_layers = len(self.w_bits)
         for l in range(n_layers):
             timed = gemm_events is not None and l in gemm_events
@@ -84,7 +94,13 @@ class BinaryMLP:
                 start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 start.record()
             hidden = l + 1 < n_layers
-            if self.fused and hidden:
+            if self.input_uint8 and l == 0:
+                if self.fused and hidden:
+                    B.bitplane_gemm_bn_sign_pack(self.a_bits[0], self.w_bits[0], self.K[0], self.thr[0],
+                                                 self.flip[0], out=self.a_bits[1])
+                else:
+                    B.bitplane_gemm(self.a_bits[0], self.w_bits[0], self.K[0], out=self.s[0])
+            elif self.fused and hidden:
                 B.xnor_gemm_bn_sign_pack(self.a_bits[l], self.w_bits[l], self.K[l], self.thr[l], self.flip[l],
                                          out=self.a_bits[l + 1], kernel=self.kernel)
             else:

@@ -372,6 +372,83 @@ def test_mlp_full_batch_sampled_rows():
         assert (net.s[l].cpu().numpy()[rows] == tr["s"][l]).all(), f"s_{l}"
 
 
+# ------------------------------------------------------------------ first layer on 8-bit inputs
+
+@pytest.mark.parametrize("rows,cols", [(1, 1), (3, 31), (5, 32), (7, 33), (33, 784), (130, 100), (2, 4099)])
+def test_pack_bitplanes(rows, cols):
+    """Plane p of the packed output == the oracle's packing of bit p of every input byte."""
+    rng = np.random.default_rng(rows * 131 + cols)
+    X = synth.uint8_input(rng, (rows, cols))
+    X.flat[:4] = (0, 255, 1, 128)[:min(4, X.size)]
+    got = words_to_host(bnn.pack_bitplanes(torch.from_numpy(X).to(DEV)))
+    kw = (cols + 31) // 32
+    assert got.shape == (rows, 8 * kw)
+    for p in range(8):
+        plane = np.where((X >> p) & 1, 1, -1).astype(np.int8)
+        assert (got[:, p::8] == oracle.pack_bits(plane)).all(), f"plane {p}"
+
+
+def test_pack_bitplanes_unaligned_input():
+    rng = np.random.default_rng(5)
+    big = synth.uint8_input(rng, (9, 77))
+    xd = torch.from_numpy(big).to(DEV)[:, 1:71]             # base 1 byte off, ld 77
+    got = words_to_host(bnn.pack_bitplanes(xd))
+    for p in range(8):
+        plane = np.where((big[:, 1:71] >> p) & 1, 1, -1).astype(np.int8)
+        assert (got[:, p::8] == oracle.pack_bits(plane)).all()
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (7, 33, 31), (33, 7, 65), (130, 200, 1000), (300, 4096, 784),
+                                   (513, 129, 96), (64, 1024, 1024), (1000, 10, 784)])
+def test_bitplane_gemm_first_layer(M, N, K):
+    """Alg. 4 step 1 / Sec. 1.6: sum_n 2^(n-1) <x^n, w> on 8-bit inputs, and its fused BN+Sign form."""
+    rng = np.random.default_rng(M * 17 + N * 3 + K)
+    X = synth.uint8_input(rng, (M, K))
+    Wb = synth.pm1(rng, (K, N))
+    bn = synth.bn_params(rng, N, 255 * K, adversarial=True)
+    bn = (bn[0], bn[1], (bn[2] * 4).astype(np.float32), bn[3])        # spread the thresholds over the wider range
+    S = oracle.first_layer_bitplanes(X, Wb)
+    planes = bnn.pack_bitplanes(torch.from_numpy(X).to(DEV))
+    wb = words_to_dev(poison_pad_bits(oracle.pack_bits(np.ascontiguousarray(Wb.T)), K))
+    got = bnn.bitplane_gemm(planes, wb, K).cpu().numpy()
+    assert (got == S).all()
+    thr, flip = bnn.bn_fold(*bn, EPS, 255 * K)
+    fused = bnn.bitplane_gemm_bn_sign_pack(planes, wb, K, torch.from_numpy(thr).to(DEV),
+                                           torch.from_numpy(flip.view(np.int32)).to(DEV))
+    assert (words_to_host(fused) == oracle.pack_bits(oracle.bn_sign(S, *bn, eps=EPS))).all()
+
+
+def test_bitplane_gemm_ignores_pad_bits_of_the_planes():
+    rng = np.random.default_rng(8)
+    M, N, K = 40, 50, 70
+    X = synth.uint8_input(rng, (M, K))
+    Wb = synth.pm1(rng, (K, N))
+    planes = words_to_host(bnn.pack_bitplanes(torch.from_numpy(X).to(DEV))).copy()
+    planes[:, -8:] |= np.uint32((0xFFFFFFFF << (K % 32)) & 0xFFFFFFFF)      # poison the last K-word of every plane
+    got = bnn.bitplane_gemm(words_to_dev(planes), words_to_dev(oracle.pack_bits(np.ascontiguousarray(Wb.T))), K)
+    assert (got.cpu().numpy() == oracle.first_layer_bitplanes(X, Wb)).all()
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_mlp_uint8_first_layer_full_batch_sampled_rows(fused):
+    """Alg. 4 as printed (8-bit inputs through bit planes), batch 10000, MNIST-shaped MLP."""
+    _x, weights, bns = synth.config_mlp()
+    x8 = synth.uint8_input(synth.rng_for(1, 1), (synth.MLP_BATCH, synth.MLP_SIZES[0]))
+    bn0 = synth.bn_params(synth.rng_for(1, 30), synth.MLP_SIZES[1], 255 * synth.MLP_SIZES[0])
+    bns = [bn0] + list(bns[1:])
+    wr = [torch.from_numpy(np.ascontiguousarray(w.T).astype(np.float32)).to(DEV) for w in weights]
+    net = bnn.BinaryMLP(wr, bns, EPS, synth.MLP_BATCH, fused=fused, input_uint8=True)
+    scores = net.forward(torch.from_numpy(x8).to(DEV)).cpu().numpy()
+    rows = np.sort(np.random.default_rng(6).choice(synth.MLP_BATCH, 300, replace=False))
+    rows[0], rows[-1] = 0, synth.MLP_BATCH - 1
+    tr = oracle.mlp_forward_uint8(x8[rows], weights, bns, eps=EPS)
+    for l in range(1, len(weights)):
+        assert (words_to_host(net.a_bits[l])[rows] == oracle.pack_bits(tr["a"][l])).all(), f"a^b_{l}"
+    if not fused:
+        assert (net.s[0].cpu().numpy()[rows] == tr["s"][0]).all()
+    assert (scores[rows] == tr["s"][-1]).all()
+
+
 # ------------------------------------------------------------------ int8 MFMA variant
 
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (7, 33, 31), (33, 7, 65), (128, 128, 64), (130, 200, 1000),

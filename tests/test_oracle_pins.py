@@ -301,6 +301,15 @@ def test_first_layer_bitplanes_equals_integer_product():
     assert (S == X.astype(np.int64) @ Wb.astype(np.int64)).all()
 
 
+def test_mlp_uint8_driver_first_layer_is_integer_product():
+    x8 = synth.uint8_input(np.random.default_rng(13), (10, 40))
+    _x, weights, bns = synth.config_mlp(batch=10, sizes=(40, 64, 10))
+    tr = oracle.mlp_forward_uint8(x8, weights, bns)
+    assert (tr["s"][0] == x8.astype(np.int64) @ weights[0].astype(np.int64)).all()
+    a1 = oracle.bn_sign(tr["s"][0], *bns[0])
+    assert (tr["s"][1] == a1.astype(np.int64) @ weights[1].astype(np.int64)).all()
+
+
 # --------------------------------------------------------------- network driver
 
 def test_mlp_driver_chains_the_steps():
