@@ -271,19 +271,22 @@ def main():
         for layer, (ch, hw) in enumerate(synth.CONV_LAYERS):
             xc, Wt, bn = synth.config_conv(layer)
             B = xc.shape[0]
-            cl = bnn.BinaryConvLayer(torch.from_numpy(Wt.astype(np.float32)).to(dev), bn, eps, B, hw, hw, fused=True)
+            wt = torch.from_numpy(Wt.astype(np.float32)).to(dev)
             xb = bnn.pack_sign(torch.from_numpy(xc.reshape(-1, ch).astype(np.float32)).to(dev)).view(B, hw, hw, ch // 32)
-            ms, _ = time_launches(lambda: cl.forward(xb), 20)
-            ms_i, _ = time_launches(lambda: bnn.conv_im2col_pack(xb, ch, out=cl.cols), 20)
-            ms_g, _ = time_launches(lambda: bnn.xnor_gemm_bn_sign_pack(cl.cols, cl.w_bits, cl.K, cl.thr, cl.flip, out=cl.out_bits), 20)
-            wbytes = cl.M * cl.K / 8
+            imp = bnn.BinaryConvLayer(wt, bn, eps, B, hw, hw, fused=True, implicit=True)
+            low = bnn.BinaryConvLayer(wt, bn, eps, B, hw, hw, fused=True, implicit=False)
+            ms_imp, _ = time_launches(lambda: imp.forward(xb), 20)
+            ms_low, _ = time_launches(lambda: low.forward(xb), 20)
+            ms_i, _ = time_launches(lambda: bnn.conv_im2col_pack(xb, ch, out=low.cols), 20)
+            same = bool(torch.equal(imp.out_bits, low.out_bits))
+            ops_c = 2.0 * imp.M * imp.K * imp.Cout
             conv[f"{ch}ch_{hw}x{hw}"] = {
-                "layer_ms": ms, "images_per_s": B / ms * 1e3, "im2col_ms": ms_i,
-                "im2col_write_GBps": wbytes / ms_i / 1e6, "fused_gemm_ms": ms_g,
-                "gemm_binary_tops": 2.0 * cl.M * cl.K * cl.Cout / ms_g / 1e9}
-            log(f"conv {ch}ch {hw}x{hw} batch {B}: layer {ms:.3f} ms, im2col {ms_i:.3f} ms, gemm {ms_g:.3f} ms "
-                f"({conv[f'{ch}ch_{hw}x{hw}']['gemm_binary_tops']:.0f} TOP/s)")
-            del cl, xb
+                "implicit_fused_layer_ms": ms_imp, "images_per_s": B / ms_imp * 1e3,
+                "binary_tops": ops_c / ms_imp / 1e9, "im2col_then_fused_gemm_layer_ms": ms_low,
+                "im2col_ms": ms_i, "im2col_write_GBps": imp.M * imp.K / 8 / ms_i / 1e6, "paths_equal": same}
+            log(f"conv {ch}ch {hw}x{hw} batch {B}: implicit fused layer {ms_imp:.3f} ms ({ops_c / ms_imp / 1e9:.0f} TOP/s, "
+                f"{B / ms_imp * 1e3:,.0f} images/s); im2col + fused GEMM {ms_low:.3f} ms (im2col {ms_i:.3f}); equal: {same}")
+            del imp, low, xb
         extras["conv_layers_batch256"] = conv
         result["extras"] = extras
 

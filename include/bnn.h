@@ -201,6 +201,42 @@ int bnn_conv_im2col_pack(const uint32_t *in, int64_t B, int64_t H, int64_t W,
                          uint32_t *out, int64_t ld_out, void *stream);
 
 /*
+ * A whole binary convolution layer without the intermediate matrix (implicit GEMM): the
+ * receptive fields described under bnn_conv_im2col_pack are gathered by the product's tile
+ * loader straight from the packed NHWC input.
+ *   S[(b*Ho + oy)*Wo + ox][co] = sum_{ky,kx,ci} in(b, oy*stride+ky-pad, ox*stride+kx-pad, ci) * Wt[co][ky][kx][ci]
+ *   in   packed NHWC [B][H][W][Cin/32] uint32, out-of-image taps read as +1
+ *   Wb   packed filters [Cout][ldw], row co = Wt[co] flattened as (ky, kx, ci), ldw >= kh*kw*Cin/32
+ *   bnn_conv_xnor:          S [B*Ho*Wo][lds] int32, lds >= Cout
+ *   bnn_conv_bn_sign_pack:  out [B*Ho*Wo][ld_out] packed bits = (S >= thr[co]) XOR flip[co]
+ *                           (= packed NHWC input of the next layer), thr/flip from bnn_bn_fold
+ * Bit-identical to bnn_conv_im2col_pack followed by bnn_xnor_gemm (and bnn_bn_sign_pack).
+ * Requires Cin % 128 == 0, `in` 16-byte aligned, kh*kw*Cin <= 2^24, H, W <= 32767 and an input of
+ * fewer than 2^32 words; otherwise BNN_ERR_UNSUPPORTED (use the im2col path).
+ */
+int bnn_conv_xnor(const uint32_t *in, int64_t B, int64_t H, int64_t W, int64_t Cin,
+                  const uint32_t *Wb, int64_t ldw, int64_t Cout, int kh, int kw, int stride, int pad,
+                  int32_t *S, int64_t lds, void *stream);
+int bnn_conv_bn_sign_pack(const uint32_t *in, int64_t B, int64_t H, int64_t W, int64_t Cin,
+                          const uint32_t *Wb, int64_t ldw, int64_t Cout, int kh, int kw, int stride,
+                          int pad, const int32_t *thr, const uint32_t *flip_bits, uint32_t *out,
+                          int64_t ld_out, void *stream);
+
+/*
+ * Max pooling for binarized layers.  The paper's ConvNets pool the pre-activations between a
+ * convolution and its BatchNorm + Sign; since Sign(BatchNorm(.)) is monotone per channel, the bit
+ * of the pooled pre-activation is the OR of the window's bits where the channel's folded flip
+ * bit is 0 and their AND where it is 1, so pooling runs on the packed output of the fused layer:
+ *   out[b][py][px][c] = OR / AND over dy < ph, dx < pw of in[b][py*stride+dy][px*stride+dx][c]
+ *   in  packed NHWC [B][H][W][ceil(C/32)], out packed NHWC [B][Hp][Wp][ceil(C/32)],
+ *   Hp = (H - ph)/stride + 1, Wp = (W - pw)/stride + 1 (no padding)
+ *   flip_bits [ceil(C/32)] device words from bnn_bn_fold, or NULL for OR on every channel.
+ * Pad bits of `in` pass through the same operations (zero stays zero under OR).
+ */
+int bnn_maxpool_bits(const uint32_t *in, int64_t B, int64_t H, int64_t W, int64_t C, int ph, int pw,
+                     int stride, const uint32_t *flip_bits, uint32_t *out, void *stream);
+
+/*
  * The competing dense-engine variant of the same product (the role the vendor
  * GEMM plays in Sec. 4 / Fig. 3): +-1 stored one per int8, multiplied on the
  * int8 MFMA units with int32 accumulation.

@@ -22,5 +22,7 @@ from .bnn_oracle import (  # noqa: F401
     mlp_forward,
     mlp_forward_uint8,
     conv_layer,
+    conv_pool_layer,
+    maxpool2d,
     EPS_DEFAULT,
 )

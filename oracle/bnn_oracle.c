@@ -28,6 +28,8 @@
  *   oracle_im2col        the definitional lowering of that convolution to a
  *                        matrix whose row m holds the receptive field of
  *                        output pixel m, K index = (ky*kw + kx)*Cin + ci.
+ *   oracle_maxpool2d     plain window maximum of int32 pre-activations (the pooling the
+ *                        paper's ConvNets apply between a convolution and its BatchNorm).
  *   oracle_first_layer_bitplanes
  *                        Alg. 4 step 1 / Eq. (4) of Sec. 1.6: 8-bit inputs as
  *                        sum_n 2^(n-1) <x^n, w^b>.
@@ -209,6 +211,32 @@ void oracle_im2col(const int8_t *in, int64_t B, int64_t H, int64_t W,
                                 in, H, W, Cin, b, oy * stride + ky - pad,
                                 ox * stride + kx - pad, ci);
             }
+}
+
+/* Max pooling of the integer pre-activations (the paper's ConvNets pool between the
+ * convolution and its BatchNorm; Sec. 2.2 describes the architecture as that of
+ * BinaryConnect, where every second convolution is followed by 2x2 max pooling):
+ *   P[b][py][px][c] = max over (dy < ph, dx < pw) of S[b][py*stride+dy][px*stride+dx][c]
+ * No padding; Hp = (H - ph)/stride + 1, Wp likewise. */
+void oracle_maxpool2d(const int32_t *S, int64_t B, int64_t H, int64_t W, int64_t C,
+                      int64_t ph, int64_t pw, int64_t stride, int32_t *P)
+{
+    const int64_t Hp = (H - ph) / stride + 1;
+    const int64_t Wp = (W - pw) / stride + 1;
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t py = 0; py < Hp; ++py)
+            for (int64_t px = 0; px < Wp; ++px)
+                for (int64_t c = 0; c < C; ++c) {
+                    int32_t best = S[((b * H + py * stride) * W + px * stride) * C + c];
+                    for (int64_t dy = 0; dy < ph; ++dy)
+                        for (int64_t dx = 0; dx < pw; ++dx) {
+                            const int32_t v =
+                                S[((b * H + py * stride + dy) * W + px * stride + dx) * C + c];
+                            if (v > best)
+                                best = v;
+                        }
+                    P[((b * Hp + py) * Wp + px) * C + c] = best;
+                }
 }
 
 /* First layer on 8-bit fixed-point inputs (Sec. 1.6, Alg. 4 step 1):

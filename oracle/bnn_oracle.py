@@ -166,6 +166,16 @@ def im2col(x, kh=3, kw=3, stride=1, pad=1) -> np.ndarray:
     return cols
 
 
+def maxpool2d(S, ph=2, pw=2, stride=2) -> np.ndarray:
+    """Window maximum of int32 maps [B][H][W][C] -> [B][Hp][Wp][C], no padding."""
+    S = _c(S, np.int32)
+    B, H, W, C = S.shape
+    Hp, Wp = (H - ph) // stride + 1, (W - pw) // stride + 1
+    P = np.empty((B, Hp, Wp, C), np.int32)
+    _load().oracle_maxpool2d(_p(S), _i64(B), _i64(H), _i64(W), _i64(C), _i64(ph), _i64(pw), _i64(stride), _p(P))
+    return P
+
+
 def first_layer_bitplanes(X, Wb) -> np.ndarray:
     """Sec. 1.6 / Alg. 4 step 1: uint8 X[M][K], +-1 Wb[K][N] -> sum_p 2^(p-1) <x^p, w>."""
     X = _c(X, np.uint8)
@@ -224,6 +234,16 @@ def mlp_forward_uint8(x_u8, weights, bns, eps=EPS_DEFAULT):
             a = bn_sign(s, *bns[l], eps=eps)
             trace["a"].append(a)
     return trace
+
+
+def conv_pool_layer(x_b, Wt, bn, pool=2, stride=1, pad=1, eps=EPS_DEFAULT):
+    """Binary conv layer with max pooling in the paper's order: convolution, max pooling of the
+    pre-activations, BatchNorm, Sign.  Returns (pooled S int32, a^b int8), both [B][Hp][Wp][Cout]."""
+    S = conv_direct(x_b, Wt, stride=stride, pad=pad)
+    P = maxpool2d(S, pool, pool, pool)
+    B, Hp, Wp, Cout = P.shape
+    a = bn_sign(P.reshape(-1, Cout), *bn, eps=eps).reshape(B, Hp, Wp, Cout)
+    return P, a
 
 
 def conv_layer(x_b, Wt, bn, stride=1, pad=1, eps=EPS_DEFAULT):

@@ -18,6 +18,9 @@ from .binding import (  # noqa: F401
     bn_sign_pack,
     xnor_gemm_bn_sign_pack,
     conv_im2col_pack,
+    conv_xnor,
+    conv_bn_sign_pack,
+    maxpool_bits,
     pack_bitplanes,
     bitplane_gemm,
     bitplane_gemm_bn_sign_pack,

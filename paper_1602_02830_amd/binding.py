@@ -39,6 +39,10 @@ _SIGNATURES = {
     "bnn_bn_fold": (_int, [_ptr, _ptr, _ptr, _ptr, _f32, _i64, _i64, _ptr, _ptr]),
     "bnn_bn_sign_pack": (_int, [_ptr, _i64, _i64, _i64, _ptr, _ptr, _ptr, _i64, _ptr]),
     "bnn_conv_im2col_pack": (_int, [_ptr, _i64, _i64, _i64, _i64, _int, _int, _int, _int, _ptr, _i64, _ptr]),
+    "bnn_conv_xnor": (_int, [_ptr, _i64, _i64, _i64, _i64, _ptr, _i64, _i64, _int, _int, _int, _int, _ptr, _i64, _ptr]),
+    "bnn_conv_bn_sign_pack": (_int, [_ptr, _i64, _i64, _i64, _i64, _ptr, _i64, _i64, _int, _int, _int, _int, _ptr,
+                                     _ptr, _ptr, _i64, _ptr]),
+    "bnn_maxpool_bits": (_int, [_ptr, _i64, _i64, _i64, _i64, _int, _int, _int, _ptr, _ptr, _ptr]),
     "bnn_gemm_i8_mfma": (_int, [_ptr, _i64, _ptr, _i64, _ptr, _i64, _i64, _i64, _i64, _ptr]),
     "bnn_unpack_i8": (_int, [_ptr, _i64, _i64, _i64, _ptr, _i64, _ptr]),
 }
@@ -288,6 +292,75 @@ def conv_im2col_pack(x_bits: torch.Tensor, Cin: int, kh: int = 3, kw: int = 3, s
     _check("bnn_conv_im2col_pack",
            lib.bnn_conv_im2col_pack(x_bits.data_ptr(), B, H, W, Cin, kh, kw, stride, pad, out.data_ptr(),
                                     _ld(out), _stream()))
+    return out
+
+
+def _check_nhwc_bits(x_bits: torch.Tensor, Cin: int):
+    if not x_bits.is_cuda or x_bits.dtype != torch.int32 or x_bits.dim() != 4 or not x_bits.is_contiguous():
+        raise ValueError("x_bits must be a contiguous int32 device tensor [B][H][W][ceil(Cin/32)]")
+    if x_bits.shape[3] != words_per_row(Cin):
+        raise ValueError("last dimension does not match the channel count")
+
+
+def conv_xnor(x_bits: torch.Tensor, Cin: int, w_bits: torch.Tensor, kh: int = 3, kw: int = 3, stride: int = 1,
+              pad: int = 1, out: torch.Tensor | None = None) -> torch.Tensor:
+    """bnn_conv_xnor: packed NHWC input, packed filters [Cout][kh*kw*Cin/32] -> int32 [B*Ho*Wo][Cout]."""
+    lib = load_library()
+    _check_nhwc_bits(x_bits, Cin)
+    _dev(w_bits, torch.int32, "w_bits")
+    B, H, W, _ = x_bits.shape
+    Cout = w_bits.shape[0]
+    Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    if out is None:
+        out = torch.empty((B * Ho * Wo, Cout), dtype=torch.int32, device=x_bits.device)
+    _dev(out, torch.int32, "out")
+    _check("bnn_conv_xnor", lib.bnn_conv_xnor(x_bits.data_ptr(), B, H, W, Cin, w_bits.data_ptr(), _ld(w_bits), Cout,
+                                             kh, kw, stride, pad, out.data_ptr(), _ld(out), _stream()))
+    return out
+
+
+def conv_bn_sign_pack(x_bits: torch.Tensor, Cin: int, w_bits: torch.Tensor, thr: torch.Tensor,
+                      flip_bits: torch.Tensor, kh: int = 3, kw: int = 3, stride: int = 1, pad: int = 1,
+                      out: torch.Tensor | None = None) -> torch.Tensor:
+    """bnn_conv_bn_sign_pack: binary conv + Sign(BatchNorm) -> packed bits [B*Ho*Wo][ceil(Cout/32)]."""
+    lib = load_library()
+    _check_nhwc_bits(x_bits, Cin)
+    _dev(w_bits, torch.int32, "w_bits")
+    B, H, W, _ = x_bits.shape
+    Cout = w_bits.shape[0]
+    Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    nw = words_per_row(Cout)
+    if thr.dtype != torch.int32 or flip_bits.dtype != torch.int32 or not thr.is_cuda or not flip_bits.is_cuda:
+        raise ValueError("thr and flip_bits must be int32 device tensors")
+    if thr.numel() != Cout or flip_bits.numel() != nw or not thr.is_contiguous() or not flip_bits.is_contiguous():
+        raise ValueError("thr must be [Cout] and flip_bits [ceil(Cout/32)], contiguous")
+    if out is None:
+        out = torch.empty((B * Ho * Wo, nw), dtype=torch.int32, device=x_bits.device)
+    _dev(out, torch.int32, "out")
+    _check("bnn_conv_bn_sign_pack",
+           lib.bnn_conv_bn_sign_pack(x_bits.data_ptr(), B, H, W, Cin, w_bits.data_ptr(), _ld(w_bits), Cout, kh, kw,
+                                     stride, pad, thr.data_ptr(), flip_bits.data_ptr(), out.data_ptr(), _ld(out),
+                                     _stream()))
+    return out
+
+
+def maxpool_bits(x_bits: torch.Tensor, C: int, flip_bits: torch.Tensor | None, ph: int = 2, pw: int = 2,
+                 stride: int = 2, out: torch.Tensor | None = None) -> torch.Tensor:
+    """bnn_maxpool_bits: packed NHWC [B][H][W][Cw] -> [B][Hp][Wp][Cw]; OR where flip = 0, AND where flip = 1."""
+    lib = load_library()
+    _check_nhwc_bits(x_bits, C)
+    B, H, W, Cw = x_bits.shape
+    Hp, Wp = (H - ph) // stride + 1, (W - pw) // stride + 1
+    if flip_bits is not None and (flip_bits.dtype != torch.int32 or not flip_bits.is_cuda or
+                                  flip_bits.numel() != Cw or not flip_bits.is_contiguous()):
+        raise ValueError("flip_bits must be a contiguous int32 device tensor [ceil(C/32)]")
+    if out is None:
+        out = torch.empty((B, Hp, Wp, Cw), dtype=torch.int32, device=x_bits.device)
+    if not out.is_cuda or out.dtype != torch.int32 or not out.is_contiguous() or out.numel() != B * Hp * Wp * Cw:
+        raise ValueError("out must be a contiguous int32 device tensor [B][Hp][Wp][Cw]")
+    _check("bnn_maxpool_bits", lib.bnn_maxpool_bits(x_bits.data_ptr(), B, H, W, C, ph, pw, stride,
+                                                   flip_bits.data_ptr() if flip_bits is not None else None,
+                                                   out.data_ptr(), _stream()))
     return out
 
 

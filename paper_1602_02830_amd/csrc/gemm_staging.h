@@ -74,4 +74,10 @@ struct BnSignArgs {
     int64_t ld_out;
 };
 
+// Geometry of a convolution whose receptive fields are gathered on the fly (implicit GEMM):
+// input packed NHWC [B][H][W][Cw words], taps kh x kw, row m = (b*Ho + oy)*Wo + ox.
+struct ConvArgs {
+    int H, W, Cw, kh, kw, stride, pad, Ho, Wo;
+};
+
 }  // namespace bnn

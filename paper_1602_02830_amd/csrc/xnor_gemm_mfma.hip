@@ -3,6 +3,11 @@
 //   binary  (PLANES = false)  a_k = XnorDotProduct(a^b_{k-1}, W^b_k), Sec. 4 Eq. (5)
 //   planes  (PLANES = true)   a_1 = sum_{n=1..8} 2^(n-1) * <a_0^n, W^b_1>, Alg. 4 step 1 /
 //                             Sec. 1.6: 8-bit inputs as eight bit planes a_0^n in {0,1}
+//   conv    (CONV = true)     the binary product whose A rows are the receptive fields of a
+//                             kh x kw convolution (3 x 3 in the paper's nets, Sec. 3.3), gathered
+//                             from the packed NHWC input while the tile is staged (implicit
+//                             GEMM: the im2col matrix is never written); taps outside the image
+//                             are +1, i.e. all-ones words (zero padding through Eq. (1))
 //
 // Operands stay packed 32 per word in HBM and LDS (the 32x smaller footprint the
 // paper argues for); only inside registers is each bit widened to a 4-bit float
@@ -72,10 +77,12 @@ __device__ inline int popc4_weighted(uint4 v, int p0) {
 
 __device__ inline uint32_t quad_word(const uint4& q, int s) { return s == 0 ? q.x : s == 1 ? q.y : s == 2 ? q.z : q.w; }
 
-template <int WM, int WN, bool VEC, bool FUSED, bool PLANES>
+template <int WM, int WN, bool VEC, bool FUSED, bool PLANES, bool CONV>
 __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
     const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B, int64_t ldb,
-    int32_t* __restrict__ C, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n, BnSignArgs bn) {
+    int32_t* __restrict__ C, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n, BnSignArgs bn,
+    ConvArgs cv) {
+    static_assert(!(PLANES && CONV), "one A layout at a time");
     constexpr int BM = 64 * WM, BN = 64 * WN;          // 2 x 2 wavefronts
     constexpr int PLANE_A = BM + 2, PLANE_B = BN + 2;  // 16-byte slots per quad plane (2 pad slots)
     constexpr int ST_ROWS = 256 / kMfmaKQ;             // rows covered by one staging pass
@@ -109,13 +116,29 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
     const int n_full_ktiles = PLANES ? (K >> 5) / 2 : (K >> 5) / kMfmaKT;
 
     const int st_q = tid % kMfmaKQ, st_r = tid / kMfmaKQ;
+    // conv: per staged row the word offset of its image and its output pixel (oy << 16 | ox);
+    // otherwise the row pointer.  fill_a: what staging writes for a fetched quad
+    // (0 = the loaded words, 1 = all ones: tap outside the image, 2 = zeros: no such row or word).
     const uint32_t* pa[LOADS_A];
+    uint32_t img_off[LOADS_A];
+    int pix[LOADS_A];
     bool live_a[LOADS_A];
+    int fill_a[LOADS_A];
 #pragma unroll
     for (int l = 0; l < LOADS_A; ++l) {
         const int r = row0 + st_r + l * ST_ROWS;
         live_a[l] = r < M;
-        pa[l] = A + int64_t(min(r, M - 1)) * lda;
+        fill_a[l] = 0;
+        const int rc = min(r, M - 1);
+        if (CONV) {
+            const int ox = rc % cv.Wo, t = rc / cv.Wo;
+            const int oy = t % cv.Ho, b = t / cv.Ho;
+            img_off[l] = uint32_t(b) * uint32_t(cv.H * cv.W * cv.Cw);
+            pix[l] = (oy << 16) | ox;
+            pa[l] = A;
+        } else {
+            pa[l] = A + int64_t(rc) * lda;
+        }
     }
     // binary: B rows staged like A.  planes: thread t stages word (2*kt + t/BN) of B row col0 + t%BN.
     const uint32_t* pb[NB];
@@ -152,9 +175,36 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
         }
         return v;
     };
+    // conv: quad `quad` of a receptive field is 4 channel words of one tap; the load address is
+    // clamped into the image and the choice between the loaded words, all-ones and zeros is made
+    // at staging, so the loads themselves are unconditional.
+    auto fetch_conv = [&](int quad) {
+        const int w0 = min(quad * 4, kwa - 4);
+        const int tap = w0 / cv.Cw, cw = w0 - tap * cv.Cw;
+        const int ky = tap / cv.kw, kx = tap - ky * cv.kw;
+#pragma unroll
+        for (int l = 0; l < LOADS_A; ++l) {
+            const int y = (pix[l] >> 16) * cv.stride - cv.pad + ky;
+            const int x = (pix[l] & 0xFFFF) * cv.stride - cv.pad + kx;
+            const bool inside = y >= 0 && y < cv.H && x >= 0 && x < cv.W;
+            const int yc = min(max(y, 0), cv.H - 1), xc = min(max(x, 0), cv.W - 1);
+            ra[l] = *reinterpret_cast<const uint4*>(A + img_off[l] + uint32_t((yc * cv.W + xc) * cv.Cw + cw));
+            fill_a[l] = (!live_a[l] || quad * 4 >= kwa) ? 2 : (inside ? 0 : 1);
+        }
+    };
     auto fetch = [&](int kt) {
         const int quad = kt * kMfmaKQ + st_q;
-        if (kt < n_full_ktiles) {
+        if (CONV) {
+            fetch_conv(quad);
+            if (kt < n_full_ktiles) {
+#pragma unroll
+                for (int l = 0; l < LOADS_B; ++l) rb[l] = load_quad_unchecked<VEC>(pb[l], quad);
+            } else {
+#pragma unroll
+                for (int l = 0; l < LOADS_B; ++l)
+                    rb[l] = load_quad<VEC>(B, ldb, N, kw, tmask, col0 + st_r + l * ST_ROWS, quad);
+            }
+        } else if (kt < n_full_ktiles) {
 #pragma unroll
             for (int l = 0; l < LOADS_A; ++l) ra[l] = load_quad_unchecked<VEC>(pa[l], quad);
             if (PLANES) {
@@ -185,7 +235,13 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
     auto stage = [&](int buf) {
 #pragma unroll
         for (int l = 0; l < LOADS_A; ++l) {
-            const uint4 v = zero_unless(live_a[l], ra[l]);
+            uint4 v = zero_unless(live_a[l], ra[l]);
+            if (CONV) {
+                const bool keep = fill_a[l] == 0;
+                const uint32_t fill = fill_a[l] == 1 ? ~0u : 0u;
+                v = make_uint4(keep ? ra[l].x : fill, keep ? ra[l].y : fill, keep ? ra[l].z : fill,
+                               keep ? ra[l].w : fill);
+            }
             cnt_a[l] += PLANES ? popc4_weighted(v, 4 * (st_q & 1)) : popc4(v);
             lds_a[buf][st_q * PLANE_A + st_r + l * ST_ROWS] = v;
         }
@@ -351,22 +407,24 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
     }
 }
 
-template <bool FUSED, bool PLANES>
+template <bool FUSED, bool PLANES, bool CONV>
 static int launch_mfma(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc,
-                       int64_t M, int64_t N, int64_t K, BnSignArgs bn, void* stream) {
+                       int64_t M, int64_t N, int64_t K, BnSignArgs bn, ConvArgs cv, void* stream) {
     constexpr int WM = 4, WN = 2;
     const int64_t tiles_m = ceil_div(M, 64 * WM), tiles_n = ceil_div(N, 64 * WN);
     if (tiles_m * tiles_n > kMaxDim) return BNN_ERR_UNSUPPORTED;
-    // The planes kernel reads B one word at a time, so only A's alignment matters there.
-    const bool vec = aligned_to(A, 16) && lda % 4 == 0 && (PLANES || (aligned_to(B, 16) && ldb % 4 == 0));
+    // The planes kernel reads B one word at a time, so only A's alignment matters there; the conv
+    // kernel always reads whole 16-byte channel quads of A (its caller has checked that it can).
+    const bool vec_a = CONV || (aligned_to(A, 16) && lda % 4 == 0);
+    const bool vec = vec_a && (PLANES || (aligned_to(B, 16) && ldb % 4 == 0));
     const dim3 grid{unsigned(tiles_m * tiles_n)};
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (vec)
-        hipLaunchKernelGGL((xnor_gemm_mfma_kernel<WM, WN, true, FUSED, PLANES>), grid, dim3(256), 0, s, A, lda, B,
-                           ldb, C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn);
+        hipLaunchKernelGGL((xnor_gemm_mfma_kernel<WM, WN, true, FUSED, PLANES, CONV>), grid, dim3(256), 0, s, A,
+                           lda, B, ldb, C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn, cv);
     else
-        hipLaunchKernelGGL((xnor_gemm_mfma_kernel<WM, WN, false, FUSED, PLANES>), grid, dim3(256), 0, s, A, lda,
-                           B, ldb, C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn);
+        hipLaunchKernelGGL((xnor_gemm_mfma_kernel<WM, WN, false, FUSED, PLANES, CONV>), grid, dim3(256), 0, s, A,
+                           lda, B, ldb, C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn, cv);
     return check_launch();
 }
 
@@ -376,22 +434,35 @@ bool mfma_planes_path_supports(int64_t K) { return 255 * K < kMfmaMaxAcc; }
 
 int launch_xnor_gemm_mfma(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
                           int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream) {
-    return launch_mfma<false, false>(A, lda, B, ldb, C, ldc, M, N, K, BnSignArgs{}, stream);
+    return launch_mfma<false, false, false>(A, lda, B, ldb, C, ldc, M, N, K, BnSignArgs{}, ConvArgs{}, stream);
 }
 
 int launch_xnor_gemm_mfma_fused(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M,
                                 int64_t N, int64_t K, BnSignArgs bn, void* stream) {
-    return launch_mfma<true, false>(A, lda, B, ldb, nullptr, 0, M, N, K, bn, stream);
+    return launch_mfma<true, false, false>(A, lda, B, ldb, nullptr, 0, M, N, K, bn, ConvArgs{}, stream);
 }
 
 int launch_bitplane_gemm_mfma(const uint32_t* Xp, int64_t ldx, const uint32_t* B, int64_t ldb, int32_t* C,
                               int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream) {
-    return launch_mfma<false, true>(Xp, ldx, B, ldb, C, ldc, M, N, K, BnSignArgs{}, stream);
+    return launch_mfma<false, true, false>(Xp, ldx, B, ldb, C, ldc, M, N, K, BnSignArgs{}, ConvArgs{}, stream);
 }
 
 int launch_bitplane_gemm_mfma_fused(const uint32_t* Xp, int64_t ldx, const uint32_t* B, int64_t ldb, int64_t M,
                                     int64_t N, int64_t K, BnSignArgs bn, void* stream) {
-    return launch_mfma<true, true>(Xp, ldx, B, ldb, nullptr, 0, M, N, K, bn, stream);
+    return launch_mfma<true, true, false>(Xp, ldx, B, ldb, nullptr, 0, M, N, K, bn, ConvArgs{}, stream);
+}
+
+// Implicit-GEMM convolution: `in` is the packed NHWC input, B the packed filters [N][kh*kw*Cw].
+// The conv kernel reads A in unaligned-tolerant fashion only through 16-byte quads, so the
+// caller guarantees in is 16-byte aligned and Cw % 4 == 0.
+int launch_conv_mfma(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc, int64_t M,
+                     int64_t N, int64_t K, ConvArgs cv, void* stream) {
+    return launch_mfma<false, false, true>(in, 0, B, ldb, C, ldc, M, N, K, BnSignArgs{}, cv, stream);
+}
+
+int launch_conv_mfma_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
+                           BnSignArgs bn, ConvArgs cv, void* stream) {
+    return launch_mfma<true, false, true>(in, 0, B, ldb, nullptr, 0, M, N, K, bn, cv, stream);
 }
 
 }  // namespace bnn

@@ -122,9 +122,11 @@ class BinaryConvLayer:
     """
 
     def __init__(self, weight_real, bn, eps: float, batch: int, H: int, W: int, stride: int = 1, pad: int = 1,
-                 fused: bool = False):
+                 fused: bool = False, implicit: bool = False, pool: int = 0):
         dev = weight_real.device
         self.fused = fused      # GEMM and BN+Sign in one launch; the int32 pre-activations are not produced
+        self.implicit = implicit  # receptive fields gathered inside the GEMM (no im2col matrix); Cin % 128 == 0
+        self.pool = pool        # pool x pool max pooling (stride pool) of the pre-activations, done on the output bits
         self.Cout, self.kh, self.kw, self.Cin = (int(d) for d in weight_real.shape)
         self.stride, self.pad = stride, pad
         self.B, self.H, self.W = batch, H, W
@@ -141,16 +143,32 @@ class BinaryConvLayer:
         thr, flip = B.bn_fold(*bn, eps, self.K)
         self.thr = torch.from_numpy(thr).to(dev)
         self.flip = torch.from_numpy(flip.view(np.int32)).to(dev)
-        self.cols = _packed_buffer(self.M, self.K, dev)
+        self.cols = None if implicit else _packed_buffer(self.M, self.K, dev)
         self.s = None if fused else torch.empty((self.M, self.Cout), dtype=torch.int32, device=dev)
         self.out_bits = torch.empty((self.M, B.words_per_row(self.Cout)), dtype=torch.int32, device=dev)
+        if pool:
+            self.Hp, self.Wp = (self.Ho - pool) // pool + 1, (self.Wo - pool) // pool + 1
+            self.pooled = torch.empty((batch, self.Hp, self.Wp, B.words_per_row(self.Cout)), dtype=torch.int32,
+                                      device=dev)
 
     def forward(self, x_bits: torch.Tensor) -> torch.Tensor:
         """x_bits: packed NHWC int32 [B][H][W][Cin/32].  Returns packed NHWC [B][Ho][Wo][ceil(Cout/32)]."""
-        B.conv_im2col_pack(x_bits, self.Cin, self.kh, self.kw, self.stride, self.pad, out=self.cols)
-        if self.fused:
-            B.xnor_gemm_bn_sign_pack(self.cols, self.w_bits, self.K, self.thr, self.flip, out=self.out_bits)
+        if self.implicit:
+            if self.fused:
+                B.conv_bn_sign_pack(x_bits, self.Cin, self.w_bits, self.thr, self.flip, self.kh, self.kw,
+                                    self.stride, self.pad, out=self.out_bits)
+            else:
+                B.conv_xnor(x_bits, self.Cin, self.w_bits, self.kh, self.kw, self.stride, self.pad, out=self.s)
+                B.bn_sign_pack(self.s, self.thr, self.flip, out=self.out_bits)
         else:
-            B.xnor_gemm(self.cols, self.w_bits, self.K, out=self.s)
-            B.bn_sign_pack(self.s, self.thr, self.flip, out=self.out_bits)
-        return self.out_bits.view(self.B, self.Ho, self.Wo, -1)
+            B.conv_im2col_pack(x_bits, self.Cin, self.kh, self.kw, self.stride, self.pad, out=self.cols)
+            if self.fused:
+                B.xnor_gemm_bn_sign_pack(self.cols, self.w_bits, self.K, self.thr, self.flip, out=self.out_bits)
+            else:
+                B.xnor_gemm(self.cols, self.w_bits, self.K, out=self.s)
+                B.bn_sign_pack(self.s, self.thr, self.flip, out=self.out_bits)
+        out = self.out_bits.view(self.B, self.Ho, self.Wo, -1)
+        if self.pool:
+            B.maxpool_bits(out, self.Cout, self.flip, self.pool, self.pool, self.pool, out=self.pooled)
+            return self.pooled
+        return out

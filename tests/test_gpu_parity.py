@@ -341,6 +341,74 @@ def test_conv_layers_full_batch_sampled_images(fused):
             assert (out[img] == oracle.pack_bits(a_want.reshape(-1, C))).all()
 
 
+@pytest.mark.parametrize("shape", [
+    # B, H, W, Cin, Cout, kh, kw, stride, pad
+    (2, 8, 8, 128, 64, 3, 3, 1, 1),
+    (3, 5, 7, 128, 33, 3, 3, 1, 1),
+    (2, 9, 6, 256, 130, 3, 3, 2, 1),
+    (1, 6, 6, 128, 40, 5, 3, 1, 2),
+    (2, 4, 4, 384, 16, 1, 1, 1, 0),
+    (1, 32, 32, 128, 128, 3, 3, 1, 1),
+    (40, 8, 8, 512, 512, 3, 3, 1, 1),
+])
+def test_implicit_conv_matches_direct_convolution(shape):
+    """Implicit-GEMM conv (no im2col matrix) == the oracle's direct convolution; fused form ==
+    direct convolution, float BatchNorm, Sign."""
+    B, H, W, Cin, Cout, kh, kw, stride, pad = shape
+    rng = np.random.default_rng(sum(shape))
+    x = synth.pm1(rng, (B, H, W, Cin))
+    Wt = synth.pm1(rng, (Cout, kh, kw, Cin))
+    bn = synth.bn_params(rng, Cout, kh * kw * Cin, adversarial=True)
+    S = oracle.conv_direct(x, Wt, stride=stride, pad=pad)
+    xb = words_to_dev(_pack_nhwc(x).reshape(-1, Cin // 32)).view(B, H, W, Cin // 32)
+    wb = words_to_dev(oracle.pack_bits(Wt.reshape(Cout, -1)))
+    got = bnn.conv_xnor(xb, Cin, wb, kh, kw, stride, pad).cpu().numpy()
+    assert (got.reshape(S.shape) == S).all()
+    thr, flip = _fold_to_dev(bn, kh * kw * Cin)
+    bits = words_to_host(bnn.conv_bn_sign_pack(xb, Cin, wb, thr, flip, kh, kw, stride, pad))
+    want = oracle.pack_bits(oracle.bn_sign(S.reshape(-1, Cout), *bn, eps=EPS))
+    assert (bits == want).all()
+
+
+def test_implicit_conv_rejects_unsupported_channel_counts():
+    xb = torch.zeros((1, 4, 4, 1), dtype=torch.int32, device=DEV)
+    wb = torch.zeros((8, 9), dtype=torch.int32, device=DEV)
+    with pytest.raises(bnn.BnnError) as e:
+        bnn.conv_xnor(xb, 32, wb)
+    assert e.value.status == 3          # BNN_ERR_UNSUPPORTED: the im2col path handles this
+
+
+@pytest.mark.parametrize("shape", [(2, 8, 8, 128, 2, 2), (3, 7, 9, 40, 2, 2), (1, 6, 6, 33, 3, 3), (2, 5, 5, 64, 2, 1)])
+def test_maxpool_bits_matches_pooling_of_preactivations(shape):
+    """Pooling on output bits == the oracle's max pooling of int32 pre-activations, then float
+    BatchNorm, then Sign (the paper's order), including gamma < 0 and gamma == 0 channels."""
+    B, H, W, C, pool, stride = shape
+    rng = np.random.default_rng(sum(shape))
+    K = 300
+    S = (2 * rng.integers(0, K + 1, (B, H, W, C)) - K).astype(np.int32)
+    S = np.clip(np.rint(S / 8), -K, K).astype(np.int32)           # concentrate near the thresholds
+    bn = synth.bn_params(rng, C, K, adversarial=True)
+    want = oracle.bn_sign(oracle.maxpool2d(S, pool, pool, stride).reshape(-1, C), *bn, eps=EPS)
+    thr, flip = _fold_to_dev(bn, K)
+    bits = bnn.bn_sign_pack(torch.from_numpy(S.reshape(-1, C)).to(DEV), thr, flip)
+    pooled = bnn.maxpool_bits(bits.view(B, H, W, -1), C, flip, pool, pool, stride)
+    assert (words_to_host(pooled.reshape(-1, pooled.shape[-1])) == oracle.pack_bits(want)).all()
+
+
+def test_conv_pool_layers_full_batch_sampled_images():
+    """conv -> max pool -> BatchNorm -> Sign at batch 256 with the implicit, fused layer + pooling on bits."""
+    for layer in range(3):
+        x, Wt, bn = synth.config_conv(layer, adversarial=True)
+        B, H, W, C = x.shape
+        conv = bnn.BinaryConvLayer(torch.from_numpy(Wt.astype(np.float32)).to(DEV), bn, EPS, B, H, W, fused=True,
+                                   implicit=True, pool=2)
+        xb = words_to_dev(_pack_nhwc(x).reshape(-1, C // 32)).view(B, H, W, C // 32)
+        out = words_to_host(conv.forward(xb).reshape(B, (H // 2) * (W // 2), -1))
+        for img in (0, 77, 255):
+            _P, a_want = oracle.conv_pool_layer(x[img:img + 1], Wt, bn, pool=2, eps=EPS)
+            assert (out[img] == oracle.pack_bits(a_want.reshape(-1, C))).all()
+
+
 # ------------------------------------------------------------------ MLP chain
 
 def _mlp_on_gpu(x, weights, bns, batch):

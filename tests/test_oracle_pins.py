@@ -289,6 +289,32 @@ def test_im2col_matches_library_unfold():
     assert (cols == unf.numpy().astype(np.int8)).all()
 
 
+@pytest.mark.parametrize("shape", [(2, 8, 8, 5, 2, 2, 2), (1, 7, 9, 3, 3, 2, 1), (2, 6, 6, 4, 3, 3, 3)])
+def test_maxpool_equals_library_max_pool2d(shape):
+    B, H, W, C, ph, pw, stride = shape
+    rng = np.random.default_rng(sum(shape))
+    S = rng.integers(-500, 500, (B, H, W, C)).astype(np.int32)
+    P = oracle.maxpool2d(S, ph, pw, stride)
+    lib = torch.nn.functional.max_pool2d(torch.from_numpy(S).float().permute(0, 3, 1, 2), (ph, pw), stride)
+    assert (P == lib.permute(0, 2, 3, 1).numpy().astype(np.int64)).all()
+
+
+def test_pooling_commutes_with_sign_of_monotone_bn():
+    """What lets pooling run on bits: for gamma >= 0 Sign(BN(max s)) is the OR of the window's
+    bits, for gamma < 0 the AND (BN is monotone per channel, Sign is monotone)."""
+    rng = np.random.default_rng(21)
+    x = synth.pm1(rng, (2, 8, 8, 32))
+    Wt = synth.pm1(rng, (16, 3, 3, 32))
+    bn = synth.bn_params(rng, 16, 9 * 32, adversarial=True)
+    _P, a_pool = oracle.conv_pool_layer(x, Wt, bn)
+    _S, a = oracle.conv_layer(x, Wt, bn)
+    win = a.reshape(2, 4, 2, 4, 2, 16)
+    any_plus = (win == 1).any(axis=(2, 4))
+    all_plus = (win == 1).all(axis=(2, 4))
+    want = np.where(bn[0] < 0, all_plus, any_plus)
+    assert ((a_pool == 1) == want).all()
+
+
 # ------------------------------------------------ first layer, Sec. 1.6 / Alg. 4
 
 def test_first_layer_bitplanes_equals_integer_product():
