@@ -90,8 +90,9 @@ int bnn_xnor_gemm(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb
  * output, 2 = 128x128 LDS-tiled register-blocked XNOR-popcount kernel,
  * 3 = K-split kernel with wavefront reduction (skinny outputs), 4 = 64x64
  * tiled XNOR-popcount kernel, 5 = bits-in / matrix-engine-inside kernel (bits
- * widened to 4-bit floats in registers, MFMA; needs K <= 2^24, else
- * BNN_ERR_UNSUPPORTED).  Unknown ids give BNN_ERR_INVALID_ARG. */
+ * widened to 4-bit floats in registers, MFMA, 256x128 tiles; needs
+ * K <= 2^24, else BNN_ERR_UNSUPPORTED), 6 = the same with 128x128 tiles.
+ * Unknown ids give BNN_ERR_INVALID_ARG. */
 int bnn_xnor_gemm_kernel(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb,
                          int32_t *C, int64_t ldc, int64_t M, int64_t N, int64_t K,
                          int kernel_id, void *stream);
@@ -147,7 +148,7 @@ int bnn_xnor_gemm_bn_sign_pack(const uint32_t *A, int64_t lda, const uint32_t *B
                                const uint32_t *flip_bits, uint32_t *out, int64_t ld_out,
                                void *stream);
 
-/* Same contract with the kernel chosen by the caller: 0 = automatic, 2, 4, 5 as
+/* Same contract with the kernel chosen by the caller: 0 = automatic, 2, 4, 5, 6 as
  * in bnn_xnor_gemm_kernel (the other kernels have no fused form). */
 int bnn_xnor_gemm_bn_sign_pack_kernel(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb,
                                       int64_t M, int64_t N, int64_t K, const int32_t *thr,

@@ -32,5 +32,6 @@ from .binding import (  # noqa: F401
     KERNEL_KSPLIT,
     KERNEL_TILED64,
     KERNEL_MFMA,
+    KERNEL_MFMA128,
 )
 from .network import BinaryMLP, BinaryConvLayer  # noqa: F401

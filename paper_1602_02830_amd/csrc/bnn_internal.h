@@ -44,16 +44,4 @@ __device__ inline uint32_t or_reduce8(uint32_t v) {
     return v;
 }
 
-// Sum over the 64 lanes of a wavefront, result in every lane (DPP within rows
-// of 16, then cross-row through ds_swizzle-free shuffles).
-__device__ inline int wave_sum(int v) {
-    v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);    // xor 1
-    v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);    // xor 2
-    v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);   // half mirror: other quad
-    v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, true);   // row mirror: other half row
-    v += __shfl_xor(v, 16, 64);
-    v += __shfl_xor(v, 32, 64);
-    return v;
-}
-
 }  // namespace bnn

@@ -13,9 +13,9 @@
 //   tiled   - BMxBN output tile per 256-thread workgroup, TMxTN accumulators per
 //             thread, operand tiles staged global -> registers -> LDS (double
 //             buffered, one barrier per K-tile), read back as 128-bit LDS loads.
-//   ksplit  - skinny outputs (few columns or few rows): a wavefront owns a
-//             small output tile and its 64 lanes split K; lane partial sums
-//             are combined with DPP / cross-lane adds.
+//   ksplit  - skinny outputs (few columns or few rows): 8 lanes share one row of
+//             the long operand and split K; their partial sums are combined
+//             with DPP permutes.
 //   naive   - one thread per output, for tiny problems and as a cross-check.
 #include "bnn_internal.h"
 #include "gemm_staging.h"
@@ -227,56 +227,92 @@ __global__ __launch_bounds__(256, 3) void xnor_gemm_tiled_kernel(
 }
 
 // ----------------------------------------------------------------------------
-// ksplit: one wavefront per RS x CS output tile, lanes split K
+// ksplit: skinny outputs.  An aligned group of 8 lanes owns one row of the long operand X and
+// up to 16 rows of the short operand Y; the 8 lanes split K by 16-byte quads (so a group reads
+// 128 contiguous bytes of its X row per load), each lane keeps 16 partial sums, and the group
+// combines them with three DPP permutes per sum.  K advances in chunks of 256 words: the
+// workgroup stages the chunk of Y in LDS (every group needs all of it) while each lane's 8 quads
+// of X are in flight, so one chunk costs a single global-memory round trip.  out(x, y) is
+// stored at C[x * sx + y * sy], which lets the same kernel serve few columns (X = A) and few
+// rows (X = B).
 // ----------------------------------------------------------------------------
-template <int RS, int CS>
+constexpr int kSkinnyCols = 16;
+constexpr int kSkinnyChunkQuads = 64;     // 256 words of K per chunk
+
+template <bool VEC>
 __global__ __launch_bounds__(256) void xnor_gemm_ksplit_kernel(
-    const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B, int64_t ldb,
-    int32_t* __restrict__ C, int64_t ldc, int M, int N, int K, int tiles_n, int64_t n_tiles) {
-    const int lane = threadIdx.x & 63;
-    const int64_t tile = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    if (tile >= n_tiles) return;                  // whole wavefront leaves together
-    const int tm = int(tile / tiles_n);
-    const int tn = int(tile - int64_t(tm) * tiles_n);
-    const int row0 = tm * RS, col0 = tn * CS;
+    const uint32_t* __restrict__ X, int64_t ldx, int nx, const uint32_t* __restrict__ Y, int64_t ldy, int ny,
+    int32_t* __restrict__ C, int64_t sx, int64_t sy, int K) {
+    __shared__ uint4 lds_y[kSkinnyCols * kSkinnyChunkQuads];          // [row][quad]
+    const int tid = threadIdx.x;
+    const int q = tid & 7;
+    const int row = blockIdx.x * 32 + (tid >> 3);                     // 32 groups per workgroup
+    const int y0 = blockIdx.y * kSkinnyCols;
     const int kw = (K + 31) >> 5;
     const uint32_t tmask = tail_mask(K);
+    const int n_quads = (kw + 3) >> 2;
+    const bool live = row < nx;
+    const int xr = min(row, nx - 1);
 
-    int acc[RS][CS];
+    int acc[kSkinnyCols];
 #pragma unroll
-    for (int i = 0; i < RS; ++i)
-#pragma unroll
-        for (int j = 0; j < CS; ++j) acc[i][j] = 0;
+    for (int j = 0; j < kSkinnyCols; ++j) acc[j] = 0;
 
-    for (int w = lane; w < kw; w += 64) {
-        const uint32_t mask = (w == kw - 1) ? tmask : 0xFFFFFFFFu;
-        uint32_t a[RS], b[CS];
+    for (int q0 = 0; q0 < n_quads; q0 += kSkinnyChunkQuads) {
+        // This lane's quads of the chunk: q, q + 8, ..., q + 56 (zero beyond the row's end).
+        uint4 a[kSkinnyChunkQuads / 8];
 #pragma unroll
-        for (int i = 0; i < RS; ++i) a[i] = (row0 + i < M) ? A[int64_t(row0 + i) * lda + w] & mask : 0u;
+        for (int t = 0; t < kSkinnyChunkQuads / 8; ++t) a[t] = load_quad<VEC>(X, ldx, nx, kw, tmask, xr, q0 + q + 8 * t);
+        // Stage Y: 16 rows x 64 quads, 4 quads per thread; rows beyond ny repeat the last row.
+        __syncthreads();                                              // previous chunk fully consumed
 #pragma unroll
-        for (int j = 0; j < CS; ++j) b[j] = (col0 + j < N) ? B[int64_t(col0 + j) * ldb + w] & mask : 0u;
-#pragma unroll
-        for (int i = 0; i < RS; ++i)
-#pragma unroll
-            for (int j = 0; j < CS; ++j) acc[i][j] += __popc(a[i] ^ b[j]);
-    }
-    // Lanes that ran fewer iterations hold smaller partial sums; all 64 lanes are
-    // active again here, as the reduction needs.
-#pragma unroll
-    for (int i = 0; i < RS; ++i)
-#pragma unroll
-        for (int j = 0; j < CS; ++j) {
-            const int total = wave_sum(acc[i][j]);
-            if (lane == 0 && row0 + i < M && col0 + j < N)
-                C[int64_t(row0 + i) * ldc + col0 + j] = K - 2 * total;
+        for (int t = 0; t < kSkinnyCols * kSkinnyChunkQuads / 256; ++t) {
+            const int idx = tid + 256 * t;
+            const int yr = idx / kSkinnyChunkQuads, yq = idx % kSkinnyChunkQuads;
+            lds_y[idx] = load_quad<VEC>(Y, ldy, ny, kw, tmask, min(y0 + yr, ny - 1), q0 + yq);
         }
+        __syncthreads();
+        // Steps and columns that do not exist are skipped (both bounds are wavefront-uniform).
+        const int steps = (min(kSkinnyChunkQuads, n_quads - q0) + 7) >> 3;
+        const int cols = min(kSkinnyCols, ny - y0);
+#pragma unroll
+        for (int t = 0; t < kSkinnyChunkQuads / 8; ++t) {
+            if (t < steps) {
+#pragma unroll
+                for (int j = 0; j < kSkinnyCols; ++j) {
+                    if (j < cols) {
+                        const uint4 b = lds_y[j * kSkinnyChunkQuads + q + 8 * t];
+                        acc[j] += __popc(a[t].x ^ b.x) + __popc(a[t].y ^ b.y) + __popc(a[t].z ^ b.z) +
+                                  __popc(a[t].w ^ b.w);
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < kSkinnyCols; ++j) {
+        int v = acc[j];
+        v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);    // lane ^ 1
+        v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);    // lane ^ 2
+        v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);   // other quad of the group
+        acc[j] = v;
+    }
+    // Lane q of the group stores columns q and q + 8.
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int j = q + 8 * h;
+        int v = 0;
+#pragma unroll
+        for (int jj = 0; jj < kSkinnyCols; ++jj) v = (jj == j) ? acc[jj] : v;
+        if (live && y0 + j < ny) C[int64_t(row) * sx + int64_t(y0 + j) * sy] = K - 2 * v;
+    }
 }
 
 // ----------------------------------------------------------------------------
 // host side
 // ----------------------------------------------------------------------------
 enum { KERNEL_AUTO = 0, KERNEL_NAIVE = 1, KERNEL_TILED128 = 2, KERNEL_KSPLIT = 3, KERNEL_TILED64 = 4,
-       KERNEL_MFMA = 5, KERNEL_LAST = KERNEL_MFMA };
+       KERNEL_MFMA = 5, KERNEL_MFMA128 = 6, KERNEL_LAST = KERNEL_MFMA128 };
 
 // Matrix-engine variant, defined in xnor_gemm_mfma.hip.
 bool mfma_path_supports(int64_t K);
@@ -284,6 +320,10 @@ int launch_xnor_gemm_mfma(const uint32_t* A, int64_t lda, const uint32_t* B, int
                           int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream);
 int launch_xnor_gemm_mfma_fused(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M,
                                 int64_t N, int64_t K, BnSignArgs bn, void* stream);
+int launch_xnor_gemm_mfma128(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
+                             int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream);
+int launch_xnor_gemm_mfma128_fused(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M,
+                                   int64_t N, int64_t K, BnSignArgs bn, void* stream);
 bool mfma_planes_path_supports(int64_t K);
 int launch_bitplane_gemm_mfma(const uint32_t* Xp, int64_t ldx, const uint32_t* B, int64_t ldb, int32_t* C,
                               int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream);
@@ -306,15 +346,21 @@ static void launch_tiled(const uint32_t* A, int64_t lda, const uint32_t* B, int6
                            B, ldb, C, ldc, M, N, K, tiles_m, tiles_n, bn);
 }
 
-// Kernel choice, from measurements on MI355X: the matrix-engine kernel is 2-4x faster than the
-// vector-ALU XNOR-popcount kernels whenever its 256 x 128 tiles number about a hundred or more
-// (enough for most of the 256 compute units); below that the 64 x 64 XNOR tiles spread a
-// small problem over more compute units; skinny outputs go to the K-split kernel.
+// Kernel choice, from measurements on MI355X: the matrix-engine kernels are 2-4x faster than the
+// vector-ALU XNOR-popcount kernels down to a few dozen tiles.  Their 256 x 128 tile (two workgroups
+// per compute unit) wins only for long K with the fused epilogue on a grid of a thousand tiles or
+// more; otherwise the 128 x 128 tile (three workgroups per compute unit) hides short K loops and
+// the int32 stores better.  Tiny grids go to the 64 x 64 XNOR tiles, which spread over more
+// compute units; skinny outputs go to the K-split kernel; K beyond the exact-fp32 range stays on
+// the vector ALU.
 static int choose_kernel(int64_t M, int64_t N, int64_t K, bool fused) {
     if (!fused && (N <= 16 || M <= 4)) return KERNEL_KSPLIT;
-    const int64_t tiles_mfma = ceil_div(M, 256) * ceil_div(N, 128);
-    if (mfma_path_supports(K) && tiles_mfma >= 96) return KERNEL_MFMA;
-    return ceil_div(M, 128) * ceil_div(N, 128) >= 512 ? KERNEL_TILED128 : KERNEL_TILED64;
+    const int64_t tiles128 = ceil_div(M, 128) * ceil_div(N, 128);
+    if (mfma_path_supports(K)) {
+        if (fused && K >= 4096 && ceil_div(M, 256) * ceil_div(N, 128) >= 1024) return KERNEL_MFMA;
+        if (tiles128 >= 32) return KERNEL_MFMA128;
+    }
+    return tiles128 >= 512 ? KERNEL_TILED128 : KERNEL_TILED64;
 }
 
 static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
@@ -322,7 +368,8 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
                               void* stream) {
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return BNN_ERR_INVALID_ARG;
     if (kernel_id < KERNEL_AUTO || kernel_id > KERNEL_LAST) return BNN_ERR_INVALID_ARG;
-    if (kernel_id == KERNEL_MFMA && !mfma_path_supports(K)) return BNN_ERR_UNSUPPORTED;
+    if ((kernel_id == KERNEL_MFMA || kernel_id == KERNEL_MFMA128) && !mfma_path_supports(K))
+        return BNN_ERR_UNSUPPORTED;
     const int64_t kw = ceil_div(K, 32);
     if (lda < kw || ldb < kw || ldc < N) return BNN_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return BNN_OK;
@@ -351,16 +398,29 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
             launch_tiled<4, 4, 16, false>(A, lda, B, ldb, C, ldc, m, n, k, BnSignArgs{}, s);
             break;
         case KERNEL_KSPLIT: {
-            constexpr int RS = 2, CS = 4;
-            const int tiles_n = int(ceil_div(N, CS));
-            const int64_t n_tiles = ceil_div(M, RS) * tiles_n;
-            if (ceil_div(n_tiles, 4) > kMaxDim) return BNN_ERR_UNSUPPORTED;
-            hipLaunchKernelGGL((xnor_gemm_ksplit_kernel<RS, CS>), dim3(unsigned(ceil_div(n_tiles, 4))),
-                               dim3(256), 0, s, A, lda, B, ldb, C, ldc, m, n, k, tiles_n, n_tiles);
+            // The long operand gets one group of 8 lanes per row, the short one 16 rows per pass.
+            const bool a_long = M >= N;
+            const uint32_t* X = a_long ? A : B;
+            const uint32_t* Y = a_long ? B : A;
+            const int64_t ldx = a_long ? lda : ldb, ldy = a_long ? ldb : lda;
+            const int nx = a_long ? m : n, ny = a_long ? n : m;
+            const int64_t sx = a_long ? ldc : 1, sy = a_long ? 1 : ldc;
+            const int64_t passes = ceil_div(ny, kSkinnyCols);
+            if (passes > 65535) return BNN_ERR_UNSUPPORTED;
+            const dim3 grid(unsigned(ceil_div(nx, 32)), unsigned(passes));
+            const bool vec = aligned_to(A, 16) && aligned_to(B, 16) && lda % 4 == 0 && ldb % 4 == 0;
+            if (vec)
+                hipLaunchKernelGGL(xnor_gemm_ksplit_kernel<true>, grid, dim3(256), 0, s, X, ldx, nx, Y, ldy, ny, C,
+                                   sx, sy, k);
+            else
+                hipLaunchKernelGGL(xnor_gemm_ksplit_kernel<false>, grid, dim3(256), 0, s, X, ldx, nx, Y, ldy, ny,
+                                   C, sx, sy, k);
             break;
         }
         case KERNEL_MFMA:
             return launch_xnor_gemm_mfma(A, lda, B, ldb, C, ldc, M, N, K, stream);
+        case KERNEL_MFMA128:
+            return launch_xnor_gemm_mfma128(A, lda, B, ldb, C, ldc, M, N, K, stream);
         default:
             return BNN_ERR_INVALID_ARG;
     }
@@ -373,9 +433,10 @@ static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const
                                            int kernel_id, void* stream) {
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return BNN_ERR_INVALID_ARG;
     if (kernel_id != KERNEL_AUTO && kernel_id != KERNEL_TILED128 && kernel_id != KERNEL_TILED64 &&
-        kernel_id != KERNEL_MFMA)
+        kernel_id != KERNEL_MFMA && kernel_id != KERNEL_MFMA128)
         return BNN_ERR_INVALID_ARG;
-    if (kernel_id == KERNEL_MFMA && !mfma_path_supports(K)) return BNN_ERR_UNSUPPORTED;
+    if ((kernel_id == KERNEL_MFMA || kernel_id == KERNEL_MFMA128) && !mfma_path_supports(K))
+        return BNN_ERR_UNSUPPORTED;
     const int64_t kw = ceil_div(K, 32);
     if (lda < kw || ldb < kw || ld_out < ceil_div(N, 32)) return BNN_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return BNN_OK;
@@ -388,6 +449,7 @@ static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const
     const BnSignArgs bn{thr, flip_bits, out, ld_out};
     if (kernel_id == KERNEL_AUTO) kernel_id = choose_kernel(M, N, K, /*fused=*/true);
     if (kernel_id == KERNEL_MFMA) return launch_xnor_gemm_mfma_fused(A, lda, B, ldb, M, N, K, bn, stream);
+    if (kernel_id == KERNEL_MFMA128) return launch_xnor_gemm_mfma128_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_TILED128)
         launch_tiled<8, 8, 16, true>(A, lda, B, ldb, nullptr, 0, int(M), int(N), int(K), bn, s);
     else

@@ -78,7 +78,7 @@ __device__ inline int popc4_weighted(uint4 v, int p0) {
 __device__ inline uint32_t quad_word(const uint4& q, int s) { return s == 0 ? q.x : s == 1 ? q.y : s == 2 ? q.z : q.w; }
 
 template <int WM, int WN, bool VEC, bool FUSED, bool PLANES, bool CONV>
-__global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
+__global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
     const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B, int64_t ldb,
     int32_t* __restrict__ C, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n, BnSignArgs bn,
     ConvArgs cv) {
@@ -407,10 +407,10 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_kernel(
     }
 }
 
-template <bool FUSED, bool PLANES, bool CONV>
+template <int WM, bool FUSED, bool PLANES, bool CONV>
 static int launch_mfma(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc,
                        int64_t M, int64_t N, int64_t K, BnSignArgs bn, ConvArgs cv, void* stream) {
-    constexpr int WM = 4, WN = 2;
+    constexpr int WN = 2;
     const int64_t tiles_m = ceil_div(M, 64 * WM), tiles_n = ceil_div(N, 64 * WN);
     if (tiles_m * tiles_n > kMaxDim) return BNN_ERR_UNSUPPORTED;
     // The planes kernel reads B one word at a time, so only A's alignment matters there; the conv
@@ -434,22 +434,34 @@ bool mfma_planes_path_supports(int64_t K) { return 255 * K < kMfmaMaxAcc; }
 
 int launch_xnor_gemm_mfma(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
                           int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream) {
-    return launch_mfma<false, false, false>(A, lda, B, ldb, C, ldc, M, N, K, BnSignArgs{}, ConvArgs{}, stream);
+    return launch_mfma<4, false, false, false>(A, lda, B, ldb, C, ldc, M, N, K, BnSignArgs{}, ConvArgs{}, stream);
 }
 
 int launch_xnor_gemm_mfma_fused(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M,
                                 int64_t N, int64_t K, BnSignArgs bn, void* stream) {
-    return launch_mfma<true, false, false>(A, lda, B, ldb, nullptr, 0, M, N, K, bn, ConvArgs{}, stream);
+    return launch_mfma<4, true, false, false>(A, lda, B, ldb, nullptr, 0, M, N, K, bn, ConvArgs{}, stream);
+}
+
+// 128 x 128 tiles (2 x 2 blocks per wavefront, 3 workgroups per compute unit): more, smaller
+// workgroups for products whose K is short or whose 256 x 128 grid would leave units idle.
+int launch_xnor_gemm_mfma128(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
+                             int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream) {
+    return launch_mfma<2, false, false, false>(A, lda, B, ldb, C, ldc, M, N, K, BnSignArgs{}, ConvArgs{}, stream);
+}
+
+int launch_xnor_gemm_mfma128_fused(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M,
+                                   int64_t N, int64_t K, BnSignArgs bn, void* stream) {
+    return launch_mfma<2, true, false, false>(A, lda, B, ldb, nullptr, 0, M, N, K, bn, ConvArgs{}, stream);
 }
 
 int launch_bitplane_gemm_mfma(const uint32_t* Xp, int64_t ldx, const uint32_t* B, int64_t ldb, int32_t* C,
                               int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream) {
-    return launch_mfma<false, true, false>(Xp, ldx, B, ldb, C, ldc, M, N, K, BnSignArgs{}, ConvArgs{}, stream);
+    return launch_mfma<4, false, true, false>(Xp, ldx, B, ldb, C, ldc, M, N, K, BnSignArgs{}, ConvArgs{}, stream);
 }
 
 int launch_bitplane_gemm_mfma_fused(const uint32_t* Xp, int64_t ldx, const uint32_t* B, int64_t ldb, int64_t M,
                                     int64_t N, int64_t K, BnSignArgs bn, void* stream) {
-    return launch_mfma<true, true, false>(Xp, ldx, B, ldb, nullptr, 0, M, N, K, bn, ConvArgs{}, stream);
+    return launch_mfma<4, true, true, false>(Xp, ldx, B, ldb, nullptr, 0, M, N, K, bn, ConvArgs{}, stream);
 }
 
 // Implicit-GEMM convolution: `in` is the packed NHWC input, B the packed filters [N][kh*kw*Cw].
@@ -457,12 +469,12 @@ int launch_bitplane_gemm_mfma_fused(const uint32_t* Xp, int64_t ldx, const uint3
 // caller guarantees in is 16-byte aligned and Cw % 4 == 0.
 int launch_conv_mfma(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc, int64_t M,
                      int64_t N, int64_t K, ConvArgs cv, void* stream) {
-    return launch_mfma<false, false, true>(in, 0, B, ldb, C, ldc, M, N, K, BnSignArgs{}, cv, stream);
+    return launch_mfma<4, false, false, true>(in, 0, B, ldb, C, ldc, M, N, K, BnSignArgs{}, cv, stream);
 }
 
 int launch_conv_mfma_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
                            BnSignArgs bn, ConvArgs cv, void* stream) {
-    return launch_mfma<true, false, true>(in, 0, B, ldb, nullptr, 0, M, N, K, bn, cv, stream);
+    return launch_mfma<4, true, false, true>(in, 0, B, ldb, nullptr, 0, M, N, K, bn, cv, stream);
 }
 
 }  // namespace bnn

@@ -22,6 +22,7 @@ GEMM_KERNELS = {
     "ksplit": bnn.KERNEL_KSPLIT,
     "tiled64": bnn.KERNEL_TILED64,
     "mfma": bnn.KERNEL_MFMA,
+    "mfma128": bnn.KERNEL_MFMA128,
 }
 
 
@@ -135,7 +136,7 @@ def test_xnor_gemm_ragged_sweep(kernel):
         _gemm_case(A, Bm, GEMM_KERNELS[kernel], poison=True)
 
 
-@pytest.mark.parametrize("kernel", ["auto", "tiled128", "tiled64", "naive", "ksplit", "mfma"])
+@pytest.mark.parametrize("kernel", ["auto", "tiled128", "tiled64", "naive", "ksplit", "mfma", "mfma128"])
 def test_xnor_gemm_odd_leading_dimensions(kernel):
     rng = np.random.default_rng(5)
     for (M, N, K) in [(130, 70, 1000), (17, 300, 129), (256, 256, 2048)]:
@@ -144,7 +145,7 @@ def test_xnor_gemm_odd_leading_dimensions(kernel):
             _gemm_case(A, Bm, GEMM_KERNELS[kernel], poison=True, ld_extra=extra)
 
 
-@pytest.mark.parametrize("kernel", ["auto", "tiled128", "tiled64", "mfma"])
+@pytest.mark.parametrize("kernel", ["auto", "tiled128", "tiled64", "mfma", "mfma128", "ksplit"])
 def test_xnor_gemm_multi_tile_shapes(kernel):
     rng = np.random.default_rng(6)
     for (M, N, K) in [(64, 1024, 1024), (300, 520, 784), (1024, 10, 4096), (513, 129, 96), (2, 2048, 640)]:
@@ -179,7 +180,7 @@ def test_xnor_gemm_dense_layer_config(kernel):
     _gemm_case(A, Bm, GEMM_KERNELS[kernel])
 
 
-@pytest.mark.parametrize("kernel", ["auto", "tiled128", "mfma"])
+@pytest.mark.parametrize("kernel", ["auto", "tiled128", "mfma", "mfma128"])
 def test_xnor_gemm_large_square_hadamard_and_sampled_rows(kernel):
     """8192^3 in the launch configuration the benchmark times.  (i) Sylvester-Hadamard
     operands: the full 8192 x 8192 result must be 8192 * I (closed form, checked on
@@ -243,7 +244,7 @@ def test_bn_sign_pack_strided_unaligned_and_canary():
 
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (7, 33, 31), (33, 7, 65), (64, 1024, 1024), (130, 200, 1000),
                                    (1000, 1000, 4097), (300, 4096, 784), (2000, 4096, 4096), (129, 95, 96)])
-@pytest.mark.parametrize("kernel", ["auto", "tiled128", "tiled64", "mfma"])
+@pytest.mark.parametrize("kernel", ["auto", "tiled128", "tiled64", "mfma", "mfma128"])
 def test_fused_layer_matches_float_bn_then_sign(M, N, K, kernel):
     """Alg. 4 hidden layer in one launch == oracle product, float BatchNorm, Sign, pack."""
     rng = np.random.default_rng(M * 3 + N * 5 + K * 7)
