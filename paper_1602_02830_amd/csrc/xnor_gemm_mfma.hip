@@ -21,8 +21,9 @@
 // the staging threads gather for free while they copy the tile.  In the planes
 // kernel the weight 2^(n-1) is the MFMA's block scale of the A operand (E8M0
 // exponent 127 + n - 1), so all eight planes accumulate into the same registers.
-// Pad bits and rows outside the matrix are zeroed at staging and therefore
-// contribute to neither S nor the popcounts.
+// Pad bits and words beyond K are zeroed at staging and therefore contribute to
+// neither S nor the popcounts; tile rows beyond the matrix are computed on a copy
+// of its last row and never stored.
 //
 // Widening: element k of a word lands in operand register k%4, nibble k/4, for
 // both operands (the sum over k does not depend on its order).  The E2M1 codes
@@ -43,6 +44,8 @@
 //           B contributes one word per lane half and tile, widened once per tile.
 // The tile is long enough that the global loads of the next tile, issued
 // before the MFMA steps, have landed when they are staged.
+#include <type_traits>
+
 #include "bnn_internal.h"
 #include "gemm_staging.h"
 
@@ -97,6 +100,7 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
     __shared__ uint32_t lds_bw[PLANES ? 2 : 1][PLANES ? 2 * BN : 1];     // planes: [buf][half][row]
     __shared__ __attribute__((aligned(16))) int pop_a[BM];
     __shared__ __attribute__((aligned(16))) int pop_b[BN];
+    __shared__ __attribute__((aligned(16))) float pop_af[FUSED ? BM : 4];   // row term of the float threshold
 
     int tile_m, tile_n;
     tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
@@ -235,7 +239,9 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
     auto stage = [&](int buf) {
 #pragma unroll
         for (int l = 0; l < LOADS_A; ++l) {
-            uint4 v = zero_unless(live_a[l], ra[l]);
+            // Rows beyond the matrix hold a copy of its last row (clamped load): their sums and
+            // outputs are computed and never stored, so nothing has to be zeroed here.
+            uint4 v = ra[l];
             if (CONV) {
                 const bool keep = fill_a[l] == 0;
                 const uint32_t fill = fill_a[l] == 1 ? ~0u : 0u;
@@ -246,11 +252,11 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
             lds_a[buf][st_q * PLANE_A + st_r + l * ST_ROWS] = v;
         }
         if (PLANES) {
-            lds_bw[buf][bw_h * BN + bw_r] = live_b[0] ? rbw : 0u;
+            lds_bw[buf][bw_h * BN + bw_r] = rbw;
         } else {
 #pragma unroll
             for (int l = 0; l < LOADS_B; ++l) {
-                const uint4 v = zero_unless(live_b[l], rb[l]);
+                const uint4 v = rb[l];
                 cnt_b[l] += popc4(v);
                 lds_b[buf][st_q * PLANE_B + st_r + l * ST_ROWS] = v;
             }
@@ -324,7 +330,10 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
         int c = cnt_a[l];
         c += __builtin_amdgcn_update_dpp(0, c, 0xB1, 0xF, 0xF, true);       // lane ^ 1
         c += __builtin_amdgcn_update_dpp(0, c, 0x4E, 0xF, 0xF, true);       // lane ^ 2
-        if (st_q == 0) pop_a[st_r + l * ST_ROWS] = PLANES ? c : 2 * c;
+        if (st_q == 0) {
+            pop_a[st_r + l * ST_ROWS] = PLANES ? c : 2 * c;
+            if (FUSED) pop_af[st_r + l * ST_ROWS] = 0.5f * float(c);       // 2pa/4 (binary), rowsum/2 (planes)
+        }
     }
 #pragma unroll
     for (int l = 0; l < LOADS_B; ++l) {
@@ -367,7 +376,12 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
         // of one 32-row block are gathered with v_writelane so that lane r (block j = 0) and
         // lane 32 + r (block j = 1) end up holding row r's two words: one store per block row.
         static_assert(WN == 2, "the fused epilogue pairs the two column blocks with the two lane halves");
+        // While every term stays below 2^22 the comparison is done in float, where it is exact
+        // (all terms are multiples of 1/4): S >= (thr - K + 2pb)/4 + 2pa/4, resp. S >= thr/2 + rowsum/2.
+        // That is one add and one compare per element instead of four integer operations.
+        const bool fp_exact = PLANES ? (255 * int64_t(K) < (int64_t(1) << 22)) : (K <= (1 << 21));
         int u3[WN];
+        float tj[WN];
         uint64_t flip_mask[WN], live_mask[WN];
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
@@ -376,34 +390,44 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
             const bool live = n < N;
             const int thr = live ? bn.thr[n] : 0;
             const bool flip = live && ((bn.flip_bits[n >> 5] >> (n & 31)) & 1u) != 0u;
-            u3[j] = PLANES ? thr + 1 : thr - K + pop_b[nl] + 3;
+            const int cj = PLANES ? thr : thr - K + pop_b[nl];
+            u3[j] = cj + (PLANES ? 1 : 3);
+            tj[j] = (PLANES ? 0.5f : 0.25f) * float(cj);
             flip_mask[j] = __ballot(flip);
             live_mask[j] = __ballot(live);
         }
         const int64_t nw = (int64_t(N) + 31) >> 5;
         const int64_t w = ((int64_t(col0) + wn * 32 * WN) >> 5) + fh;       // word column of this lane
+        auto pack_and_store = [&](auto fp_tag) {
+            constexpr bool FP = decltype(fp_tag)::value;
 #pragma unroll
-        for (int i = 0; i < WM; ++i) {
-            int words = 0;
+            for (int i = 0; i < WM; ++i) {
+                int words = 0;
 #pragma unroll
-            for (int vq = 0; vq < 4; ++vq) {
-                const int ml = wm * 32 * WM + i * 32 + 8 * vq + 4 * fh;
-                const int4 pa2 = *reinterpret_cast<const int4*>(&pop_a[ml]);
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int ml = wm * 32 * WM + i * 32 + 8 * vq + 4 * fh;
+                    const int4 pa2 = *reinterpret_cast<const int4*>(&pop_a[ml]);
+                    const float4 paf = *reinterpret_cast<const float4*>(&pop_af[ml]);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int pa = e == 0 ? pa2.x : e == 1 ? pa2.y : e == 2 ? pa2.z : pa2.w;
+                    for (int e = 0; e < 4; ++e) {
+                        const int pa = e == 0 ? pa2.x : e == 1 ? pa2.y : e == 2 ? pa2.z : pa2.w;
+                        const float pf = e == 0 ? paf.x : e == 1 ? paf.y : e == 2 ? paf.z : paf.w;
 #pragma unroll
-                    for (int j = 0; j < WN; ++j) {
-                        const bool p = int(acc[i][j][4 * vq + e]) >= ((u3[j] + pa) >> kShift);
-                        const uint64_t mask = (__ballot(p) ^ flip_mask[j]) & live_mask[j];
-                        words = bnn_llvm_writelane(int(uint32_t(mask)), 32 * j + 8 * vq + e, words);
-                        words = bnn_llvm_writelane(int(uint32_t(mask >> 32)), 32 * j + 8 * vq + 4 + e, words);
+                        for (int j = 0; j < WN; ++j) {
+                            const float sacc = acc[i][j][4 * vq + e];
+                            const bool p = FP ? (sacc >= tj[j] + pf) : (int(sacc) >= ((u3[j] + pa) >> kShift));
+                            const uint64_t mask = (__ballot(p) ^ flip_mask[j]) & live_mask[j];
+                            words = bnn_llvm_writelane(int(uint32_t(mask)), 32 * j + 8 * vq + e, words);
+                            words = bnn_llvm_writelane(int(uint32_t(mask >> 32)), 32 * j + 8 * vq + 4 + e, words);
+                        }
                     }
                 }
+                const int m = row0 + wm * 32 * WM + i * 32 + fr;
+                if (m < M && w < nw) bn.out[int64_t(m) * bn.ld_out + w] = uint32_t(words);
             }
-            const int m = row0 + wm * 32 * WM + i * 32 + fr;
-            if (m < M && w < nw) bn.out[int64_t(m) * bn.ld_out + w] = uint32_t(words);
-        }
+        };
+        if (fp_exact) pack_and_store(std::true_type{});
+        else pack_and_store(std::false_type{});
     }
 }
 
