@@ -319,6 +319,15 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
             }
         }
 
+        // Ordering pin: without it the compiler hoists the staging of the next tile (and with it
+        // the wait for the global loads issued at the top of this iteration) above the MFMA steps,
+        // which exposes the whole memory latency every iteration.  The empty asm "uses" the
+        // accumulators, so all MFMAs precede it, and clobbers memory, so the LDS stores follow it.
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+#pragma unroll
+            for (int j = 0; j < WN; ++j) asm volatile("" : "+v"(acc[i][j]) : : "memory");
+
         if (kt + 1 < n_ktiles) stage(buf ^ 1);
         __syncthreads();
     }
