@@ -348,16 +348,15 @@ static void launch_tiled(const uint32_t* A, int64_t lda, const uint32_t* B, int6
 
 // Kernel choice, from measurements on MI355X: the matrix-engine kernels are 2-4x faster than the
 // vector-ALU XNOR-popcount kernels down to a few dozen tiles.  Their 256 x 128 tile (two workgroups
-// per compute unit) wins only for long K with the fused epilogue on a grid of a thousand tiles or
-// more; otherwise the 128 x 128 tile (three workgroups per compute unit) hides short K loops and
-// the int32 stores better.  Tiny grids go to the 64 x 64 XNOR tiles, which spread over more
+// per compute unit) wins for long K on a grid of a thousand tiles or more; otherwise the
+// 128 x 128 tile (three workgroups per compute unit) hides short K loops better.  Tiny grids go to the 64 x 64 XNOR tiles, which spread over more
 // compute units; skinny outputs go to the K-split kernel; K beyond the exact-fp32 range stays on
 // the vector ALU.
 static int choose_kernel(int64_t M, int64_t N, int64_t K, bool fused) {
     if (!fused && (N <= 16 || M <= 4)) return KERNEL_KSPLIT;
     const int64_t tiles128 = ceil_div(M, 128) * ceil_div(N, 128);
     if (mfma_path_supports(K)) {
-        if (fused && K >= 4096 && ceil_div(M, 256) * ceil_div(N, 128) >= 1024) return KERNEL_MFMA;
+        if (K >= 4096 && ceil_div(M, 256) * ceil_div(N, 128) >= 1024) return KERNEL_MFMA;
         if (tiles128 >= 32) return KERNEL_MFMA128;
     }
     return tiles128 >= 512 ? KERNEL_TILED128 : KERNEL_TILED64;
