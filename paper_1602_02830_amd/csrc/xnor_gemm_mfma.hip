@@ -44,41 +44,11 @@
 //           B contributes one word per lane half and tile, widened once per tile.
 // The tile is long enough that the global loads of the next tile, issued
 // before the MFMA steps, have landed when they are staged.
-#include <type_traits>
-
 #include "bnn_internal.h"
 #include "gemm_staging.h"
+#include "mfma_fp4.h"
 
 namespace bnn {
-
-typedef int v8i __attribute__((ext_vector_type(8)));
-typedef float v16f __attribute__((ext_vector_type(16)));
-
-constexpr int kMfmaKT = 16;              // words of A per row and staged tile
-constexpr int kMfmaKQ = kMfmaKT / 4;     // 16-byte quads per row per tile
-constexpr int64_t kMfmaMaxAcc = int64_t(1) << 24;   // exact fp32 accumulation of non-negative integers
-
-__device__ inline v8i widen_fp4_a(uint32_t w) {
-    v8i f = {int(w & 0x11111111u), int(w & 0x22222222u), int(w & 0x44444444u), int((w >> 2) & 0x22222222u),
-             0, 0, 0, 0};
-    return f;
-}
-
-__device__ inline v8i widen_fp4_b(uint32_t w) {
-    const uint32_t r = w >> 2;
-    v8i f = {int((w << 2) & 0x44444444u), int(w & 0x22222222u), int(r & 0x11111111u), int(r & 0x22222222u),
-             0, 0, 0, 0};
-    return f;
-}
-
-__device__ inline int popc4(uint4 v) { return __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w); }
-
-// Sum over k of the four plane words of a quad weighted 2^p0 .. 2^(p0+3).
-__device__ inline int popc4_weighted(uint4 v, int p0) {
-    return (__popc(v.x) + 2 * __popc(v.y) + 4 * __popc(v.z) + 8 * __popc(v.w)) << p0;
-}
-
-__device__ inline uint32_t quad_word(const uint4& q, int s) { return s == 0 ? q.x : s == 1 ? q.y : s == 2 ? q.z : q.w; }
 
 template <int WM, int WN, bool VEC, bool FUSED, bool PLANES, bool CONV>
 __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
@@ -309,13 +279,17 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
                     for (int j = 0; j < WN; ++j) fb[j] = widen_fp4_b(quad_word(bw[j], s));
                 }
                 // planes: this step is plane 4*hq + s, weight 2^(4*hq + s) through the A block scale.
-                const int scale_a = PLANES ? kScaleOne + (4 * hq + s) * 0x01010101 : kScaleOne;
+                // Without planes both block scales are 1: literal zero scale operands make the
+                // compiler emit the plain v_mfma_f32_32x32x64_f8f6f4 (unit scale, half the encoding
+                // size and no scale-register reads) instead of the scaled pair.
+                const int scale_a = PLANES ? kScaleOne + (4 * hq + s) * 0x01010101 : 0;
+                constexpr int scale_b = PLANES ? kScaleOne : 0;
 #pragma unroll
                 for (int i = 0; i < WM; ++i)
 #pragma unroll
                     for (int j = 0; j < WN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                            fa[i], fb[j], acc[i][j], 4 /* A: fp4 */, 4 /* B: fp4 */, 0, scale_a, 0, kScaleOne);
+                            fa[i], fb[j], acc[i][j], 4 /* A: fp4 */, 4 /* B: fp4 */, 0, scale_a, 0, scale_b);
             }
         }
 
@@ -353,91 +327,7 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
     }
     __syncthreads();
 
-    // Result from the matrix-engine sum S:  binary  K - 2pa - 2pb + 4S,   planes  2S - rowsum.
-    // Accumulator register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32 of its 32x32 block.
-    constexpr int kShift = PLANES ? 1 : 2;
-    if (!FUSED) {
-#pragma unroll
-        for (int j = 0; j < WN; ++j) {
-            const int nl = wn * 32 * WN + j * 32 + fr;
-            const int n = col0 + nl;
-            const int base_n = PLANES ? 0 : K - pop_b[nl];
-#pragma unroll
-            for (int i = 0; i < WM; ++i)
-#pragma unroll
-                for (int vq = 0; vq < 4; ++vq) {
-                    const int ml = wm * 32 * WM + i * 32 + 8 * vq + 4 * fh;
-                    const int4 pa2 = *reinterpret_cast<const int4*>(&pop_a[ml]);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int m = row0 + ml + e;
-                        const int pa = e == 0 ? pa2.x : e == 1 ? pa2.y : e == 2 ? pa2.z : pa2.w;
-                        const int dot = base_n - pa + (int(acc[i][j][4 * vq + e]) << kShift);
-                        if (m < M && n < N) C[int64_t(m) * ldc + n] = dot;
-                    }
-                }
-        }
-    } else {
-        // bit(m, n) = (result >= thr[n]) XOR flip[n], i.e.
-        //   binary: S >= ceil((thr - K + 2pb + 2pa) / 4),   planes: S >= ceil((thr + rowsum) / 2).
-        // A ballot over one accumulator register gives, in its low half, the 32-column word of
-        // the row held by lanes 0-31 and, in its high half, that of the row 4 below.  The words
-        // of one 32-row block are gathered with v_writelane so that lane r (block j = 0) and
-        // lane 32 + r (block j = 1) end up holding row r's two words: one store per block row.
-        static_assert(WN == 2, "the fused epilogue pairs the two column blocks with the two lane halves");
-        // While every term stays below 2^22 the comparison is done in float, where it is exact
-        // (all terms are multiples of 1/4): S >= (thr - K + 2pb)/4 + 2pa/4, resp. S >= thr/2 + rowsum/2.
-        // That is one add and one compare per element instead of four integer operations.
-        const bool fp_exact = PLANES ? (255 * int64_t(K) < (int64_t(1) << 22)) : (K <= (1 << 21));
-        int u3[WN];
-        float tj[WN];
-        uint64_t flip_mask[WN], live_mask[WN];
-#pragma unroll
-        for (int j = 0; j < WN; ++j) {
-            const int nl = wn * 32 * WN + j * 32 + fr;
-            const int n = col0 + nl;
-            const bool live = n < N;
-            const int thr = live ? bn.thr[n] : 0;
-            const bool flip = live && ((bn.flip_bits[n >> 5] >> (n & 31)) & 1u) != 0u;
-            const int cj = PLANES ? thr : thr - K + pop_b[nl];
-            u3[j] = cj + (PLANES ? 1 : 3);
-            tj[j] = (PLANES ? 0.5f : 0.25f) * float(cj);
-            flip_mask[j] = __ballot(flip);
-            live_mask[j] = __ballot(live);
-        }
-        const int64_t nw = (int64_t(N) + 31) >> 5;
-        const int64_t w = ((int64_t(col0) + wn * 32 * WN) >> 5) + fh;       // word column of this lane
-        auto pack_and_store = [&](auto fp_tag) {
-            constexpr bool FP = decltype(fp_tag)::value;
-#pragma unroll
-            for (int i = 0; i < WM; ++i) {
-                int words = 0;
-#pragma unroll
-                for (int vq = 0; vq < 4; ++vq) {
-                    const int ml = wm * 32 * WM + i * 32 + 8 * vq + 4 * fh;
-                    const int4 pa2 = *reinterpret_cast<const int4*>(&pop_a[ml]);
-                    const float4 paf = *reinterpret_cast<const float4*>(&pop_af[ml]);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int pa = e == 0 ? pa2.x : e == 1 ? pa2.y : e == 2 ? pa2.z : pa2.w;
-                        const float pf = e == 0 ? paf.x : e == 1 ? paf.y : e == 2 ? paf.z : paf.w;
-#pragma unroll
-                        for (int j = 0; j < WN; ++j) {
-                            const float sacc = acc[i][j][4 * vq + e];
-                            const bool p = FP ? (sacc >= tj[j] + pf) : (int(sacc) >= ((u3[j] + pa) >> kShift));
-                            const uint64_t mask = (__ballot(p) ^ flip_mask[j]) & live_mask[j];
-                            words = bnn_llvm_writelane(int(uint32_t(mask)), 32 * j + 8 * vq + e, words);
-                            words = bnn_llvm_writelane(int(uint32_t(mask >> 32)), 32 * j + 8 * vq + 4 + e, words);
-                        }
-                    }
-                }
-                const int m = row0 + wm * 32 * WM + i * 32 + fr;
-                if (m < M && w < nw) bn.out[int64_t(m) * bn.ld_out + w] = uint32_t(words);
-            }
-        };
-        if (fp_exact) pack_and_store(std::true_type{});
-        else pack_and_store(std::false_type{});
-    }
+    mfma_epilogue<WM, WN, FUSED, PLANES>(acc, pop_a, pop_af, pop_b, C, ldc, bn, M, N, K, row0, col0, wm, wn, fr, fh);
 }
 
 template <int WM, bool FUSED, bool PLANES, bool CONV>
