@@ -41,12 +41,15 @@ __device__ inline uint32_t quad_word(const uint4& q, int s) { return s == 0 ? q.
 // Epilogue of a wavefront that owns WM x WN blocks of 32 x 32 fp32 accumulators at block
 // position (wm, wn) of a (64*WM) x (64*WN) workgroup tile whose first row / column is row0 / col0.
 // pop_a[tile row] / pop_b[tile column] hold 2*popcount (binary) or the plain row sum of the 8-bit
-// inputs (planes, pop_b unused); pop_af[tile row] = pop_a / 4 (binary) or / 2 (planes) as float.
+// inputs (planes, pop_b unused); pop_af[tile row] = pop_a / 4 (binary) or / 2 (planes) as float;
+// thr_s[tile column] / flip_s[tile column / 32]: the tile's thresholds and flip words (fused only,
+// zero for columns beyond N).
 // fr = lane % 32, fh = lane / 32.
 template <int WM, int WN, bool FUSED, bool PLANES>
 __device__ inline void mfma_epilogue(const v16f (&acc)[WM][WN], const int* pop_a, const float* pop_af,
-                                     const int* pop_b, int32_t* __restrict__ C, int64_t ldc, const BnSignArgs& bn,
-                                     int M, int N, int K, int row0, int col0, int wm, int wn, int fr, int fh) {
+                                     const int* pop_b, const int* thr_s, const uint32_t* flip_s,
+                                     int32_t* __restrict__ C, int64_t ldc, const BnSignArgs& bn, int M, int N, int K,
+                                     int row0, int col0, int wm, int wn, int fr, int fh) {
     // Result from the matrix-engine sum S:  binary  K - 2pa - 2pb + 4S,   planes  2S - rowsum.
     // Accumulator register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32 of its 32x32 block.
     constexpr int kShift = PLANES ? 1 : 2;
@@ -91,8 +94,8 @@ __device__ inline void mfma_epilogue(const v16f (&acc)[WM][WN], const int* pop_a
             const int nl = wn * 32 * WN + j * 32 + fr;
             const int n = col0 + nl;
             const bool live = n < N;
-            const int thr = live ? bn.thr[n] : 0;
-            const bool flip = live && ((bn.flip_bits[n >> 5] >> (n & 31)) & 1u) != 0u;
+            const int thr = thr_s[nl];
+            const bool flip = ((flip_s[nl >> 5] >> (nl & 31)) & 1u) != 0u;          // col0 is a multiple of 32
             const int cj = PLANES ? thr : thr - K + pop_b[nl];
             u3[j] = cj + (PLANES ? 1 : 3);
             tj[j] = (PLANES ? 0.5f : 0.25f) * float(cj);

@@ -71,6 +71,8 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
     __shared__ __attribute__((aligned(16))) int pop_a[BM];
     __shared__ __attribute__((aligned(16))) int pop_b[BN];
     __shared__ __attribute__((aligned(16))) float pop_af[FUSED ? BM : 4];   // row term of the float threshold
+    __shared__ int thr_s[FUSED ? BN : 1];                  // the tile's thresholds and flip words, fetched
+    __shared__ uint32_t flip_s[FUSED ? BN / 32 : 1];       // before the K loop (read in the epilogue)
 
     int tile_m, tile_n;
     tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
@@ -241,6 +243,10 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
+    if (FUSED) {
+        if (tid < BN) thr_s[tid] = col0 + tid < N ? bn.thr[col0 + tid] : 0;
+        if (tid < BN / 32) flip_s[tid] = col0 + 32 * tid < N ? bn.flip_bits[(col0 >> 5) + tid] : 0u;
+    }
     if (n_ktiles > 0) {
         fetch(0);
         stage(0);
@@ -327,7 +333,8 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
     }
     __syncthreads();
 
-    mfma_epilogue<WM, WN, FUSED, PLANES>(acc, pop_a, pop_af, pop_b, C, ldc, bn, M, N, K, row0, col0, wm, wn, fr, fh);
+    mfma_epilogue<WM, WN, FUSED, PLANES>(acc, pop_a, pop_af, pop_b, thr_s, flip_s, C, ldc, bn, M, N, K, row0, col0, wm, wn,
+                                         fr, fh);
 }
 
 template <int WM, bool FUSED, bool PLANES, bool CONV>
