@@ -37,6 +37,7 @@ PEAK_I8_MFMA_TOPS = 5000.0                                # dense int8, 2*M*N*K 
 PEAK_FP4_MFMA_TFLOPS = 10100.0                            # dense fp4/fp6 MFMA, 2*M*N*K counting
 # HBM bytes per launch of the dominant kernel (fetched + written), from the FETCH_SIZE / WRITE_SIZE counter
 # runs summarised in profiles/xnor_gemm_mfma_mlp_batch10000.txt and profiles/xnor_gemm_tiled128_mlp_batch10000.txt.
+WARM_SECONDS = 0.05
 PROFILED_TRAFFIC_BYTES = {("mfma", True): 23.2e6 + 13.0e6, ("valu", False): 32.9e6 + 166.4e6}
 
 
@@ -45,20 +46,28 @@ def log(*a):
 
 
 def time_launches(fn, iters, warmup=2):
-    """Average duration in ms of fn() measured with events on the current stream."""
+    """Average duration in ms of fn(): `iters` back-to-back launches bracketed by one pair of events on
+    the current stream (an event pair around every single launch adds several microseconds to each,
+    which is a large share of the short kernels here).  Returns (average, average) for callers that
+    also report a minimum."""
     import torch
+    # The clocks need some tens of milliseconds of load to settle after an idle spell (host-side set-up):
+    # warm up for `warmup` launches and at least WARM_SECONDS.
     for _ in range(warmup):
         fn()
-    evs = []
+    t_end = time.perf_counter() + WARM_SECONDS
+    while time.perf_counter() < t_end:
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s.record()
     for _ in range(iters):
-        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        s.record()
         fn()
-        e.record()
-        evs.append((s, e))
+    e.record()
     torch.cuda.synchronize()
-    t = [s.elapsed_time(e) for s, e in evs]
-    return float(np.mean(t)), float(np.min(t))
+    t = s.elapsed_time(e) / iters
+    return float(t), float(t)
 
 
 def gemm_only(args, bnn, torch, dev):
@@ -95,8 +104,10 @@ def gemm_only(args, bnn, torch, dev):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    # Defaults: 300 warm-up steps (~50 ms: after the host-side set-up the GPU clocks take ~35 ms of load to
+    # settle, during which a step is up to 25 % slower), then 500 timed steps (~80 ms).
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=300)
     ap.add_argument("--unfused", action="store_true",
                     help="hidden layers as separate GEMM and BN+Sign launches (int32 pre-activations through HBM)")
     ap.add_argument("--valu", action="store_true",
@@ -145,16 +156,26 @@ def main():
     for _ in range(args.warmup):
         net.forward(xd)
     torch.cuda.synchronize()
-    dominant_layers = [1, 2]                # the two 4096 x 4096 layers: same kernel, same shape
-    events = {l: [] for l in dominant_layers}
+    # Dominant kernel: the two 4096 x 4096 layers (same kernel, same shape; consecutive launches when
+    # the epilogue is fused).  On every EVENT_EVERY-th timed step one pair of events brackets them (only
+    # the second one when a BN+Sign launch sits in between); on the other steps nothing is recorded,
+    # because each event record drains the queue and costs the step several microseconds.
+    dominant_layers = [1, 2] if fused else [2]
+    EVENT_EVERY = 10
+    pairs = []
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        net.forward(xd, gemm_events=events)
+    for i in range(args.steps):
+        if i % EVENT_EVERY == 0:
+            ev = {}
+            net.forward(xd, span_events=(dominant_layers[0], dominant_layers[-1], ev))
+            pairs.append(ev)
+        else:
+            net.forward(xd)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     images_per_s = batch / (ms_per_step * 1e-3)
-    gemm_ms = float(np.mean([s.elapsed_time(e) for l in dominant_layers for s, e in events[l]]))
+    gemm_ms = float(np.mean([ev["start"].elapsed_time(ev["end"]) for ev in pairs])) / len(dominant_layers)
     M, N, K = batch, 4096, 4096
     ops_per_launch = 2.0 * M * N * K
     achieved_tops = ops_per_launch / (gemm_ms * 1e-3) / 1e12
@@ -186,12 +207,14 @@ def main():
         result["roofline"] = {
             "bound": "alu", "kernel": kname, "achieved": achieved_tops, "peak": PEAK_BINARY_TOPS,
             "unit": "binary TOP/s (2*M*N*K/s; peak = 256 CU x 64 lanes x 2.4 GHz / 2 lane-ops per word x 64)",
-            "frac": achieved_tops / PEAK_BINARY_TOPS, "avg_launch_ms": gemm_ms, "traffic": traffic}
+            "frac": achieved_tops / PEAK_BINARY_TOPS, "avg_launch_ms": gemm_ms, "event_samples": len(pairs),
+            "traffic": traffic}
     else:
         result["roofline"] = {
             "bound": "mfma", "kernel": kname, "achieved": achieved_tops, "peak": PEAK_FP4_MFMA_TFLOPS,
             "unit": "TFLOP/s (fp4 MFMA, 2*M*N*K per launch)",
-            "frac": achieved_tops / PEAK_FP4_MFMA_TFLOPS, "avg_launch_ms": gemm_ms, "traffic": traffic}
+            "frac": achieved_tops / PEAK_FP4_MFMA_TFLOPS, "avg_launch_ms": gemm_ms, "event_samples": len(pairs),
+            "traffic": traffic}
 
     if args.calibration_copy:
         src = torch.zeros(256 * 1024 * 1024, dtype=torch.int32, device=dev)      # 1 GiB read + 1 GiB written

@@ -77,11 +77,12 @@ class BinaryMLP:
             self.s = [scratch[:, :n] if n != scratch.shape[1] else scratch for n in self.N[:-1]]
             self.s.append(torch.empty((batch, self.N[-1]), dtype=torch.int32, device=dev))
 
-    def forward(self, x: torch.Tensor, gemm_events=None) -> torch.Tensor:
+    def forward(self, x: torch.Tensor, span_events=None) -> torch.Tensor:
         """x: float32 device tensor [batch][K_0].  Returns the int32 scores [batch][N_last].
 
-        gemm_events: optional dict layer -> list; for those layers a (start, end) pair of
-        events is recorded on the current stream around the GEMM launch and appended.
+        span_events: optional (first_layer, last_layer, dict); one event is recorded on the current
+        stream before the GEMM launch of first_layer and one right after that of last_layer,
+        stored as dict["start"], dict["end"].
         """
         if self.input_uint8:
             B.pack_bitplanes(x, out=self.a_bits[0])
@@ -89,10 +90,9 @@ class BinaryMLP:
             B.pack_sign(x, out=self.a_bits[0])
         n_layers = len(self.w_bits)
         for l in range(n_layers):
-            timed = gemm_events is not None and l in gemm_events
-            if timed:
-                start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                start.record()
+            if span_events is not None and l == span_events[0]:
+                span_events[2]["start"] = torch.cuda.Event(enable_timing=True)
+                span_events[2]["start"].record()
             hidden = l + 1 < n_layers
             if self.input_uint8 and l == 0:
                 if self.fused and hidden:
@@ -106,9 +106,9 @@ class BinaryMLP:
             else:
                 B.xnor_gemm(self.a_bits[l], self.w_bits[l], self.K[l], out=self.s[l],
                             kernel=self.kernel if hidden else B.KERNEL_AUTO)
-            if timed:
-                end.record()
-                gemm_events[l].append((start, end))
+            if span_events is not None and l == span_events[1]:
+                span_events[2]["end"] = torch.cuda.Event(enable_timing=True)
+                span_events[2]["end"].record()
             if hidden and not self.fused:
                 B.bn_sign_pack(self.s[l], self.thr[l], self.flip[l], out=self.a_bits[l + 1])
         return self.s[-1]
