@@ -181,6 +181,19 @@ def test_bn_exact_small_numbers():
     assert Y2.tolist() == [[2.0]]
 
 
+def test_bn_epsilon_sits_inside_the_square_root():
+    """eps and var both powers of two, so sqrt(var + eps) is exact: a dropped eps, or one added outside
+    the root, changes the result.  var = 0, eps = 2^-8 -> inv = 16;  var = 3*2^-8 -> var + eps = 2^-6 -> inv = 8."""
+    eps = 2.0 ** -8
+    S = np.array([[5, 5]], np.int32)
+    Y = oracle.bn_float(S, [0.5, 0.5], [1.0, 1.0], [2.0, 2.0], [0.0, 3.0 * 2.0 ** -8], eps=eps)
+    assert Y.tolist() == [[0.5 * (3.0 * 16.0) + 1.0, 0.5 * (3.0 * 8.0) + 1.0]]
+    sgn = oracle.bn_sign(np.array([[1]], np.int32), [-1.0], [20.0], [0.0], [0.0], eps=eps)     # -16 + 20 >= 0
+    assert sgn.tolist() == [[1]]
+    sgn = oracle.bn_sign(np.array([[1]], np.int32), [-1.0], [15.0], [0.0], [0.0], eps=eps)     # -16 + 15 < 0
+    assert sgn.tolist() == [[-1]]
+
+
 def test_bn_matches_library_batch_norm_and_fp64():
     rng = np.random.default_rng(8)
     K, N = 1024, 257
