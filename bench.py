@@ -280,16 +280,47 @@ def main():
         log(f"gemm_i8_mfma 8192^3: {ms:.3f} ms = {ops / ms / 1e9:.1f} TOP/s; equal to xnor result: "
             f"{extras['gemm_i8_mfma_8192']['equal_to_xnor']}")
         del a8, b8, c2
-        ms, _ = time_launches(lambda: bnn.pack_sign(a_f, out=a_bits), 20)
-        bytes_ = n * n * 4 + n * n / 8
-        extras["pack_sign_8192x8192"] = {"ms": ms, "GBps": bytes_ / ms / 1e6, "frac_of_hbm_peak": bytes_ / ms / 1e6 / PEAK_HBM_GBS}
-        log(f"pack_sign 8192x8192: {ms:.3f} ms = {bytes_ / ms / 1e6:.0f} GB/s")
+        del a_f, b_f, c, a_bits, b_bits
+
+        # Streaming kernels on 32768 x 8192 inputs (1 GiB: four times the last-level cache, so the rate is HBM's).
+        rows_s = 4 * n
+        x_s = torch.empty((rows_s, n), dtype=torch.float32, device=dev).normal_()
+        bits_s = torch.empty((rows_s, n // 32), dtype=torch.int32, device=dev)
+        bytes_ = rows_s * n * 4 + rows_s * n / 8
+        ms, _ = time_launches(lambda: bnn.pack_sign(x_s, out=bits_s), 20)
+        extras["pack_sign_32768x8192"] = {"ms": ms, "GBps": bytes_ / ms / 1e6, "frac_of_hbm_peak": bytes_ / ms / 1e6 / PEAK_HBM_GBS}
+        log(f"pack_sign 32768x8192: {ms:.3f} ms = {bytes_ / ms / 1e6:.0f} GB/s")
+        c_s = x_s.view(torch.int32)                       # any int32 values do for the compare
         thr = torch.zeros(n, dtype=torch.int32, device=dev)
         flip = torch.zeros(n // 32, dtype=torch.int32, device=dev)
-        ms, _ = time_launches(lambda: bnn.bn_sign_pack(c, thr, flip, out=a_bits), 20)
-        extras["bn_sign_pack_8192x8192"] = {"ms": ms, "GBps": bytes_ / ms / 1e6, "frac_of_hbm_peak": bytes_ / ms / 1e6 / PEAK_HBM_GBS}
-        log(f"bn_sign_pack 8192x8192: {ms:.3f} ms = {bytes_ / ms / 1e6:.0f} GB/s")
-        del a_f, b_f, c, a_bits, b_bits
+        ms, _ = time_launches(lambda: bnn.bn_sign_pack(c_s, thr, flip, out=bits_s), 20)
+        extras["bn_sign_pack_32768x8192"] = {"ms": ms, "GBps": bytes_ / ms / 1e6, "frac_of_hbm_peak": bytes_ / ms / 1e6 / PEAK_HBM_GBS}
+        log(f"bn_sign_pack 32768x8192: {ms:.3f} ms = {bytes_ / ms / 1e6:.0f} GB/s")
+        del x_s, c_s, bits_s
+
+        # The small dense layer (64 x 1024 x 1024) and the ragged sweep: launch-latency bound, time only.
+        A0, Bm0, bn0 = synth.config_dense()
+        a0 = bnn.pack_sign(torch.from_numpy(A0.astype(np.float32)).to(dev))
+        b0 = bnn.pack_sign(torch.from_numpy(np.ascontiguousarray(Bm0.T).astype(np.float32)).to(dev))
+        thr0, flip0 = bnn.bn_fold(*bn0, eps, 1024)
+        thr0, flip0 = torch.from_numpy(thr0).to(dev), torch.from_numpy(flip0.view(np.int32)).to(dev)
+        out0 = torch.empty((64, 32), dtype=torch.int32, device=dev)
+        ms, _ = time_launches(lambda: bnn.xnor_gemm_bn_sign_pack(a0, b0, 1024, thr0, flip0, out=out0), 200)
+        extras["dense_64x1024x1024_fused_layer"] = {"us": ms * 1e3, "note": "launch-latency bound; includes the host-side launch cost"}
+        log(f"dense layer 64x1024x1024 (fused GEMM + BN + Sign): {ms * 1e3:.1f} us per launch")
+        cases = []
+        for idx, (Mr, Nr, Kr, _p) in enumerate(synth.ragged_cases()):
+            Ar, Br = synth.config_ragged(idx)
+            cases.append((bnn.pack_sign(torch.from_numpy(Ar.astype(np.float32)).to(dev)),
+                          bnn.pack_sign(torch.from_numpy(np.ascontiguousarray(Br.T).astype(np.float32)).to(dev)), Kr,
+                          torch.empty((Mr, Nr), dtype=torch.int32, device=dev)))
+        def sweep():
+            for ar, br, Kr, cr in cases:
+                bnn.xnor_gemm(ar, br, Kr, out=cr)
+        ms, _ = time_launches(sweep, 5, warmup=1)
+        extras["ragged_sweep_336_cases"] = {"ms_total": ms, "us_per_case": ms * 1e3 / len(cases)}
+        log(f"ragged sweep, {len(cases)} GEMMs: {ms:.3f} ms in total ({ms * 1e3 / len(cases):.1f} us per case)")
+        del cases
 
         conv = {}
         for layer, (ch, hw) in enumerate(synth.CONV_LAYERS):

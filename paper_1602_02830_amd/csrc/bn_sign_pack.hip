@@ -19,20 +19,25 @@ template <bool VEC>
 __global__ __launch_bounds__(kBnThreads) void bn_sign_pack_kernel(
     const int32_t* __restrict__ C, int64_t ldc, int64_t M, int64_t N,
     const int32_t* __restrict__ thr, const uint32_t* __restrict__ flip_bits,
-    uint32_t* __restrict__ out, int64_t ld_out, int64_t nw, int64_t n_words) {
+    uint32_t* __restrict__ out, int64_t ld_out, int64_t nw, int64_t n_words, int64_t slice_row, int64_t slice_word,
+    int64_t pass_row, int64_t pass_word) {
+    // Word groups are numbered row-major (g = row * nw + word).  A workgroup takes kBnUnroll consecutive
+    // slices of 32 groups per pass (16 KB of contiguous input when rows are dense), thread t group t/8 of
+    // each slice; passes are a whole grid apart.  (row, word) are stepped by (groups / nw, groups % nw)
+    // with a carry: one division per thread, not per group.
+    constexpr int kSlice = kBnThreads / 8;
     const int q = threadIdx.x & 7;
-    const int64_t groups_per_pass = int64_t(gridDim.x) * (kBnThreads / 8);
-    int64_t g0 = int64_t(blockIdx.x) * (kBnThreads / 8) + (threadIdx.x >> 3);
+    const int64_t pass_groups = int64_t(gridDim.x) * kSlice * kBnUnroll;
+    int64_t g0 = int64_t(blockIdx.x) * kSlice * kBnUnroll + (threadIdx.x >> 3);
+    int64_t row0 = g0 / nw, w0 = g0 - row0 * nw;
 
-    for (; g0 < n_words; g0 += groups_per_pass * kBnUnroll) {
+    for (; g0 < n_words; g0 += pass_groups) {
         int4 c[kBnUnroll];
         int64_t row_of[kBnUnroll], word_of[kBnUnroll];
+        int64_t row = row0, w = w0;
 #pragma unroll
         for (int u = 0; u < kBnUnroll; ++u) {
-            const int64_t g = g0 + u * groups_per_pass;
-            const bool live = g < n_words;
-            const int64_t row = live ? g / nw : 0;
-            const int64_t w = live ? g - row * nw : 0;
+            const bool live = g0 + u * kSlice < n_words;
             row_of[u] = live ? row : -1;
             word_of[u] = w;
             const int64_t n0 = w * 32 + q * 4;
@@ -48,6 +53,18 @@ __global__ __launch_bounds__(kBnThreads) void bn_sign_pack_kernel(
                     if (n0 + 3 < N) c[u].w = p[3];
                 }
             }
+            row += slice_row;
+            w += slice_word;
+            if (w >= nw) {
+                w -= nw;
+                ++row;
+            }
+        }
+        row0 += pass_row;
+        w0 += pass_word;
+        if (w0 >= nw) {
+            w0 -= nw;
+            ++row0;
         }
 #pragma unroll
         for (int u = 0; u < kBnUnroll; ++u) {
@@ -94,12 +111,13 @@ extern "C" int bnn_bn_sign_pack(const int32_t* C, int64_t ldc, int64_t M, int64_
     const int64_t max_blocks = 256 * 32;
     if (blocks > max_blocks) blocks = max_blocks;
     const bool vec = aligned_to(C, 16) && aligned_to(thr, 16) && ldc % 4 == 0;
+    const int64_t slice = kBnThreads / 8, pass = blocks * slice * kBnUnroll;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (vec)
         hipLaunchKernelGGL(bn_sign_pack_kernel<true>, dim3(unsigned(blocks)), dim3(kBnThreads), 0, s, C, ldc,
-                           M, N, thr, flip_bits, out, ld_out, nw, n_words);
+                           M, N, thr, flip_bits, out, ld_out, nw, n_words, slice / nw, slice % nw, pass / nw, pass % nw);
     else
         hipLaunchKernelGGL(bn_sign_pack_kernel<false>, dim3(unsigned(blocks)), dim3(kBnThreads), 0, s, C, ldc,
-                           M, N, thr, flip_bits, out, ld_out, nw, n_words);
+                           M, N, thr, flip_bits, out, ld_out, nw, n_words, slice / nw, slice % nw, pass / nw, pass % nw);
     return check_launch();
 }

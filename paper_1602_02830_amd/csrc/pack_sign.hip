@@ -17,24 +17,44 @@ constexpr int kPackUnroll = 4;   // words per group of 8 lanes per pass (loads i
 
 __device__ inline uint32_t ge_zero(float v) { return v >= 0.0f ? 1u : 0u; }
 
+// Word groups are numbered row-major (g = row * kw + word).  (row, word) coordinates are stepped by a
+// constant number of groups with a carry instead of being divided out for every group.
+struct WordStep {
+    int64_t d_row;   // groups / kw
+    int64_t d_word;  // groups % kw
+};
+
+inline WordStep word_step(int64_t groups, int64_t kw) { return WordStep{groups / kw, groups % kw}; }
+
+__device__ inline void advance(int64_t& row, int64_t& w, const WordStep& st, int64_t kw) {
+    row += st.d_row;
+    w += st.d_word;
+    if (w >= kw) {
+        w -= kw;
+        ++row;
+    }
+}
+
+// A workgroup takes kPackUnroll consecutive slices of 32 word groups per pass (16 KB of contiguous
+// input when rows are dense), thread t group t/8 of each slice; passes are a whole grid apart.
 template <bool VEC>
 __global__ __launch_bounds__(kPackThreads) void pack_sign_kernel(
     const float* __restrict__ x, int64_t rows, int64_t cols, int64_t ld_x,
-    uint32_t* __restrict__ out, int64_t ld_out, int64_t kw, int64_t n_words) {
+    uint32_t* __restrict__ out, int64_t ld_out, int64_t kw, int64_t n_words, WordStep slice, WordStep pass) {
+    constexpr int kSlice = kPackThreads / 8;             // word groups per slice
     const int q = threadIdx.x & 7;                       // lane within its group
-    const int64_t groups_per_pass = int64_t(gridDim.x) * (kPackThreads / 8);
-    int64_t g0 = int64_t(blockIdx.x) * (kPackThreads / 8) + (threadIdx.x >> 3);
+    const int64_t pass_groups = int64_t(gridDim.x) * kSlice * kPackUnroll;
+    int64_t g0 = int64_t(blockIdx.x) * kSlice * kPackUnroll + (threadIdx.x >> 3);
+    int64_t row0 = g0 / kw, w0 = g0 - row0 * kw;         // the only division of the thread
 
-    for (; g0 < n_words; g0 += groups_per_pass * kPackUnroll) {
+    for (; g0 < n_words; g0 += pass_groups) {
         float v[kPackUnroll][4];
         int64_t word_of[kPackUnroll];
         int64_t row_of[kPackUnroll];
+        int64_t row = row0, w = w0;
 #pragma unroll
         for (int u = 0; u < kPackUnroll; ++u) {
-            const int64_t g = g0 + u * groups_per_pass;
-            const bool live = g < n_words;
-            const int64_t row = live ? g / kw : 0;
-            const int64_t w = live ? g - row * kw : 0;
+            const bool live = g0 + u * kSlice < n_words;
             row_of[u] = live ? row : -1;
             word_of[u] = w;
             const int64_t c0 = w * 32 + q * 4;
@@ -51,6 +71,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_sign_kernel(
                         if (c0 + e < cols) v[u][e] = p[e];
                 }
             }
+            advance(row, w, slice, kw);
         }
 #pragma unroll
         for (int u = 0; u < kPackUnroll; ++u) {
@@ -59,6 +80,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_sign_kernel(
             const uint32_t word = or_reduce8(nib << (4 * q));
             if (q == 0 && row_of[u] >= 0) out[row_of[u] * ld_out + word_of[u]] = word;
         }
+        advance(row0, w0, pass, kw);
     }
 }
 
@@ -74,13 +96,13 @@ __global__ __launch_bounds__(kPackThreads) void pack_sign_kernel(
 template <bool VEC>
 __global__ __launch_bounds__(kPackThreads) void pack_bitplanes_kernel(
     const uint8_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ld_x,
-    uint32_t* __restrict__ out, int64_t ld_out, int64_t kw, int64_t n_groups) {
+    uint32_t* __restrict__ out, int64_t ld_out, int64_t kw, int64_t n_groups, WordStep st) {
+    // One word group per thread group and pass; passes are a whole grid apart (step st).
     const int q = threadIdx.x & 7;
     const int64_t groups_per_pass = int64_t(gridDim.x) * (kPackThreads / 8);
-    for (int64_t g = int64_t(blockIdx.x) * (kPackThreads / 8) + (threadIdx.x >> 3); g < n_groups;
-         g += groups_per_pass) {
-        const int64_t row = g / kw;
-        const int64_t w = g - row * kw;
+    int64_t g = int64_t(blockIdx.x) * (kPackThreads / 8) + (threadIdx.x >> 3);
+    int64_t row = g / kw, w = g - row * kw;
+    for (; g < n_groups; g += groups_per_pass) {
         const int64_t c0 = w * 32 + q * 4;
         const uint8_t* p = x + row * ld_x + c0;
         uint32_t d = 0u;                                  // out-of-range elements read as 0: all planes 0
@@ -99,6 +121,7 @@ __global__ __launch_bounds__(kPackThreads) void pack_bitplanes_kernel(
             if (q == pl) mine = word;
         }
         out[row * ld_out + 8 * w + q] = mine;
+        advance(row, w, st, kw);
     }
 }
 
@@ -117,13 +140,14 @@ extern "C" int bnn_pack_bitplanes(const uint8_t* x, int64_t rows, int64_t cols, 
     int64_t blocks = ceil_div(n_groups, kPackThreads / 8);
     if (blocks > 256 * 32) blocks = 256 * 32;
     const bool vec = aligned_to(x, 4) && (ld_x % 4 == 0);
+    const WordStep st = word_step(blocks * (kPackThreads / 8), kw);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (vec)
         hipLaunchKernelGGL(pack_bitplanes_kernel<true>, dim3(unsigned(blocks)), dim3(kPackThreads), 0, s, x, rows,
-                           cols, ld_x, out, ld_out, kw, n_groups);
+                           cols, ld_x, out, ld_out, kw, n_groups, st);
     else
         hipLaunchKernelGGL(pack_bitplanes_kernel<false>, dim3(unsigned(blocks)), dim3(kPackThreads), 0, s, x, rows,
-                           cols, ld_x, out, ld_out, kw, n_groups);
+                           cols, ld_x, out, ld_out, kw, n_groups, st);
     return check_launch();
 }
 
@@ -143,12 +167,14 @@ extern "C" int bnn_pack_sign(const float* x, int64_t rows, int64_t cols, int64_t
     const int64_t max_blocks = 256 * 32;   // 256 CUs, enough blocks in flight to cover HBM latency
     if (blocks > max_blocks) blocks = max_blocks;
     const bool vec = aligned_to(x, 16) && (ld_x % 4 == 0);
+    const WordStep slice = word_step(groups_per_block, kw);
+    const WordStep pass = word_step(blocks * groups_per_block * kPackUnroll, kw);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (vec)
         hipLaunchKernelGGL(pack_sign_kernel<true>, dim3(unsigned(blocks)), dim3(kPackThreads), 0, s,
-                           x, rows, cols, ld_x, out, ld_out, kw, n_words);
+                           x, rows, cols, ld_x, out, ld_out, kw, n_words, slice, pass);
     else
         hipLaunchKernelGGL(pack_sign_kernel<false>, dim3(unsigned(blocks)), dim3(kPackThreads), 0, s,
-                           x, rows, cols, ld_x, out, ld_out, kw, n_words);
+                           x, rows, cols, ld_x, out, ld_out, kw, n_words, slice, pass);
     return check_launch();
 }
