@@ -67,6 +67,45 @@ def test_argument_validation_happens_before_any_launch():
     assert lib.bnn_unpack_i8(p, 1, 2, 33, p, 36, None) == INVALID
 
 
+def test_argument_validation_of_the_fused_bitplane_and_conv_entry_points():
+    lib = bnn.load_library()
+    buf = (ctypes.c_uint32 * 64)()
+    p = ctypes.addressof(buf)
+    INVALID, ALIGN, UNSUPPORTED = 1, 2, 3
+    # fused hidden layer: short leading dimensions, null thresholds, unknown kernel id, empty problem
+    assert lib.bnn_xnor_gemm_bn_sign_pack(p, 1, p, 2, 4, 4, 33, p, p, p, 1, None) == INVALID     # lda < ceil(K/32)
+    assert lib.bnn_xnor_gemm_bn_sign_pack(p, 2, p, 2, 4, 40, 33, p, p, p, 1, None) == INVALID    # ld_out < ceil(N/32)
+    assert lib.bnn_xnor_gemm_bn_sign_pack(p, 2, p, 2, 4, 4, 33, None, p, p, 1, None) == INVALID
+    assert lib.bnn_xnor_gemm_bn_sign_pack(p, 2, p, 2, 4, 4, 33, p, p, p + 2, 1, None) == ALIGN
+    assert lib.bnn_xnor_gemm_bn_sign_pack(p, 2, p, 2, 0, 4, 33, p, p, p, 1, None) == 0
+    assert lib.bnn_xnor_gemm_bn_sign_pack_kernel(p, 2, p, 2, 4, 4, 33, p, p, p, 1, 3, None) == INVALID   # no fused K-split
+    assert lib.bnn_xnor_gemm_bn_sign_pack_kernel(p, 2, p, 2, 4, 4, 33, p, p, p, 1, 99, None) == INVALID
+    # 8-bit first layer: a row holds 8 words per K-word
+    assert lib.bnn_pack_bitplanes(p, -1, 4, 4, p, 8, None) == INVALID
+    assert lib.bnn_pack_bitplanes(p, 2, 40, 40, p, 15, None) == INVALID                           # ld_out < 8 * ceil(cols/32)
+    assert lib.bnn_pack_bitplanes(p, 2, 40, 39, p, 16, None) == INVALID                           # ld_x < cols
+    assert lib.bnn_pack_bitplanes(p, 0, 40, 40, p, 16, None) == 0
+    assert lib.bnn_bitplane_gemm(p, 15, p, 2, p, 4, 4, 4, 33, None) == INVALID                    # ldx < 8 * ceil(K/32)
+    assert lib.bnn_bitplane_gemm(p, 16, p, 2, p, 3, 4, 4, 33, None) == INVALID                    # ldc < N
+    assert lib.bnn_bitplane_gemm(p, 16, p, 2, p, 4, 0, 4, 33, None) == 0
+    assert lib.bnn_bitplane_gemm(p, 8 * 2 ** 12, p, 2 ** 12, p, 4, 4, 4, 2 ** 17, None) == UNSUPPORTED   # 255 K >= 2^24
+    assert lib.bnn_bitplane_gemm_bn_sign_pack(p, 16, p, 2, 4, 4, 33, None, p, p, 1, None) == INVALID
+    # implicit-GEMM convolution: geometry, leading dimensions, channel granularity
+    assert lib.bnn_conv_xnor(p, 1, 4, 4, 128, p, 36, 4, 3, 3, 0, 1, p, 4, None) == INVALID        # stride 0
+    assert lib.bnn_conv_xnor(p, 1, 4, 4, 128, p, 35, 4, 3, 3, 1, 1, p, 4, None) == INVALID        # ldw < 9 * Cin / 32
+    assert lib.bnn_conv_xnor(p, 1, 4, 4, 128, p, 36, 4, 3, 3, 1, 1, p, 3, None) == INVALID        # lds < Cout
+    assert lib.bnn_conv_xnor(p, 1, 1, 1, 128, p, 36, 4, 3, 3, 1, 0, p, 4, None) == INVALID        # no output pixel
+    assert lib.bnn_conv_xnor(p, 1, 4, 4, 64, p, 18, 4, 3, 3, 1, 1, p, 4, None) == UNSUPPORTED     # Cin % 128 != 0
+    assert lib.bnn_conv_xnor(p, 0, 4, 4, 128, p, 36, 4, 3, 3, 1, 1, p, 4, None) == 0
+    assert lib.bnn_conv_bn_sign_pack(p, 1, 4, 4, 128, p, 36, 40, 3, 3, 1, 1, p, p, p, 1, None) == INVALID   # ld_out < ceil(Cout/32)
+    assert lib.bnn_conv_bn_sign_pack(p, 1, 4, 4, 128, p, 36, 4, 3, 3, 1, 1, None, p, p, 1, None) == INVALID
+    # pooling on bits: window larger than the map, zero stride, empty batch
+    assert lib.bnn_maxpool_bits(p, 1, 2, 2, 32, 3, 3, 1, None, p, None) == INVALID
+    assert lib.bnn_maxpool_bits(p, 1, 4, 4, 32, 2, 2, 0, None, p, None) == INVALID
+    assert lib.bnn_maxpool_bits(None, 1, 4, 4, 32, 2, 2, 2, None, p, None) == INVALID
+    assert lib.bnn_maxpool_bits(p, 0, 4, 4, 32, 2, 2, 2, None, p, None) == 0
+
+
 # ------------------------------------------------------------------ bnn_bn_fold
 
 def _fold_matches_oracle_everywhere(bn, K, eps=oracle.EPS_DEFAULT):
