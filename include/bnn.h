@@ -122,6 +122,7 @@ int bnn_bn_fold(const float *gamma, const float *beta, const float *mean,
  *   out[m][n/32] bit (n%32) = (C[m][n] >= thr[n]) XOR flip[n]
  *   C    [M][ldc] int32, ldc >= N
  *   thr  [N] int32 (device), flip_bits [ceil(N/32)] uint32 (device), from bnn_bn_fold
+ *        (any int32 is a valid threshold; pad bits of the last flip word must be 0)
  *   out  [M][ld_out] uint32, ld_out >= ceil(N/32); pad bits of the last word 0;
  *        words beyond ceil(N/32) untouched
  * Fast path when C and thr are 16-byte aligned and ldc % 4 == 0.
@@ -141,7 +142,7 @@ int bnn_bn_sign_pack(const int32_t *C, int64_t ldc, int64_t M, int64_t N,
  * Arguments as in those two calls (A [M][lda], B [N][ldb] packed rows of K bits;
  * thr [N], flip_bits [ceil(N/32)] device arrays from bnn_bn_fold;
  * out [M][ld_out], ld_out >= ceil(N/32), pad bits 0, words beyond untouched).
- * The result is bit-identical to the two-call sequence.
+ * The result is bit-identical to the two-call sequence for every int32 threshold.
  */
 int bnn_xnor_gemm_bn_sign_pack(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb,
                                int64_t M, int64_t N, int64_t K, const int32_t *thr,

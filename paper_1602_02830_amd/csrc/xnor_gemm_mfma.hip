@@ -244,7 +244,10 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
     if (FUSED) {
-        if (tid < BN) thr_s[tid] = col0 + tid < N ? bn.thr[col0 + tid] : 0;
+        // No result exceeds lim in magnitude, so clamping a threshold to [-lim, lim] changes no output
+        // bit and keeps the bounds the epilogue derives from it inside int32 for any caller-given value.
+        const int lim = (PLANES ? 255 * K : K) + 1;
+        if (tid < BN) thr_s[tid] = col0 + tid < N ? max(-lim, min(lim, bn.thr[col0 + tid])) : 0;
         if (tid < BN / 32) flip_s[tid] = col0 + 32 * tid < N ? bn.flip_bits[(col0 >> 5) + tid] : 0u;
     }
     if (n_ktiles > 0) {

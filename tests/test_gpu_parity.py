@@ -266,6 +266,26 @@ def test_fused_layer_matches_float_bn_then_sign(M, N, K, kernel):
     assert torch.equal(two, out[:, :nw])
 
 
+@pytest.mark.parametrize("kernel", ["auto", "tiled128", "tiled64", "mfma", "mfma128"])
+def test_fused_layer_with_thresholds_outside_the_result_range(kernel):
+    """Thresholds need not come from the fold: any int32 is a valid threshold, including values far
+    outside [-K, K] (constant channels).  Expected bits: (dot >= thr) XOR flip on the oracle's product."""
+    M, N, K = 150, 130, 700
+    rng = np.random.default_rng(77)
+    A, Bm = synth.pm1(rng, (M, K)), synth.pm1(rng, (K, N))
+    S = oracle.matmul_pm1(A, Bm)
+    extremes = np.array([-2 ** 31, -2 ** 31 + 1, -2 ** 30, -K - 1, -K, -1, 0, 1, K, K + 1, 2 ** 30, 2 ** 31 - 1], np.int64)
+    thr = extremes[rng.integers(0, len(extremes), N)].astype(np.int32)
+    flip = rng.integers(0, 2, N).astype(bool)
+    want_pm1 = np.where((S >= thr[None, :].astype(np.int64)) != flip[None, :], 1, -1).astype(np.int8)
+    flip_words = oracle.pack_bits(np.where(flip, 1, -1).astype(np.int8)[None, :])[0]
+    pa = words_to_dev(oracle.pack_bits(A))
+    pb = words_to_dev(oracle.pack_bits(np.ascontiguousarray(Bm.T)))
+    got = bnn.xnor_gemm_bn_sign_pack(pa, pb, K, torch.from_numpy(thr).to(DEV), words_to_dev(flip_words[None, :])[0],
+                                     kernel=GEMM_KERNELS[kernel])
+    assert (words_to_host(got) == oracle.pack_bits(want_pm1)).all()
+
+
 def test_fused_mlp_full_batch_sampled_rows():
     x, weights, bns = synth.config_mlp(adversarial=True)
     wr = [torch.from_numpy(np.ascontiguousarray(w.T).astype(np.float32)).to(DEV) for w in weights]
