@@ -33,5 +33,6 @@ from .binding import (  # noqa: F401
     KERNEL_TILED64,
     KERNEL_MFMA,
     KERNEL_MFMA128,
+    KERNEL_MFMA_SHORTK,
 )
 from .network import BinaryMLP, BinaryConvLayer  # noqa: F401

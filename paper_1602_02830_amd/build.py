@@ -19,7 +19,7 @@ LIB = os.path.join(PKG, "libbnn_hip.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 ARCH = "gfx950"
 
-HIP_SOURCES = ["pack_sign.hip", "xnor_gemm.hip", "xnor_gemm_mfma.hip", "bn_sign_pack.hip", "im2col_pack.hip", "conv_implicit.hip",
+HIP_SOURCES = ["pack_sign.hip", "xnor_gemm.hip", "xnor_gemm_mfma.hip", "xnor_gemm_mfma_shortk.hip", "bn_sign_pack.hip", "im2col_pack.hip", "conv_implicit.hip",
                "gemm_i8_mfma.hip"]
 HOST_SOURCES = ["bn_fold.cpp", "api.cpp"]
 

@@ -88,22 +88,21 @@ __device__ inline void mfma_epilogue(const v16f (&acc)[WM][WN], const int* pop_a
         const bool fp_exact = PLANES ? (255 * int64_t(K) < (int64_t(1) << 22)) : (K <= (1 << 21));
         int u3[WN];
         float tj[WN];
-        uint64_t flip_mask[WN], live_mask[WN];
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
             const int nl = wn * 32 * WN + j * 32 + fr;
-            const int n = col0 + nl;
-            const bool live = n < N;
-            const int thr = thr_s[nl];
-            const bool flip = ((flip_s[nl >> 5] >> (nl & 31)) & 1u) != 0u;          // col0 is a multiple of 32
-            const int cj = PLANES ? thr : thr - K + pop_b[nl];
+            const int cj = PLANES ? thr_s[nl] : thr_s[nl] - K + pop_b[nl];
             u3[j] = cj + (PLANES ? 1 : 3);
             tj[j] = (PLANES ? 0.5f : 0.25f) * float(cj);
-            flip_mask[j] = __ballot(flip);
-            live_mask[j] = __ballot(live);
         }
+        // Flip and validity are applied to whole output words after the gather: lane l holds the
+        // word of column block l / 32, whose flip word is flip_s[...] and whose valid bits are the
+        // columns below N.
         const int64_t nw = (int64_t(N) + 31) >> 5;
         const int64_t w = ((int64_t(col0) + wn * 32 * WN) >> 5) + fh;       // word column of this lane
+        const uint32_t flip_word = flip_s[wn * WN + fh];                    // col0 is a multiple of 32
+        const int cols_left = N - (col0 + wn * 32 * WN + fh * 32);
+        const uint32_t live_word = cols_left >= 32 ? ~0u : cols_left <= 0 ? 0u : ((1u << cols_left) - 1u);
         auto pack_and_store = [&](auto fp_tag) {
             constexpr bool FP = decltype(fp_tag)::value;
 #pragma unroll
@@ -122,14 +121,14 @@ __device__ inline void mfma_epilogue(const v16f (&acc)[WM][WN], const int* pop_a
                         for (int j = 0; j < WN; ++j) {
                             const float sacc = acc[i][j][4 * vq + e];
                             const bool p = FP ? (sacc >= tj[j] + pf) : (int(sacc) >= ((u3[j] + pa) >> kShift));
-                            const uint64_t mask = (__ballot(p) ^ flip_mask[j]) & live_mask[j];
+                            const uint64_t mask = __ballot(p);
                             words = bnn_llvm_writelane(int(uint32_t(mask)), 32 * j + 8 * vq + e, words);
                             words = bnn_llvm_writelane(int(uint32_t(mask >> 32)), 32 * j + 8 * vq + 4 + e, words);
                         }
                     }
                 }
                 const int m = row0 + wm * 32 * WM + i * 32 + fr;
-                if (m < M && w < nw) bn.out[int64_t(m) * bn.ld_out + w] = uint32_t(words);
+                if (m < M && w < nw) bn.out[int64_t(m) * bn.ld_out + w] = (uint32_t(words) ^ flip_word) & live_word;
             }
         };
         if (fp_exact) pack_and_store(std::true_type{});

@@ -312,7 +312,7 @@ __global__ __launch_bounds__(256) void xnor_gemm_ksplit_kernel(
 // host side
 // ----------------------------------------------------------------------------
 enum { KERNEL_AUTO = 0, KERNEL_NAIVE = 1, KERNEL_TILED128 = 2, KERNEL_KSPLIT = 3, KERNEL_TILED64 = 4,
-       KERNEL_MFMA = 5, KERNEL_MFMA128 = 6, KERNEL_LAST = KERNEL_MFMA128 };
+       KERNEL_MFMA = 5, KERNEL_MFMA128 = 6, KERNEL_MFMA_SHORTK = 7, KERNEL_LAST = KERNEL_MFMA_SHORTK };
 
 // Matrix-engine variant, defined in xnor_gemm_mfma.hip.
 bool mfma_path_supports(int64_t K);
@@ -324,6 +324,12 @@ int launch_xnor_gemm_mfma128(const uint32_t* A, int64_t lda, const uint32_t* B, 
                              int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream);
 int launch_xnor_gemm_mfma128_fused(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M,
                                    int64_t N, int64_t K, BnSignArgs bn, void* stream);
+// Short-K organisation of the matrix-engine kernel, defined in xnor_gemm_mfma_shortk.hip.
+bool mfma_shortk_supports(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t K);
+int launch_xnor_gemm_mfma_shortk(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
+                                 int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream);
+int launch_xnor_gemm_mfma_shortk_fused(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M,
+                                       int64_t N, int64_t K, BnSignArgs bn, void* stream);
 bool mfma_planes_path_supports(int64_t K);
 int launch_bitplane_gemm_mfma(const uint32_t* Xp, int64_t ldx, const uint32_t* B, int64_t ldb, int32_t* C,
                               int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream);
@@ -349,14 +355,18 @@ static void launch_tiled(const uint32_t* A, int64_t lda, const uint32_t* B, int6
 // Kernel choice, from measurements on MI355X: the matrix-engine kernels are 2-4x faster than the
 // vector-ALU XNOR-popcount kernels down to a few dozen tiles.  Their 256 x 128 tile (two workgroups
 // per compute unit) wins for long K on a grid of a thousand tiles or more; otherwise the
-// 128 x 128 tile (three workgroups per compute unit) hides short K loops better.  Tiny grids go to the 64 x 64 XNOR tiles, which spread over more
-// compute units; skinny outputs go to the K-split kernel; K beyond the exact-fp32 range stays on
-// the vector ALU.
-static int choose_kernel(int64_t M, int64_t N, int64_t K, bool fused) {
+// 128 x 128 tile (three workgroups per compute unit) hides short K loops better.  For K up to 1152
+// that is not a whole number of 512-bit K-tiles, on a grid that fills the chip, the short-K
+// organisation (B tile resident, several A tiles per workgroup, only the K words that exist) is
+// 16-18 % faster still; it needs operands that allow 16-byte loads (short_ok).  Tiny grids go to the
+// 64 x 64 XNOR tiles, which spread over more compute units; skinny outputs go to the K-split kernel;
+// K beyond the exact-fp32 range stays on the vector ALU.
+static int choose_kernel(int64_t M, int64_t N, int64_t K, bool fused, bool short_ok) {
     if (!fused && (N <= 16 || M <= 4)) return KERNEL_KSPLIT;
     const int64_t tiles128 = ceil_div(M, 128) * ceil_div(N, 128);
     if (mfma_path_supports(K)) {
         if (K >= 4096 && ceil_div(M, 256) * ceil_div(N, 128) >= 1024) return KERNEL_MFMA;
+        if (short_ok && tiles128 >= 768 && K % 512 != 0) return KERNEL_MFMA_SHORTK;
         if (tiles128 >= 32) return KERNEL_MFMA128;
     }
     return tiles128 >= 512 ? KERNEL_TILED128 : KERNEL_TILED64;
@@ -369,6 +379,7 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
     if (kernel_id < KERNEL_AUTO || kernel_id > KERNEL_LAST) return BNN_ERR_INVALID_ARG;
     if ((kernel_id == KERNEL_MFMA || kernel_id == KERNEL_MFMA128) && !mfma_path_supports(K))
         return BNN_ERR_UNSUPPORTED;
+    if (kernel_id == KERNEL_MFMA_SHORTK && !mfma_shortk_supports(A, lda, B, ldb, K)) return BNN_ERR_UNSUPPORTED;
     const int64_t kw = ceil_div(K, 32);
     if (lda < kw || ldb < kw || ldc < N) return BNN_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return BNN_OK;
@@ -380,7 +391,8 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int m = int(M), n = int(N), k = int(K);
 
-    if (kernel_id == KERNEL_AUTO) kernel_id = choose_kernel(M, N, K, /*fused=*/false);
+    if (kernel_id == KERNEL_AUTO)
+        kernel_id = choose_kernel(M, N, K, /*fused=*/false, mfma_shortk_supports(A, lda, B, ldb, K));
 
     switch (kernel_id) {
         case KERNEL_NAIVE: {
@@ -420,6 +432,8 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
             return launch_xnor_gemm_mfma(A, lda, B, ldb, C, ldc, M, N, K, stream);
         case KERNEL_MFMA128:
             return launch_xnor_gemm_mfma128(A, lda, B, ldb, C, ldc, M, N, K, stream);
+        case KERNEL_MFMA_SHORTK:
+            return launch_xnor_gemm_mfma_shortk(A, lda, B, ldb, C, ldc, M, N, K, stream);
         default:
             return BNN_ERR_INVALID_ARG;
     }
@@ -432,10 +446,11 @@ static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const
                                            int kernel_id, void* stream) {
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return BNN_ERR_INVALID_ARG;
     if (kernel_id != KERNEL_AUTO && kernel_id != KERNEL_TILED128 && kernel_id != KERNEL_TILED64 &&
-        kernel_id != KERNEL_MFMA && kernel_id != KERNEL_MFMA128)
+        kernel_id != KERNEL_MFMA && kernel_id != KERNEL_MFMA128 && kernel_id != KERNEL_MFMA_SHORTK)
         return BNN_ERR_INVALID_ARG;
     if ((kernel_id == KERNEL_MFMA || kernel_id == KERNEL_MFMA128) && !mfma_path_supports(K))
         return BNN_ERR_UNSUPPORTED;
+    if (kernel_id == KERNEL_MFMA_SHORTK && !mfma_shortk_supports(A, lda, B, ldb, K)) return BNN_ERR_UNSUPPORTED;
     const int64_t kw = ceil_div(K, 32);
     if (lda < kw || ldb < kw || ld_out < ceil_div(N, 32)) return BNN_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return BNN_OK;
@@ -446,7 +461,9 @@ static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const
     if (ceil_div(M, 16) * ceil_div(N, 16) > kMaxDim) return BNN_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const BnSignArgs bn{thr, flip_bits, out, ld_out};
-    if (kernel_id == KERNEL_AUTO) kernel_id = choose_kernel(M, N, K, /*fused=*/true);
+    if (kernel_id == KERNEL_AUTO)
+        kernel_id = choose_kernel(M, N, K, /*fused=*/true, mfma_shortk_supports(A, lda, B, ldb, K));
+    if (kernel_id == KERNEL_MFMA_SHORTK) return launch_xnor_gemm_mfma_shortk_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_MFMA) return launch_xnor_gemm_mfma_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_MFMA128) return launch_xnor_gemm_mfma128_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_TILED128)

@@ -1,0 +1,269 @@
+// Bits-in, matrix-engine-inside binary product (Sec. 4 Eq. (5), the XnorDotProduct of Alg. 4) for
+// short K: 96 < K <= 1152, the range of a first MLP layer on 28 x 28 inputs (K = 784) or of a 3 x 3
+// convolution over 128 channels (K = 1152).
+//
+// With so few MFMA steps per output the kernel in xnor_gemm_mfma.hip spends most of a workgroup's
+// life outside its K loop (first-tile load latency, epilogue, workgroup turnaround).  This one
+// keeps the arithmetic (packed bits widened to fp4 in registers, v_mfma_f32_32x32x64_f8f6f4, row /
+// column popcounts for the +-1 fix-up, the same epilogues) and changes the organisation:
+//
+//   - a workgroup owns one 128-column tile of B for its whole life: B's K bits (at most 144 bytes
+//     per row) are staged in LDS once, with their popcounts, thresholds and flip words;
+//   - it then walks over several 128-row tiles of A (every `groups`-th tile of the M direction).
+//     The whole K extent of a tile sits in LDS at once, so a tile costs two barriers and its MFMA
+//     steps run without any in between; the global loads of the next tile are in flight while the
+//     current one is multiplied, and are written to LDS before the current tile's epilogue;
+//   - only the K words that exist are multiplied: ceil(K / 128) * 2 steps of 64 bits instead of
+//     whole 512-bit K-tiles (14 instead of 16 steps at K = 784).
+//
+// LDS layout of an operand tile: planes [quad q][half h] of 8-byte slots, slot r = row r's words
+// 4q + 2h, 4q + 2h + 1.  Lane (row r = l % 32, half h = l / 32) of an MFMA operand reads slot r
+// of plane (q, h): consecutive lanes, consecutive slots.  Step 2q + s multiplies word s of that
+// pair, i.e. K words 4q + s (h = 0) and 4q + 2 + s (h = 1); the order of the K sum is free.
+//
+// Requirements (checked by the launcher): A, B 16-byte aligned, lda, ldb multiples of 4 words.
+// The last quad of a row, where it is incomplete or holds pad bits, is loaded from the row's last
+// four words (never past word K/32), moved into place and masked when it is written to LDS.
+#include <algorithm>
+#include <cstdint>
+
+#include "bnn_internal.h"
+#include "gemm_staging.h"
+#include "mfma_fp4.h"
+
+namespace bnn {
+
+constexpr int kShortMaxQuads = 9;          // K <= 1152
+constexpr int kShortMinWords = 4;          // K > 96: a row has at least one whole quad to load
+
+// A 16-byte load from an address that is only 4-byte aligned (the last four words of a row).
+__device__ inline uint4 load_quad_dword_aligned(const uint32_t* p) {
+    uint4 v;
+    __builtin_memcpy(&v, p, sizeof(v));
+    return v;
+}
+
+template <int LANES>
+__device__ inline int sum_over_lanes(int c) {
+    static_assert(LANES == 8 || LANES == 16, "aligned groups of 8 or 16 lanes");
+    c += __builtin_amdgcn_update_dpp(0, c, 0xB1, 0xF, 0xF, true);        // lane ^ 1
+    c += __builtin_amdgcn_update_dpp(0, c, 0x4E, 0xF, 0xF, true);        // lane ^ 2
+    c += __builtin_amdgcn_update_dpp(0, c, 0x141, 0xF, 0xF, true);       // row_half_mirror: 7 - lane within 8
+    if (LANES == 16) c += __builtin_amdgcn_update_dpp(0, c, 0x140, 0xF, 0xF, true);   // row_mirror: 15 - lane
+    return c;
+}
+
+// Words `first` .. `first + 3` of a quad that was loaded from the row's last four words
+// (kw - 4 .. kw - 1): entries beyond the row read 0, the row's last word is masked.
+__device__ inline uint4 align_last_quad(uint4 v, int shift, int valid, uint32_t tmask) {
+    // shift = 4 - valid: the quad's word e is loaded word e + shift.
+    const uint32_t l0 = v.x, l1 = v.y, l2 = v.z, l3 = v.w;
+    uint4 o;
+    o.x = shift == 0 ? l0 : shift == 1 ? l1 : shift == 2 ? l2 : l3;
+    o.y = shift == 0 ? l1 : shift == 1 ? l2 : shift == 2 ? l3 : 0u;
+    o.z = shift == 0 ? l2 : shift == 1 ? l3 : 0u;
+    o.w = shift == 0 ? l3 : 0u;
+    if (valid == 1) o.x &= tmask;
+    else if (valid == 2) o.y &= tmask;
+    else if (valid == 3) o.z &= tmask;
+    else o.w &= tmask;
+    return o;
+}
+
+template <int TPR, bool FUSED>
+__global__ __launch_bounds__(256, 3) void xnor_gemm_mfma_shortk_kernel(
+    const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B, int64_t ldb,
+    int32_t* __restrict__ C, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n, int groups,
+    BnSignArgs bn) {
+    constexpr int WM = 2, WN = 2, BM = 64 * WM, BN = 64 * WN;
+    static_assert(BM == BN, "one staging routine serves both operands");
+    constexpr int PLANE = BM + 2;                       // 8-byte slots per plane (2 pad slots)
+    constexpr int ROWS_PER_PASS = 256 / TPR;            // TPR threads fetch one row's quads
+    constexpr int PASSES = BM / ROWS_PER_PASS;
+    extern __shared__ uint2 lds_planes[];               // A planes, then B planes
+    __shared__ __attribute__((aligned(16))) int pop_a[2][BM];
+    __shared__ __attribute__((aligned(16))) float pop_af[2][FUSED ? BM : 4];
+    __shared__ __attribute__((aligned(16))) int pop_b[BN];
+    __shared__ int thr_s[FUSED ? BN : 1];
+    __shared__ uint32_t flip_s[FUSED ? BN / 32 : 1];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int fr = lane & 31, fh = lane >> 5;
+    const int kw = (K + 31) >> 5;
+    const int kq = (kw + 3) >> 2;                       // quads per row
+    const int n_fast = (K >> 5) >> 2;                   // quads of complete, unmasked words (kq or kq - 1)
+    const uint32_t tmask = tail_mask(K);
+    uint2* lds_a = lds_planes;
+    uint2* lds_b = lds_planes + 2 * kq * PLANE;
+
+    const int n_tile = blockIdx.x % tiles_n, group = blockIdx.x / tiles_n;
+    const int col0 = n_tile * BN;
+
+    // Staging: thread (st_r, st_q) fetches quad st_q of rows st_r, st_r + ROWS_PER_PASS, ...
+    const int st_q = tid % TPR, st_r = tid / TPR;
+    const int word_off = st_q < n_fast ? 4 * st_q : kw - 4;       // always inside the row
+    const int last_valid = kw - 4 * n_fast;                          // words of the last quad (when n_fast < kq)
+    auto fetch = [&](const uint32_t* P, int64_t ld, int nrows, int r0, uint4 (&r)[PASSES]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int l = 0; l < PASSES; ++l) {
+            const int row = min(r0 + st_r + l * ROWS_PER_PASS, nrows - 1);   // rows beyond the matrix repeat its last row
+            r[l] = load_quad_dword_aligned(P + int64_t(row) * ld + word_off);
+        }
+    };
+    // Writes the fetched quads to their two planes and returns nothing; cnt[l] = set bits written.
+    auto stage = [&](uint2* planes, const uint4 (&r)[PASSES], int (&cnt)[PASSES]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int l = 0; l < PASSES; ++l) {
+            uint4 v = r[l];
+            if (st_q >= n_fast) v = align_last_quad(v, 4 - last_valid, last_valid, tmask);
+            cnt[l] = 0;
+            if (st_q < kq) {
+                const int row = st_r + l * ROWS_PER_PASS;
+                planes[(2 * st_q) * PLANE + row] = make_uint2(v.x, v.y);
+                planes[(2 * st_q + 1) * PLANE + row] = make_uint2(v.z, v.w);
+                cnt[l] = popc4(v);
+            }
+        }
+    };
+
+    uint4 ra[PASSES];
+    int cnt[PASSES];
+    {
+        // B tile, once: bits, column popcounts, thresholds and flip words.
+        uint4 rb[PASSES];
+        fetch(B, ldb, N, col0, rb);
+        if (FUSED) {
+            // No result exceeds K in magnitude, so clamping a threshold to [-K-1, K+1] changes no
+            // output bit and keeps the bounds the epilogue derives from it inside int32.
+            if (tid < BN) thr_s[tid] = col0 + tid < N ? max(-K - 1, min(K + 1, bn.thr[col0 + tid])) : 0;
+            if (tid < BN / 32) flip_s[tid] = col0 + 32 * tid < N ? bn.flip_bits[(col0 >> 5) + tid] : 0u;
+        }
+        if (group < tiles_m) fetch(A, lda, M, group * BM, ra);
+        stage(lds_b, rb, cnt);
+#pragma unroll
+        for (int l = 0; l < PASSES; ++l) {
+            const int c = sum_over_lanes<TPR>(cnt[l]);
+            if (st_q == 0) pop_b[st_r + l * ROWS_PER_PASS] = 2 * c;
+        }
+    }
+    auto stage_a = [&](int buf) __attribute__((always_inline)) {
+        stage(lds_a, ra, cnt);
+#pragma unroll
+        for (int l = 0; l < PASSES; ++l) {
+            const int c = sum_over_lanes<TPR>(cnt[l]);
+            if (st_q == 0) {
+                pop_a[buf][st_r + l * ROWS_PER_PASS] = 2 * c;
+                if (FUSED) pop_af[buf][st_r + l * ROWS_PER_PASS] = 0.5f * float(c);
+            }
+        }
+    };
+    if (group < tiles_m) stage_a(0);
+    __syncthreads();
+
+    // Operand slots of this lane: plane (q, fh), rows wm*64 + 32*i + fr (A) / wn*64 + 32*j + fr (B).
+    const uint2* rd_a = lds_a + fh * PLANE + wm * 32 * WM + fr;
+    const uint2* rd_b = lds_b + fh * PLANE + wn * 32 * WN + fr;
+
+    int buf = 0;
+    for (int tile_m = group; tile_m < tiles_m; tile_m += groups, buf ^= 1) {
+        const bool more = tile_m + groups < tiles_m;
+        if (more) fetch(A, lda, M, (tile_m + groups) * BM, ra);      // in flight during the MFMA steps
+
+        v16f acc[WM][WN];
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+        uint2 a_cur[WM], b_cur[WN];
+#pragma unroll
+        for (int i = 0; i < WM; ++i) a_cur[i] = rd_a[i * 32];
+#pragma unroll
+        for (int j = 0; j < WN; ++j) b_cur[j] = rd_b[j * 32];
+        for (int q = 0; q < kq; ++q) {
+            // Pairs of the next quad (the last iteration re-reads its own: no branch in the loop).
+            const int qn = min(q + 1, kq - 1);
+            uint2 a_nxt[WM], b_nxt[WN];
+#pragma unroll
+            for (int i = 0; i < WM; ++i) a_nxt[i] = rd_a[2 * qn * PLANE + i * 32];
+#pragma unroll
+            for (int j = 0; j < WN; ++j) b_nxt[j] = rd_b[2 * qn * PLANE + j * 32];
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                v8i fa[WM], fb[WN];
+#pragma unroll
+                for (int i = 0; i < WM; ++i) fa[i] = widen_fp4_a(s == 0 ? a_cur[i].x : a_cur[i].y);
+#pragma unroll
+                for (int j = 0; j < WN; ++j) fb[j] = widen_fp4_b(s == 0 ? b_cur[j].x : b_cur[j].y);
+#pragma unroll
+                for (int i = 0; i < WM; ++i)
+#pragma unroll
+                    for (int j = 0; j < WN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                            fa[i], fb[j], acc[i][j], 4 /* A: fp4 */, 4 /* B: fp4 */, 0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < WM; ++i) a_cur[i] = a_nxt[i];
+#pragma unroll
+            for (int j = 0; j < WN; ++j) b_cur[j] = b_nxt[j];
+        }
+
+        __syncthreads();                            // every wavefront has read this tile's planes
+        if (more) stage_a(buf ^ 1);                 // next tile's bits and row sums (the other pop_a half)
+        mfma_epilogue<WM, WN, FUSED, false>(acc, pop_a[buf], pop_af[buf], pop_b, thr_s, flip_s, C, ldc, bn, M, N, K,
+                                            tile_m * BM, col0, wm, wn, fr, fh);
+        __syncthreads();                            // next tile staged; this tile's row sums no longer needed
+    }
+}
+
+bool mfma_shortk_supports(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t K) {
+    const int64_t kw = ceil_div(K, 32);
+    return kw >= kShortMinWords && kw <= 4 * kShortMaxQuads && aligned_to(A, 16) && aligned_to(B, 16) &&
+           lda % 4 == 0 && ldb % 4 == 0;
+}
+
+// Workgroups per 128-column tile: every workgroup of a column tile takes every `groups`-th row tile.
+// Measured on MI355X (10000 x 4096 x 784, 262144 x 128 x 1152): what counts is that three workgroups
+// are resident on every compute unit from start to end, so that one's loads, barriers and epilogue
+// overlap the others' MFMA steps; an even split of the row tiles matters less.  So: as many
+// workgroups as the chip holds at once (3 x 256), at most one per row tile.
+static int shortk_groups(int64_t tiles_m, int64_t tiles_n) {
+    constexpr int64_t kSlots = 3 * 256;
+    return int(std::max<int64_t>(1, std::min<int64_t>(tiles_m, kSlots / tiles_n)));
+}
+
+template <bool FUSED>
+static int launch_shortk(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc,
+                         int64_t M, int64_t N, int64_t K, BnSignArgs bn, void* stream) {
+    if (!mfma_shortk_supports(A, lda, B, ldb, K)) return BNN_ERR_UNSUPPORTED;
+    const int64_t tiles_m = ceil_div(M, 128), tiles_n = ceil_div(N, 128);
+    const int groups = shortk_groups(tiles_m, tiles_n);
+    if (tiles_n * groups > kMaxDim) return BNN_ERR_UNSUPPORTED;
+    const int64_t kq = ceil_div(ceil_div(K, 32), 4);
+    const size_t lds_bytes = size_t(2) * 2 * kq * (128 + 2) * sizeof(uint2);
+    const dim3 grid(unsigned(tiles_n * groups));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (kq <= 8)
+        hipLaunchKernelGGL((xnor_gemm_mfma_shortk_kernel<8, FUSED>), grid, dim3(256), lds_bytes, s, A, lda, B, ldb, C,
+                           ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), groups, bn);
+    else
+        hipLaunchKernelGGL((xnor_gemm_mfma_shortk_kernel<16, FUSED>), grid, dim3(256), lds_bytes, s, A, lda, B, ldb, C,
+                           ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), groups, bn);
+    return check_launch();
+}
+
+int launch_xnor_gemm_mfma_shortk(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
+                                 int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream) {
+    return launch_shortk<false>(A, lda, B, ldb, C, ldc, M, N, K, BnSignArgs{}, stream);
+}
+
+int launch_xnor_gemm_mfma_shortk_fused(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M,
+                                       int64_t N, int64_t K, BnSignArgs bn, void* stream) {
+    return launch_shortk<true>(A, lda, B, ldb, nullptr, 0, M, N, K, bn, stream);
+}
+
+}  // namespace bnn

@@ -24,6 +24,8 @@ GEMM_KERNELS = {
     "mfma": bnn.KERNEL_MFMA,
     "mfma128": bnn.KERNEL_MFMA128,
 }
+# The short-K organisation of the matrix-engine kernel takes only 96 < K <= 1152 and operands that
+# allow 16-byte loads, so it has tests of its own instead of a place in the sweeps above.
 
 
 def words_to_dev(w: np.ndarray) -> torch.Tensor:
@@ -150,6 +152,73 @@ def test_xnor_gemm_multi_tile_shapes(kernel):
     rng = np.random.default_rng(6)
     for (M, N, K) in [(64, 1024, 1024), (300, 520, 784), (1024, 10, 4096), (513, 129, 96), (2, 2048, 640)]:
         _gemm_case(synth.pm1(rng, (M, K)), synth.pm1(rng, (K, N)), GEMM_KERNELS[kernel])
+
+
+def _aligned_words(w: np.ndarray) -> torch.Tensor:
+    """Device copy with the leading dimension rounded up to 4 words (junk in the extra words)."""
+    kw = w.shape[1]
+    ld = (kw + 3) // 4 * 4
+    return strided_words(w, ld) if ld != kw else words_to_dev(w)
+
+
+SHORTK_SHAPES = [(128, 128, 128), (300, 200, 97), (130, 200, 1000), (1000, 1000, 1152), (129, 95, 128),
+                 (64, 1024, 1024), (777, 333, 513), (500, 260, 640), (300, 4096, 784), (1500, 700, 1151),
+                 (257, 129, 1121), (1, 1, 100), (131, 7, 992)]
+
+
+@pytest.mark.parametrize("M,N,K", SHORTK_SHAPES)
+def test_shortk_kernel_int32_and_fused(M, N, K):
+    """Kernel 7 on every K-tail length class (whole quads, partial last quad, pad bits in a whole quad),
+    ragged M and N, poisoned pad bits; int32 output against the literal product, fused output against
+    float BatchNorm + Sign."""
+    rng = np.random.default_rng(M * 11 + N * 13 + K * 17)
+    A, Bm = synth.pm1(rng, (M, K)), synth.pm1(rng, (K, N))
+    bn = synth.bn_params(rng, N, K, adversarial=True)
+    S, a_next = oracle.dense_layer(A, Bm, bn, eps=EPS)
+    pa = _aligned_words(poison_pad_bits(oracle.pack_bits(A), K))
+    pb = _aligned_words(poison_pad_bits(oracle.pack_bits(np.ascontiguousarray(Bm.T)), K))
+    got = bnn.xnor_gemm(pa, pb, K, kernel=bnn.KERNEL_MFMA_SHORTK).cpu().numpy()
+    assert (got == S).all()
+    thr, flip = _fold_to_dev(bn, K)
+    nw = (N + 31) // 32
+    out = torch.full((M, nw + 1), 0x0BADF00D, dtype=torch.int32, device=DEV)
+    bnn.xnor_gemm_bn_sign_pack(pa, pb, K, thr, flip, out=out[:, :nw], kernel=bnn.KERNEL_MFMA_SHORTK)
+    host = words_to_host(out)
+    assert (host[:, :nw] == oracle.pack_bits(a_next)).all()
+    assert (host[:, nw:] == 0x0BADF00D).all()
+
+
+def test_shortk_kernel_several_row_tiles_per_workgroup():
+    """55 row tiles over 32 column tiles: 24 workgroups per column tile, two or three row tiles each,
+    the last one ragged.  Rows sampled from every tile."""
+    M, N, K = 7000, 4096, 784
+    rng = np.random.default_rng(99)
+    A, Bm = synth.pm1(rng, (M, K)), synth.pm1(rng, (K, N))
+    bn = synth.bn_params(rng, N, K, adversarial=True)
+    pa = _aligned_words(oracle.pack_bits(A))
+    pb = _aligned_words(oracle.pack_bits(np.ascontiguousarray(Bm.T)))
+    thr, flip = _fold_to_dev(bn, K)
+    got = words_to_host(bnn.xnor_gemm_bn_sign_pack(pa, pb, K, thr, flip, kernel=bnn.KERNEL_MFMA_SHORTK))
+    auto = words_to_host(bnn.xnor_gemm_bn_sign_pack(pa, pb, K, thr, flip))      # the default dispatch picks it too
+    rows = np.unique(np.concatenate([np.arange(0, M, 37), np.arange(M - 130, M)]))
+    _s, a_next = oracle.dense_layer(A[rows], Bm, bn, eps=EPS)
+    assert (got[rows] == oracle.pack_bits(a_next)).all()
+    assert (auto == got).all()
+    c = bnn.xnor_gemm(pa, pb, K, kernel=bnn.KERNEL_MFMA_SHORTK).cpu().numpy()
+    assert (c[rows] == oracle.matmul_pm1(A[rows], Bm)).all()
+
+
+def test_shortk_kernel_rejects_what_it_cannot_take():
+    rng = np.random.default_rng(98)
+    for K, aligned in ((96, True), (1153, True), (784, False)):
+        A, Bm = synth.pm1(rng, (40, K)), synth.pm1(rng, (K, 40))
+        pa, pb = oracle.pack_bits(A), oracle.pack_bits(np.ascontiguousarray(Bm.T))
+        da, db = (_aligned_words(pa), _aligned_words(pb)) if aligned else (words_to_dev(pa), words_to_dev(pb))
+        with pytest.raises(bnn.BnnError) as e:
+            bnn.xnor_gemm(da, db, K, kernel=bnn.KERNEL_MFMA_SHORTK)
+        assert e.value.status == 3          # BNN_ERR_UNSUPPORTED
+        got = bnn.xnor_gemm(da, db, K).cpu().numpy()                                # the default dispatch still serves it
+        assert (got == oracle.matmul_pm1(A, Bm)).all()
 
 
 def test_xnor_gemm_ldc_and_canary():
