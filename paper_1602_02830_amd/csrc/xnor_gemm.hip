@@ -356,9 +356,9 @@ static void launch_tiled(const uint32_t* A, int64_t lda, const uint32_t* B, int6
 // vector-ALU XNOR-popcount kernels down to a few dozen tiles.  Their 256 x 128 tile (two workgroups
 // per compute unit) wins for long K on a grid of a thousand tiles or more; otherwise the
 // 128 x 128 tile (three workgroups per compute unit) hides short K loops better.  For K up to 1152
-// that is not a whole number of 512-bit K-tiles, on a grid that fills the chip, the short-K
-// organisation (B tile resident, several A tiles per workgroup, only the K words that exist) is
-// 16-18 % faster still; it needs operands that allow 16-byte loads (short_ok).  Tiny grids go to the
+// on a grid that fills the chip, the short-K organisation (B tile resident, several A tiles per
+// workgroup, only the K words that exist) is 5-25 % faster still; it needs operands that allow
+// 16-byte loads (short_ok).  Tiny grids go to the
 // 64 x 64 XNOR tiles, which spread over more compute units; skinny outputs go to the K-split kernel;
 // K beyond the exact-fp32 range stays on the vector ALU.
 static int choose_kernel(int64_t M, int64_t N, int64_t K, bool fused, bool short_ok) {
@@ -366,7 +366,7 @@ static int choose_kernel(int64_t M, int64_t N, int64_t K, bool fused, bool short
     const int64_t tiles128 = ceil_div(M, 128) * ceil_div(N, 128);
     if (mfma_path_supports(K)) {
         if (K >= 4096 && ceil_div(M, 256) * ceil_div(N, 128) >= 1024) return KERNEL_MFMA;
-        if (short_ok && tiles128 >= 768 && K % 512 != 0) return KERNEL_MFMA_SHORTK;
+        if (short_ok && tiles128 >= 768) return KERNEL_MFMA_SHORTK;
         if (tiles128 >= 32) return KERNEL_MFMA128;
     }
     return tiles128 >= 512 ? KERNEL_TILED128 : KERNEL_TILED64;

@@ -98,7 +98,15 @@ __global__ __launch_bounds__(256, 3) void xnor_gemm_mfma_shortk_kernel(
     uint2* lds_a = lds_planes;
     uint2* lds_b = lds_planes + 2 * kq * PLANE;
 
-    const int n_tile = blockIdx.x % tiles_n, group = blockIdx.x / tiles_n;
+    // Consecutive workgroup ids go round-robin to the 8 dies, each with its own L2.  A row of the packed
+    // output is contiguous over the column tiles (16 bytes each), so the workgroups of one die take
+    // neighbouring column tiles of the same rows: their partial lines meet in that die's L2.
+    int n_tile = blockIdx.x % tiles_n, group = blockIdx.x / tiles_n;
+    if (tiles_n % 8 == 0) {
+        const int per_die = tiles_n / 8, die = blockIdx.x % 8, idx = blockIdx.x / 8;
+        n_tile = die * per_die + idx % per_die;
+        group = idx / per_die;
+    }
     const int col0 = n_tile * BN;
 
     // Staging: thread (st_r, st_q) fetches quad st_q of rows st_r, st_r + ROWS_PER_PASS, ...
