@@ -19,8 +19,8 @@ LIB = os.path.join(PKG, "libbnn_hip.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 ARCH = "gfx950"
 
-HIP_SOURCES = ["pack_sign.hip", "xnor_gemm.hip", "xnor_gemm_mfma.hip", "xnor_gemm_mfma_shortk.hip", "bn_sign_pack.hip", "im2col_pack.hip", "conv_implicit.hip",
-               "gemm_i8_mfma.hip"]
+HIP_SOURCES = ["pack_sign.hip", "xnor_gemm.hip", "xnor_gemm_mfma.hip", "xnor_gemm_mfma_shortk.hip",
+               "bn_sign_pack.hip", "im2col_pack.hip", "conv_implicit.hip", "gemm_i8_mfma.hip"]
 HOST_SOURCES = ["bn_fold.cpp", "api.cpp"]
 
 HIP_FLAGS = [f"--offload-arch={ARCH}", "-O3", "-std=c++17", "-fPIC", f"-I{INCLUDE}", f"-I{CSRC}",

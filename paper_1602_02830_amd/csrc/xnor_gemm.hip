@@ -258,18 +258,48 @@ __global__ __launch_bounds__(256) void xnor_gemm_ksplit_kernel(
 #pragma unroll
     for (int j = 0; j < kSkinnyCols; ++j) acc[j] = 0;
 
+    // Quads made of complete, unmasked words are loaded without any check (index clamped into that
+    // range, result zeroed afterwards if the quad does not exist): the loads of a chunk then carry no
+    // control flow and are all in flight together.  The one quad that may be partial or hold pad
+    // bits (index n_full) goes through the checked, masking loader, once per chunk that contains it.
+    const int n_full = (K >> 5) >> 2;
+    const uint32_t* xrow = X + int64_t(xr) * ldx;
+
     for (int q0 = 0; q0 < n_quads; q0 += kSkinnyChunkQuads) {
         // This lane's quads of the chunk: q, q + 8, ..., q + 56 (zero beyond the row's end).
-        uint4 a[kSkinnyChunkQuads / 8];
+        uint4 a[kSkinnyChunkQuads / 8] = {};
+        if (n_full > 0) {
 #pragma unroll
-        for (int t = 0; t < kSkinnyChunkQuads / 8; ++t) a[t] = load_quad<VEC>(X, ldx, nx, kw, tmask, xr, q0 + q + 8 * t);
+            for (int t = 0; t < kSkinnyChunkQuads / 8; ++t)
+                a[t] = load_quad_unchecked<VEC>(xrow, min(q0 + q + 8 * t, n_full - 1));
+        }
+        const bool tail_here = n_full < n_quads && n_full >= q0 && n_full < q0 + kSkinnyChunkQuads;
+        uint4 a_tail = make_uint4(0u, 0u, 0u, 0u);
+        if (tail_here) a_tail = load_quad<VEC>(X, ldx, nx, kw, tmask, xr, n_full);
         // Stage Y: 16 rows x 64 quads, 4 quads per thread; rows beyond ny repeat the last row.
+        uint4 yv[kSkinnyCols * kSkinnyChunkQuads / 256] = {};
+        if (n_full > 0) {
+#pragma unroll
+            for (int t = 0; t < kSkinnyCols * kSkinnyChunkQuads / 256; ++t) {
+                const int idx = tid + 256 * t;
+                const int yr = idx / kSkinnyChunkQuads, yq = idx % kSkinnyChunkQuads;
+                yv[t] = load_quad_unchecked<VEC>(Y + int64_t(min(y0 + yr, ny - 1)) * ldy, min(q0 + yq, n_full - 1));
+            }
+        }
         __syncthreads();                                              // previous chunk fully consumed
 #pragma unroll
         for (int t = 0; t < kSkinnyCols * kSkinnyChunkQuads / 256; ++t) {
             const int idx = tid + 256 * t;
             const int yr = idx / kSkinnyChunkQuads, yq = idx % kSkinnyChunkQuads;
-            lds_y[idx] = load_quad<VEC>(Y, ldy, ny, kw, tmask, min(y0 + yr, ny - 1), q0 + yq);
+            uint4 v = zero_unless(n_full > 0 && q0 + yq < n_full, yv[t]);
+            if (tail_here && q0 + yq == n_full) v = load_quad<VEC>(Y, ldy, ny, kw, tmask, min(y0 + yr, ny - 1), n_full);
+            lds_y[idx] = v;
+        }
+#pragma unroll
+        for (int t = 0; t < kSkinnyChunkQuads / 8; ++t) {
+            const int qi = q0 + q + 8 * t;
+            a[t] = zero_unless(n_full > 0 && qi < n_full, a[t]);
+            if (qi == n_full) a[t] = a_tail;
         }
         __syncthreads();
         // Steps and columns that do not exist are skipped (both bounds are wavefront-uniform).

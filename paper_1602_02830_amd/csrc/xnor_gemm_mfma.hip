@@ -11,8 +11,8 @@
 //
 // Operands stay packed 32 per word in HBM and LDS (the 32x smaller footprint the
 // paper argues for); only inside registers is each bit widened to a 4-bit float
-// and fed to v_mfma_scale_f32_32x32x64_f8f6f4, whose fp32 accumulation of small
-// integers is exact below 2^24.  With a, b in {0,1} standing for -1/+1:
+// and fed to v_mfma_f32_32x32x64_f8f6f4 (its block-scaled form in the planes
+// kernel), whose fp32 accumulation of small integers is exact below 2^24.  With a, b in {0,1} standing for -1/+1:
 //
 //   binary:  sum_k (2a-1)(2b-1) = K - 2*popcount(A_m) - 2*popcount(B_n) + 4 * sum_k a*b
 //   planes:  sum_n 2^(n-1) sum_k x^n (2b-1) = 2 * sum_n 2^(n-1) sum_k x^n b  -  sum_k x[m][k]

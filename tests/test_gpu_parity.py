@@ -221,6 +221,83 @@ def test_shortk_kernel_rejects_what_it_cannot_take():
         assert (got == oracle.matmul_pm1(A, Bm)).all()
 
 
+@pytest.mark.parametrize("kernel", ["mfma", "mfma128"])
+def test_mfma_kernels_at_the_exact_accumulation_limit(kernel):
+    """K = 2^24 is the largest K the matrix-engine kernels accept: their fp32 sums of 0/1 products reach
+    2^24 exactly when every bit of both operands is set.  One K beyond that they refuse, and the default
+    dispatch serves the same product on the vector ALU."""
+    K = 1 << 24
+    rng = np.random.default_rng(24)
+    A = synth.pm1(rng, (4, K))
+    Bm = synth.pm1(rng, (K, 3))
+    A[0, :] = 1                      # row 0 all +1
+    Bm[:, 0] = 1                     # column 0 all +1: C[0][0] = K, the sum of products is 2^24
+    A[1, :] = -1                     # row 1 all -1: C[1][0] = -K
+    want = oracle.matmul_pm1(A, Bm)
+    assert want[0, 0] == K and want[1, 0] == -K
+    pa = words_to_dev(oracle.pack_bits(A))
+    pb = words_to_dev(oracle.pack_bits(np.ascontiguousarray(Bm.T)))
+    got = bnn.xnor_gemm(pa, pb, K, kernel=GEMM_KERNELS[kernel]).cpu().numpy()
+    assert (got == want).all()
+    # fused form at this K compares in integers (the float comparison is exact only up to K = 2^21)
+    thr = torch.tensor([K, 0, -K + 2], dtype=torch.int32, device=DEV)
+    flip = torch.tensor([0b100], dtype=torch.int32, device=DEV)
+    bits = words_to_host(bnn.xnor_gemm_bn_sign_pack(pa, pb, K, thr, flip, kernel=GEMM_KERNELS[kernel]))
+    want_bits = ((want >= thr.cpu().numpy()[None, :]) != np.array([False, False, True])[None, :])
+    assert (bits[:, 0] == (want_bits * (1 << np.arange(3))[None, :]).sum(axis=1)).all()
+    # one word more: outside the exact range
+    K2 = K + 32
+    A2 = np.concatenate([A, np.ones((4, 32), np.int8)], axis=1)
+    B2 = np.concatenate([Bm, np.ones((32, 3), np.int8)], axis=0)
+    pa2 = words_to_dev(oracle.pack_bits(A2))
+    pb2 = words_to_dev(oracle.pack_bits(np.ascontiguousarray(B2.T)))
+    with pytest.raises(bnn.BnnError) as e:
+        bnn.xnor_gemm(pa2, pb2, K2, kernel=GEMM_KERNELS[kernel])
+    assert e.value.status == 3
+    assert (bnn.xnor_gemm(pa2, pb2, K2).cpu().numpy() == want + oracle.matmul_pm1(A2[:, K:], B2[K:, :])).all()
+
+
+@pytest.mark.parametrize("K", [1 << 21, (1 << 21) + 32])
+def test_fused_layer_on_both_sides_of_the_float_compare_limit(K):
+    """Up to K = 2^21 the fused epilogue of the matrix-engine kernel compares in float, beyond in integers;
+    both must give the folded BatchNorm + Sign bits."""
+    M, N = 9, 40
+    rng = np.random.default_rng(K % 1000)
+    A, Bm = synth.pm1(rng, (M, K)), synth.pm1(rng, (K, N))
+    S = oracle.matmul_pm1(A, Bm)
+    # thresholds right at, just above and just below attained values, and at the ends of the range
+    thr = np.concatenate([S[0, :10], S[1, 10:20] + 1, S[2, 20:30] - 1, [K, K + 1, -K, -K - 1, 0, 1, -1, 2, -2, 3]]).astype(np.int32)
+    flip = rng.integers(0, 2, N).astype(bool)
+    want = np.where((S >= thr[None, :]) != flip[None, :], 1, -1).astype(np.int8)
+    flip_words = oracle.pack_bits(np.where(flip, 1, -1).astype(np.int8)[None, :])[0]
+    pa = words_to_dev(oracle.pack_bits(A))
+    pb = words_to_dev(oracle.pack_bits(np.ascontiguousarray(Bm.T)))
+    for kernel in ("mfma", "mfma128"):
+        got = bnn.xnor_gemm_bn_sign_pack(pa, pb, K, torch.from_numpy(thr).to(DEV), words_to_dev(flip_words[None, :])[0],
+                                         kernel=GEMM_KERNELS[kernel])
+        assert (words_to_host(got) == oracle.pack_bits(want)).all(), kernel
+
+
+def test_bitplane_gemm_at_the_exact_accumulation_limit():
+    """255 * K < 2^24 bounds the 8-bit first layer on the matrix engine: K = 65792 with every input 255 and
+    every weight +1 gives 16776960, the largest sum it must represent."""
+    K = 65792
+    rng = np.random.default_rng(65)
+    X = synth.uint8_input(rng, (3, K))
+    X[0, :] = 255
+    Wb = synth.pm1(rng, (K, 2))
+    Wb[:, 0] = 1
+    S = oracle.first_layer_bitplanes(X, Wb)
+    assert S[0, 0] == 255 * K
+    planes = bnn.pack_bitplanes(torch.from_numpy(X).to(DEV))
+    wb = words_to_dev(oracle.pack_bits(np.ascontiguousarray(Wb.T)))
+    assert (bnn.bitplane_gemm(planes, wb, K).cpu().numpy() == S).all()
+    with pytest.raises(bnn.BnnError) as e:
+        bnn.bitplane_gemm(torch.zeros((3, 8 * 2057), dtype=torch.int32, device=DEV),
+                          torch.zeros((2, 2057), dtype=torch.int32, device=DEV), 65824)
+    assert e.value.status == 3
+
+
 def test_xnor_gemm_ldc_and_canary():
     rng = np.random.default_rng(7)
     M, N, K = 100, 77, 500
