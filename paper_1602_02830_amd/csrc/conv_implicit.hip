@@ -33,7 +33,7 @@ static int conv_geometry(const uint32_t* in, int64_t B, int64_t H, int64_t W, in
     const int64_t Wo = (W + 2 * int64_t(pad) - kw) / stride + 1;
     K = int64_t(kh) * kw * Cin;
     M = B * Ho * Wo;
-    if (K > kMaxK || M > kMaxDim) return BNN_ERR_INVALID_ARG;
+    if (K > kMaxK || M > kMaxDim - 1024) return BNN_ERR_INVALID_ARG;      // row indices run up to one tile past M
     if (ldw < ceil_div(K, 32)) return BNN_ERR_INVALID_ARG;
     if (B > 0 && Cout > 0 && (!in || !Wb)) return BNN_ERR_INVALID_ARG;
     if (!aligned_to(in, 4) || !aligned_to(Wb, 4)) return BNN_ERR_ALIGNMENT;

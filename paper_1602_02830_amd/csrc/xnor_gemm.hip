@@ -415,8 +415,9 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
     if (M == 0 || N == 0) return BNN_OK;
     if (!C || (K > 0 && (!A || !B))) return BNN_ERR_INVALID_ARG;
     if (!aligned_to(A, 4) || !aligned_to(B, 4) || !aligned_to(C, 4)) return BNN_ERR_ALIGNMENT;
-    // Tile grids are indexed with 32-bit integers.
-    if (ceil_div(M, 16) * ceil_div(N, 16) > kMaxDim) return BNN_ERR_UNSUPPORTED;
+    // Tile grids and the row / column indices inside a tile (up to one tile past the matrix) are 32-bit.
+    if (ceil_div(M, 16) * ceil_div(N, 16) > kMaxDim || M > kMaxDim - 1024 || N > kMaxDim - 1024)
+        return BNN_ERR_UNSUPPORTED;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int m = int(M), n = int(N), k = int(K);
@@ -488,7 +489,9 @@ static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const
     if (!aligned_to(A, 4) || !aligned_to(B, 4) || !aligned_to(thr, 4) || !aligned_to(flip_bits, 4) ||
         !aligned_to(out, 4))
         return BNN_ERR_ALIGNMENT;
-    if (ceil_div(M, 16) * ceil_div(N, 16) > kMaxDim) return BNN_ERR_UNSUPPORTED;
+    // Tile grids and the row / column indices inside a tile (up to one tile past the matrix) are 32-bit.
+    if (ceil_div(M, 16) * ceil_div(N, 16) > kMaxDim || M > kMaxDim - 1024 || N > kMaxDim - 1024)
+        return BNN_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const BnSignArgs bn{thr, flip_bits, out, ld_out};
     if (kernel_id == KERNEL_AUTO)
@@ -511,7 +514,7 @@ static int bitplane_gemm_check(const uint32_t* Xp, int64_t ldx, const uint32_t* 
     if (ldx < 8 * kw || ldb < kw) return BNN_ERR_INVALID_ARG;
     if (M > 0 && N > 0 && K > 0 && (!Xp || !B)) return BNN_ERR_INVALID_ARG;
     if (!aligned_to(Xp, 4) || !aligned_to(B, 4)) return BNN_ERR_ALIGNMENT;
-    if (!mfma_planes_path_supports(K)) return BNN_ERR_UNSUPPORTED;
+    if (!mfma_planes_path_supports(K) || M > kMaxDim - 1024 || N > kMaxDim - 1024) return BNN_ERR_UNSUPPORTED;
     return BNN_OK;
 }
 

@@ -57,6 +57,7 @@ def test_argument_validation_happens_before_any_launch():
     assert lib.bnn_xnor_gemm(None, 2, p, 2, p, 4, 4, 4, 33, None) == INVALID
     assert lib.bnn_xnor_gemm(p, 2, p, 2, p, 4, 0, 4, 33, None) == 0
     assert lib.bnn_xnor_gemm_kernel(p, 2, p, 2, p, 4, 4, 4, 33, 99, None) == INVALID
+    assert lib.bnn_xnor_gemm(p, 2, p, 2, p, 4, 2 ** 31 - 100, 4, 33, None) == 3            # rows within a tile of 2^31: unsupported
     assert lib.bnn_bn_sign_pack(p, 3, 4, 4, p, p, p, 1, None) == INVALID
     assert lib.bnn_bn_sign_pack(p, 4, 4, 4, None, p, p, 1, None) == INVALID
     assert lib.bnn_conv_im2col_pack(p, 1, 4, 4, 32, 3, 3, 0, 1, p, 9, None) == INVALID   # stride 0
