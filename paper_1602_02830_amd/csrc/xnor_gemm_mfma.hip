@@ -400,13 +400,21 @@ int launch_bitplane_gemm_mfma_fused(const uint32_t* Xp, int64_t ldx, const uint3
 // Implicit-GEMM convolution: `in` is the packed NHWC input, B the packed filters [N][kh*kw*Cw].
 // The conv kernel reads A in unaligned-tolerant fashion only through 16-byte quads, so the
 // caller guarantees in is 16-byte aligned and Cw % 4 == 0.
+// Tile choice as for the plain product: 256 x 128 when that grid fills the chip's 512 workgroup
+// slots, else 128 x 128 (three workgroups per compute unit).
+static bool conv_wants_small_tiles(int64_t M, int64_t N) { return ceil_div(M, 256) * ceil_div(N, 128) < 512; }
+
 int launch_conv_mfma(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc, int64_t M,
                      int64_t N, int64_t K, ConvArgs cv, void* stream) {
+    if (conv_wants_small_tiles(M, N))
+        return launch_mfma<2, false, false, true>(in, 0, B, ldb, C, ldc, M, N, K, BnSignArgs{}, cv, stream);
     return launch_mfma<4, false, false, true>(in, 0, B, ldb, C, ldc, M, N, K, BnSignArgs{}, cv, stream);
 }
 
 int launch_conv_mfma_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
                            BnSignArgs bn, ConvArgs cv, void* stream) {
+    if (conv_wants_small_tiles(M, N))
+        return launch_mfma<2, true, false, true>(in, 0, B, ldb, nullptr, 0, M, N, K, bn, cv, stream);
     return launch_mfma<4, true, false, true>(in, 0, B, ldb, nullptr, 0, M, N, K, bn, cv, stream);
 }
 
