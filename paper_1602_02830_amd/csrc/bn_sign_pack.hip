@@ -108,7 +108,7 @@ extern "C" int bnn_bn_sign_pack(const int32_t* C, int64_t ldc, int64_t M, int64_
 
     const int64_t n_words = M * nw;
     int64_t blocks = ceil_div(n_words, int64_t(kBnThreads / 8) * kBnUnroll);
-    const int64_t max_blocks = 256 * 32;
+    const int64_t max_blocks = int64_t(1) << 20;   // one pass per workgroup up to 16 GiB of input
     if (blocks > max_blocks) blocks = max_blocks;
     const bool vec = aligned_to(C, 16) && aligned_to(thr, 16) && ldc % 4 == 0;
     const int64_t slice = kBnThreads / 8, pass = blocks * slice * kBnUnroll;

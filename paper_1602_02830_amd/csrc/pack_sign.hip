@@ -164,7 +164,9 @@ extern "C" int bnn_pack_sign(const float* x, int64_t rows, int64_t cols, int64_t
     const int64_t n_words = rows * kw;
     const int64_t groups_per_block = kPackThreads / 8;
     int64_t blocks = ceil_div(n_words, groups_per_block * kPackUnroll);
-    const int64_t max_blocks = 256 * 32;   // 256 CUs, enough blocks in flight to cover HBM latency
+    // One pass per workgroup up to 16 GiB of input: measured faster than a smaller grid that loops
+    // (1 GiB: 5.98 TB/s in one pass of 65536 workgroups, 5.60 TB/s with 8192 looping 8 times).
+    const int64_t max_blocks = int64_t(1) << 20;
     if (blocks > max_blocks) blocks = max_blocks;
     const bool vec = aligned_to(x, 16) && (ld_x % 4 == 0);
     const WordStep slice = word_step(groups_per_block, kw);
