@@ -404,8 +404,17 @@ int launch_bitplane_gemm_mfma_fused(const uint32_t* Xp, int64_t ldx, const uint3
 // slots, else 128 x 128 (three workgroups per compute unit).
 static bool conv_wants_small_tiles(int64_t M, int64_t N) { return ceil_div(M, 256) * ceil_div(N, 128) < 512; }
 
+// Short receptive fields (K <= 1152: 3 x 3 over 128 channels) go to the conv mode of the short-K
+// organisation (xnor_gemm_mfma_shortk.hip).
+bool conv_shortk_supports(const uint32_t* B, int64_t ldb, int64_t K);
+int launch_conv_mfma_shortk(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc, int64_t M,
+                            int64_t N, int64_t K, ConvArgs cv, void* stream);
+int launch_conv_mfma_shortk_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, int64_t M, int64_t N,
+                                  int64_t K, BnSignArgs bn, ConvArgs cv, void* stream);
+
 int launch_conv_mfma(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc, int64_t M,
                      int64_t N, int64_t K, ConvArgs cv, void* stream) {
+    if (conv_shortk_supports(B, ldb, K)) return launch_conv_mfma_shortk(in, B, ldb, C, ldc, M, N, K, cv, stream);
     if (conv_wants_small_tiles(M, N))
         return launch_mfma<2, false, false, true>(in, 0, B, ldb, C, ldc, M, N, K, BnSignArgs{}, cv, stream);
     return launch_mfma<4, false, false, true>(in, 0, B, ldb, C, ldc, M, N, K, BnSignArgs{}, cv, stream);
@@ -413,6 +422,7 @@ int launch_conv_mfma(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t
 
 int launch_conv_mfma_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
                            BnSignArgs bn, ConvArgs cv, void* stream) {
+    if (conv_shortk_supports(B, ldb, K)) return launch_conv_mfma_shortk_fused(in, B, ldb, M, N, K, bn, cv, stream);
     if (conv_wants_small_tiles(M, N))
         return launch_mfma<2, true, false, true>(in, 0, B, ldb, nullptr, 0, M, N, K, bn, cv, stream);
     return launch_mfma<4, true, false, true>(in, 0, B, ldb, nullptr, 0, M, N, K, bn, cv, stream);

@@ -24,6 +24,14 @@
 // Requirements (checked by the launcher): A, B 16-byte aligned, lda, ldb multiples of 4 words.
 // The last quad of a row, where it is incomplete or holds pad bits, is loaded from the row's last
 // four words (never past word K/32), moved into place and masked when it is written to LDS.
+//
+// Conv mode (CONV = true): A's rows are the receptive fields of a kh x kw convolution (Sec. 3.3)
+// over a packed NHWC input with a multiple of 128 channels, gathered while the tile is fetched
+// (implicit GEMM).  A quad is 4 channel words of one tap, so a staging thread's tap and channel
+// offset are fixed for the kernel's life; the output pixel of its rows is stepped with carries
+// from pass to pass and from tile to tile (no division inside the tile loop).  Taps outside the
+// image are +1, i.e. all-ones words (zero padding through Eq. (1)), chosen at staging so that
+// the loads stay unconditional (address clamped into the input).
 #include <algorithm>
 #include <cstdint>
 
@@ -70,11 +78,30 @@ __device__ inline uint4 align_last_quad(uint4 v, int shift, int valid, uint32_t 
     return o;
 }
 
-template <int TPR, bool FUSED>
+// Output pixel (image b, row y, column x) of a GEMM row, and a step of a fixed number of rows.
+struct Pixel {
+    int b, y, x;
+};
+
+__device__ inline Pixel pixel_of_row(int row, int Ho, int Wo) {
+    const int t = row / Wo;
+    return Pixel{t / Ho, t % Ho, row % Wo};
+}
+
+// p + d rows, d given as pixel_of_row(rows): one carry per coordinate.
+__device__ inline void advance(Pixel& p, Pixel d, int Ho, int Wo) {
+    p.x += d.x;
+    if (p.x >= Wo) { p.x -= Wo; ++p.y; }
+    p.y += d.y;
+    if (p.y >= Ho) { p.y -= Ho; ++p.b; }
+    p.b += d.b;
+}
+
+template <int TPR, bool FUSED, bool CONV>
 __global__ __launch_bounds__(256, 3) void xnor_gemm_mfma_shortk_kernel(
     const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B, int64_t ldb,
     int32_t* __restrict__ C, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n, int groups,
-    BnSignArgs bn) {
+    BnSignArgs bn, ConvArgs cv, uint32_t a_last_quad) {
     constexpr int WM = 2, WN = 2, BM = 64 * WM, BN = 64 * WN;
     static_assert(BM == BN, "one staging routine serves both operands");
     constexpr int PLANE = BM + 2;                       // 8-byte slots per plane (2 pad slots)
@@ -120,12 +147,48 @@ __global__ __launch_bounds__(256, 3) void xnor_gemm_mfma_shortk_kernel(
             r[l] = load_quad_dword_aligned(P + int64_t(row) * ld + word_off);
         }
     };
+    // conv: the tap (dy, dx relative to the output pixel's input position) and channel word of this
+    // thread's quad, the output pixel of its first row of the next tile to fetch, and the steps.
+    int tap_dy = 0, tap_dx = 0, tap_cw = 0;
+    Pixel next_pix{0, 0, 0}, pass_step{0, 0, 0}, tile_step{0, 0, 0};
+    uint32_t outside = 0u;                              // bit l: pass l's tap lies outside the image
+    if (CONV) {
+        const int tap = word_off / cv.Cw;
+        tap_cw = word_off - tap * cv.Cw;
+        tap_dy = tap / cv.kw - cv.pad;
+        tap_dx = tap % cv.kw - cv.pad;
+        next_pix = pixel_of_row(group * BM + st_r, cv.Ho, cv.Wo);
+        pass_step = pixel_of_row(ROWS_PER_PASS, cv.Ho, cv.Wo);
+        tile_step = pixel_of_row(groups * BM, cv.Ho, cv.Wo);
+    }
+    // Rows past the matrix (last tile only) step past the last image; their address is clamped to
+    // the input's last quad, and what they compute is never stored.
+    auto fetch_conv = [&](uint4 (&r)[PASSES]) __attribute__((always_inline)) {
+        Pixel p = next_pix;
+        outside = 0u;
+#pragma unroll
+        for (int l = 0; l < PASSES; ++l) {
+            const int y = p.y * cv.stride + tap_dy, x = p.x * cv.stride + tap_dx;
+            const bool inside = y >= 0 && y < cv.H && x >= 0 && x < cv.W;
+            const int yc = min(max(y, 0), cv.H - 1), xc = min(max(x, 0), cv.W - 1);
+            const uint32_t off = (uint32_t(p.b * cv.H + yc) * uint32_t(cv.W) + uint32_t(xc)) * uint32_t(cv.Cw) + uint32_t(tap_cw);
+            r[l] = *reinterpret_cast<const uint4*>(A + min(off, a_last_quad));
+            outside |= inside ? 0u : 1u << l;
+            advance(p, pass_step, cv.Ho, cv.Wo);
+        }
+        advance(next_pix, tile_step, cv.Ho, cv.Wo);
+    };
+    auto fetch_a = [&](int tile, uint4 (&r)[PASSES]) __attribute__((always_inline)) {
+        if (CONV) fetch_conv(r);
+        else fetch(A, lda, M, tile * BM, r);
+    };
     // Writes the fetched quads to their two planes and returns nothing; cnt[l] = set bits written.
-    auto stage = [&](uint2* planes, const uint4 (&r)[PASSES], int (&cnt)[PASSES]) __attribute__((always_inline)) {
+    auto stage = [&](uint2* planes, const uint4 (&r)[PASSES], int (&cnt)[PASSES], uint32_t ones) __attribute__((always_inline)) {
 #pragma unroll
         for (int l = 0; l < PASSES; ++l) {
             uint4 v = r[l];
             if (st_q >= n_fast) v = align_last_quad(v, 4 - last_valid, last_valid, tmask);
+            if (CONV && ((ones >> l) & 1u)) v = make_uint4(~0u, ~0u, ~0u, ~0u);
             cnt[l] = 0;
             if (st_q < kq) {
                 const int row = st_r + l * ROWS_PER_PASS;
@@ -148,8 +211,8 @@ __global__ __launch_bounds__(256, 3) void xnor_gemm_mfma_shortk_kernel(
             if (tid < BN) thr_s[tid] = col0 + tid < N ? max(-K - 1, min(K + 1, bn.thr[col0 + tid])) : 0;
             if (tid < BN / 32) flip_s[tid] = col0 + 32 * tid < N ? bn.flip_bits[(col0 >> 5) + tid] : 0u;
         }
-        if (group < tiles_m) fetch(A, lda, M, group * BM, ra);
-        stage(lds_b, rb, cnt);
+        if (group < tiles_m) fetch_a(group, ra);
+        stage(lds_b, rb, cnt, 0u);
 #pragma unroll
         for (int l = 0; l < PASSES; ++l) {
             const int c = sum_over_lanes<TPR>(cnt[l]);
@@ -157,7 +220,7 @@ __global__ __launch_bounds__(256, 3) void xnor_gemm_mfma_shortk_kernel(
         }
     }
     auto stage_a = [&](int buf) __attribute__((always_inline)) {
-        stage(lds_a, ra, cnt);
+        stage(lds_a, ra, cnt, outside);
 #pragma unroll
         for (int l = 0; l < PASSES; ++l) {
             const int c = sum_over_lanes<TPR>(cnt[l]);
@@ -177,7 +240,7 @@ __global__ __launch_bounds__(256, 3) void xnor_gemm_mfma_shortk_kernel(
     int buf = 0;
     for (int tile_m = group; tile_m < tiles_m; tile_m += groups, buf ^= 1) {
         const bool more = tile_m + groups < tiles_m;
-        if (more) fetch(A, lda, M, (tile_m + groups) * BM, ra);      // in flight during the MFMA steps
+        if (more) fetch_a(tile_m + groups, ra);                      // in flight during the MFMA steps
 
         v16f acc[WM][WN];
 #pragma unroll
@@ -244,34 +307,56 @@ static int shortk_groups(int64_t tiles_m, int64_t tiles_n) {
     return int(std::max<int64_t>(1, std::min<int64_t>(tiles_m, kSlots / tiles_n)));
 }
 
-template <bool FUSED>
+template <bool FUSED, bool CONV>
 static int launch_shortk(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc,
-                         int64_t M, int64_t N, int64_t K, BnSignArgs bn, void* stream) {
-    if (!mfma_shortk_supports(A, lda, B, ldb, K)) return BNN_ERR_UNSUPPORTED;
+                         int64_t M, int64_t N, int64_t K, BnSignArgs bn, ConvArgs cv, void* stream) {
     const int64_t tiles_m = ceil_div(M, 128), tiles_n = ceil_div(N, 128);
     const int groups = shortk_groups(tiles_m, tiles_n);
     if (tiles_n * groups > kMaxDim) return BNN_ERR_UNSUPPORTED;
     const int64_t kq = ceil_div(ceil_div(K, 32), 4);
     const size_t lds_bytes = size_t(2) * 2 * kq * (128 + 2) * sizeof(uint2);
+    // conv: word offset of the input's last 16-byte quad (the input holds whole images of M / (Ho * Wo)).
+    const uint32_t a_last_quad =
+        CONV ? uint32_t(M / (int64_t(cv.Ho) * cv.Wo) * cv.H * cv.W * cv.Cw - 4) : 0u;
     const dim3 grid(unsigned(tiles_n * groups));
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (kq <= 8)
-        hipLaunchKernelGGL((xnor_gemm_mfma_shortk_kernel<8, FUSED>), grid, dim3(256), lds_bytes, s, A, lda, B, ldb, C,
-                           ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), groups, bn);
+        hipLaunchKernelGGL((xnor_gemm_mfma_shortk_kernel<8, FUSED, CONV>), grid, dim3(256), lds_bytes, s, A, lda, B, ldb,
+                           C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), groups, bn, cv, a_last_quad);
     else
-        hipLaunchKernelGGL((xnor_gemm_mfma_shortk_kernel<16, FUSED>), grid, dim3(256), lds_bytes, s, A, lda, B, ldb, C,
-                           ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), groups, bn);
+        hipLaunchKernelGGL((xnor_gemm_mfma_shortk_kernel<16, FUSED, CONV>), grid, dim3(256), lds_bytes, s, A, lda, B, ldb,
+                           C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), groups, bn, cv, a_last_quad);
     return check_launch();
 }
 
 int launch_xnor_gemm_mfma_shortk(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
                                  int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream) {
-    return launch_shortk<false>(A, lda, B, ldb, C, ldc, M, N, K, BnSignArgs{}, stream);
+    if (!mfma_shortk_supports(A, lda, B, ldb, K)) return BNN_ERR_UNSUPPORTED;
+    return launch_shortk<false, false>(A, lda, B, ldb, C, ldc, M, N, K, BnSignArgs{}, ConvArgs{}, stream);
 }
 
 int launch_xnor_gemm_mfma_shortk_fused(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M,
                                        int64_t N, int64_t K, BnSignArgs bn, void* stream) {
-    return launch_shortk<true>(A, lda, B, ldb, nullptr, 0, M, N, K, bn, stream);
+    if (!mfma_shortk_supports(A, lda, B, ldb, K)) return BNN_ERR_UNSUPPORTED;
+    return launch_shortk<true, false>(A, lda, B, ldb, nullptr, 0, M, N, K, bn, ConvArgs{}, stream);
+}
+
+// Conv mode: `in` is the packed NHWC input (16-byte aligned, a multiple of 128 channels: checked by
+// the caller), B the packed filters [N][kh*kw*Cw].  K = kh*kw*Cin is then a multiple of 128.
+bool conv_shortk_supports(const uint32_t* B, int64_t ldb, int64_t K) {
+    return K <= 128 * kShortMaxQuads && aligned_to(B, 16) && ldb % 4 == 0;
+}
+
+int launch_conv_mfma_shortk(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc, int64_t M,
+                            int64_t N, int64_t K, ConvArgs cv, void* stream) {
+    if (!conv_shortk_supports(B, ldb, K)) return BNN_ERR_UNSUPPORTED;
+    return launch_shortk<false, true>(in, 0, B, ldb, C, ldc, M, N, K, BnSignArgs{}, cv, stream);
+}
+
+int launch_conv_mfma_shortk_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, int64_t M, int64_t N,
+                                  int64_t K, BnSignArgs bn, ConvArgs cv, void* stream) {
+    if (!conv_shortk_supports(B, ldb, K)) return BNN_ERR_UNSUPPORTED;
+    return launch_shortk<true, true>(in, 0, B, ldb, nullptr, 0, M, N, K, bn, cv, stream);
 }
 
 }  // namespace bnn

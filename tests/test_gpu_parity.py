@@ -517,6 +517,11 @@ def test_conv_layers_full_batch_sampled_images(fused):
     (2, 4, 4, 384, 16, 1, 1, 1, 0),
     (1, 32, 32, 128, 128, 3, 3, 1, 1),
     (40, 8, 8, 512, 512, 3, 3, 1, 1),
+    # short receptive fields (K <= 1152): the conv mode of the short-K kernel
+    (5, 13, 11, 128, 200, 3, 3, 2, 1),
+    (3, 9, 9, 256, 64, 2, 2, 1, 0),
+    (2, 5, 5, 1152, 32, 1, 1, 1, 0),
+    (7, 3, 50, 128, 130, 3, 3, 1, 2),
 ])
 def test_implicit_conv_matches_direct_convolution(shape):
     """Implicit-GEMM conv (no im2col matrix) == the oracle's direct convolution; fused form ==
