@@ -154,6 +154,61 @@ def test_xnor_gemm_multi_tile_shapes(kernel):
         _gemm_case(synth.pm1(rng, (M, K)), synth.pm1(rng, (K, N)), GEMM_KERNELS[kernel])
 
 
+def _offset_words(w: np.ndarray, ld: int, first: int) -> torch.Tensor:
+    """Device view of packed rows inside a junk-filled buffer: leading dimension ld, base `first` words
+    (4 * first bytes) past an allocation boundary."""
+    rows, kw = w.shape
+    buf = np.full(first + rows * ld + 4, 0xC3C3C3C3, np.uint32)
+    body = buf[first:first + rows * ld].reshape(rows, ld)
+    body[:, :kw] = w
+    flat = words_to_dev(buf)
+    return flat[first:first + rows * ld].view(rows, ld)[:, :kw]
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_xnor_gemm_randomized_shapes_strides_alignments_and_kernels(seed):
+    """Seeded random cases: M, N, K log-uniform, P(+1) anywhere in (0, 1), random leading dimensions and
+    base offsets (so both the 16-byte and the word-wise loaders run), poisoned pad bits, every kernel id.
+    A kernel either returns the exact product and the exact fused bits, or refuses with UNSUPPORTED."""
+    rng = np.random.default_rng(4242 + seed)
+    ids = list(GEMM_KERNELS.values()) + [bnn.KERNEL_MFMA_SHORTK]
+    fused_ids = {bnn.KERNEL_AUTO, bnn.KERNEL_TILED128, bnn.KERNEL_TILED64, bnn.KERNEL_MFMA, bnn.KERNEL_MFMA128,
+                 bnn.KERNEL_MFMA_SHORTK}
+    for _case in range(20):
+        M, N = (int(np.exp(rng.uniform(0, np.log(600)))) for _ in range(2))
+        K = int(np.exp(rng.uniform(0, np.log(5000))))
+        p = rng.uniform(0.02, 0.98)
+        A, Bm = synth.pm1(rng, (M, K), p), synth.pm1(rng, (K, N), p)
+        bn = synth.bn_params(rng, N, K, adversarial=True)
+        S, a_next = oracle.dense_layer(A, Bm, bn, eps=EPS)
+        kw = (K + 31) // 32
+        pa = poison_pad_bits(oracle.pack_bits(A), K)
+        pb = poison_pad_bits(oracle.pack_bits(np.ascontiguousarray(Bm.T)), K)
+        if rng.random() < 0.5:          # 16-byte-loadable layout
+            ld = (kw + 3) // 4 * 4 + 4 * int(rng.integers(0, 3))
+            da, db = _offset_words(pa, ld, 0), _offset_words(pb, ld, 4 * int(rng.integers(0, 3)))
+        else:
+            da = _offset_words(pa, kw + int(rng.integers(0, 6)), int(rng.integers(0, 4)))
+            db = _offset_words(pb, kw + int(rng.integers(0, 6)), int(rng.integers(0, 4)))
+        thr, flip = _fold_to_dev(bn, K)
+        want_bits = oracle.pack_bits(a_next)
+        for kid in ids:
+            tag = f"seed {seed} M={M} N={N} K={K} kernel {kid}"
+            try:
+                got = bnn.xnor_gemm(da, db, K, kernel=kid).cpu().numpy()
+            except bnn.BnnError as e:
+                assert e.status == 3, tag
+                continue
+            assert (got == S).all(), tag
+            try:
+                bits = words_to_host(bnn.xnor_gemm_bn_sign_pack(da, db, K, thr, flip, kernel=kid))
+            except bnn.BnnError as e:
+                # the naive and the K-split kernel have no fused form: invalid argument, as documented
+                assert e.status == (3 if kid in fused_ids else 1), tag
+                continue
+            assert kid in fused_ids and (bits == want_bits).all(), tag
+
+
 def _aligned_words(w: np.ndarray) -> torch.Tensor:
     """Device copy with the leading dimension rounded up to 4 words (junk in the extra words)."""
     kw = w.shape[1]
@@ -540,6 +595,31 @@ def test_implicit_conv_matches_direct_convolution(shape):
     bits = words_to_host(bnn.conv_bn_sign_pack(xb, Cin, wb, thr, flip, kh, kw, stride, pad))
     want = oracle.pack_bits(oracle.bn_sign(S.reshape(-1, Cout), *bn, eps=EPS))
     assert (bits == want).all()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_implicit_conv_randomized_geometries(seed):
+    """Seeded random geometries (batch, image size, channels, filter size, stride, padding, filters):
+    int32 sums against the oracle's direct convolution, fused bits against float BatchNorm + Sign."""
+    rng = np.random.default_rng(777 + seed)
+    for _case in range(12):
+        kh, kw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        pad, stride = int(rng.integers(0, 3)), int(rng.integers(1, 3))
+        H = int(rng.integers(max(1, kh - 2 * pad), 14))
+        W = int(rng.integers(max(1, kw - 2 * pad), 14))
+        B, Cin, Cout = int(rng.integers(1, 5)), 128 * int(rng.integers(1, 4)), int(rng.integers(1, 200))
+        tag = f"seed {seed} B={B} H={H} W={W} Cin={Cin} Cout={Cout} k={kh}x{kw} stride={stride} pad={pad}"
+        x = synth.pm1(rng, (B, H, W, Cin), rng.uniform(0.1, 0.9))
+        Wt = synth.pm1(rng, (Cout, kh, kw, Cin))
+        bn = synth.bn_params(rng, Cout, kh * kw * Cin, adversarial=True)
+        S = oracle.conv_direct(x, Wt, stride=stride, pad=pad)
+        xb = words_to_dev(_pack_nhwc(x).reshape(-1, Cin // 32)).view(B, H, W, Cin // 32)
+        wb = words_to_dev(oracle.pack_bits(Wt.reshape(Cout, -1)))
+        got = bnn.conv_xnor(xb, Cin, wb, kh, kw, stride, pad).cpu().numpy()
+        assert (got.reshape(S.shape) == S).all(), tag
+        thr, flip = _fold_to_dev(bn, kh * kw * Cin)
+        bits = words_to_host(bnn.conv_bn_sign_pack(xb, Cin, wb, thr, flip, kh, kw, stride, pad))
+        assert (bits == oracle.pack_bits(oracle.bn_sign(S.reshape(-1, Cout), *bn, eps=EPS))).all(), tag
 
 
 def test_implicit_conv_rejects_unsupported_channel_counts():
