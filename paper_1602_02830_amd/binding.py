@@ -88,8 +88,14 @@ def _check(fn: str, status: int):
         raise BnnError(fn, status)
 
 
-def _stream():
-    return _ptr(torch.cuda.current_stream().cuda_stream)
+_raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+
+
+def _stream(t: torch.Tensor):
+    """torch's current stream on the device of `t`, as the ABI's `void* stream`."""
+    if _raw_stream is not None:            # the handle itself, without building a Stream object
+        return _raw_stream(t.device.index)
+    return torch.cuda.current_stream(t.device).cuda_stream
 
 
 def _dev(t: torch.Tensor, dtype, name: str):
@@ -111,7 +117,10 @@ def version() -> int:
 
 
 def words_per_row(K: int) -> int:
-    return int(load_library().bnn_words_per_row(K))
+    """bnn_words_per_row: 32-bit words of a packed row of K values (the layout rule of the ABI, restated
+    here so that the wrappers do not pay a foreign call for it; a host test compares the two)."""
+    K = int(K)
+    return -1 if K < 0 else (K + 31) // 32
 
 
 def _alloc_words(rows: int, kw: int, device, ld: int | None = None) -> torch.Tensor:
@@ -134,7 +143,7 @@ def pack_sign(x: torch.Tensor, out: torch.Tensor | None = None, ld_out: int | No
         out = _alloc_words(rows, kw, x.device, ld_out)
     _dev(out, torch.int32, "out")
     _check("bnn_pack_sign", lib.bnn_pack_sign(x.data_ptr(), rows, cols, _ld(x), out.data_ptr(), _ld(out),
-                                             _stream()))
+                                             _stream(out)))
     return out
 
 
@@ -153,10 +162,10 @@ def xnor_gemm(A: torch.Tensor, B: torch.Tensor, K: int, out: torch.Tensor | None
     _dev(out, torch.int32, "out")
     if kernel == KERNEL_AUTO:
         st = lib.bnn_xnor_gemm(A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), out.data_ptr(), _ld(out), M, N, K,
-                               _stream())
+                               _stream(out))
     else:
         st = lib.bnn_xnor_gemm_kernel(A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), out.data_ptr(), _ld(out),
-                                      M, N, K, kernel, _stream())
+                                      M, N, K, kernel, _stream(out))
     _check("bnn_xnor_gemm", st)
     return out
 
@@ -191,7 +200,7 @@ def bn_sign_pack(C: torch.Tensor, thr: torch.Tensor, flip_bits: torch.Tensor,
         out = _alloc_words(M, nw, C.device, ld_out)
     _dev(out, torch.int32, "out")
     _check("bnn_bn_sign_pack", lib.bnn_bn_sign_pack(C.data_ptr(), _ld(C), M, N, thr.data_ptr(),
-                                                   flip_bits.data_ptr(), out.data_ptr(), _ld(out), _stream()))
+                                                   flip_bits.data_ptr(), out.data_ptr(), _ld(out), _stream(out)))
     return out
 
 
@@ -216,11 +225,11 @@ def xnor_gemm_bn_sign_pack(A: torch.Tensor, B: torch.Tensor, K: int, thr: torch.
     _dev(out, torch.int32, "out")
     if kernel == KERNEL_AUTO:
         st = lib.bnn_xnor_gemm_bn_sign_pack(A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), M, N, K, thr.data_ptr(),
-                                            flip_bits.data_ptr(), out.data_ptr(), _ld(out), _stream())
+                                            flip_bits.data_ptr(), out.data_ptr(), _ld(out), _stream(out))
     else:
         st = lib.bnn_xnor_gemm_bn_sign_pack_kernel(A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), M, N, K,
                                                    thr.data_ptr(), flip_bits.data_ptr(), out.data_ptr(),
-                                                   _ld(out), kernel, _stream())
+                                                   _ld(out), kernel, _stream(out))
     _check("bnn_xnor_gemm_bn_sign_pack", st)
     return out
 
@@ -235,7 +244,7 @@ def pack_bitplanes(x: torch.Tensor, out: torch.Tensor | None = None) -> torch.Te
         out = torch.empty((rows, kw8), dtype=torch.int32, device=x.device)
     _dev(out, torch.int32, "out")
     _check("bnn_pack_bitplanes", lib.bnn_pack_bitplanes(x.data_ptr(), rows, cols, _ld(x), out.data_ptr(), _ld(out),
-                                                       _stream()))
+                                                       _stream(out)))
     return out
 
 
@@ -249,7 +258,7 @@ def bitplane_gemm(Xp: torch.Tensor, B: torch.Tensor, K: int, out: torch.Tensor |
         out = torch.empty((M, N), dtype=torch.int32, device=Xp.device)
     _dev(out, torch.int32, "out")
     _check("bnn_bitplane_gemm", lib.bnn_bitplane_gemm(Xp.data_ptr(), _ld(Xp), B.data_ptr(), _ld(B), out.data_ptr(),
-                                                     _ld(out), M, N, K, _stream()))
+                                                     _ld(out), M, N, K, _stream(out)))
     return out
 
 
@@ -271,7 +280,7 @@ def bitplane_gemm_bn_sign_pack(Xp: torch.Tensor, B: torch.Tensor, K: int, thr: t
     _check("bnn_bitplane_gemm_bn_sign_pack",
            lib.bnn_bitplane_gemm_bn_sign_pack(Xp.data_ptr(), _ld(Xp), B.data_ptr(), _ld(B), M, N, K,
                                               thr.data_ptr(), flip_bits.data_ptr(), out.data_ptr(), _ld(out),
-                                              _stream()))
+                                              _stream(out)))
     return out
 
 
@@ -292,7 +301,7 @@ def conv_im2col_pack(x_bits: torch.Tensor, Cin: int, kh: int = 3, kw: int = 3, s
     _dev(out, torch.int32, "out")
     _check("bnn_conv_im2col_pack",
            lib.bnn_conv_im2col_pack(x_bits.data_ptr(), B, H, W, Cin, kh, kw, stride, pad, out.data_ptr(),
-                                    _ld(out), _stream()))
+                                    _ld(out), _stream(out)))
     return out
 
 
@@ -316,7 +325,7 @@ def conv_xnor(x_bits: torch.Tensor, Cin: int, w_bits: torch.Tensor, kh: int = 3,
         out = torch.empty((B * Ho * Wo, Cout), dtype=torch.int32, device=x_bits.device)
     _dev(out, torch.int32, "out")
     _check("bnn_conv_xnor", lib.bnn_conv_xnor(x_bits.data_ptr(), B, H, W, Cin, w_bits.data_ptr(), _ld(w_bits), Cout,
-                                             kh, kw, stride, pad, out.data_ptr(), _ld(out), _stream()))
+                                             kh, kw, stride, pad, out.data_ptr(), _ld(out), _stream(out)))
     return out
 
 
@@ -341,7 +350,7 @@ def conv_bn_sign_pack(x_bits: torch.Tensor, Cin: int, w_bits: torch.Tensor, thr:
     _check("bnn_conv_bn_sign_pack",
            lib.bnn_conv_bn_sign_pack(x_bits.data_ptr(), B, H, W, Cin, w_bits.data_ptr(), _ld(w_bits), Cout, kh, kw,
                                      stride, pad, thr.data_ptr(), flip_bits.data_ptr(), out.data_ptr(), _ld(out),
-                                     _stream()))
+                                     _stream(out)))
     return out
 
 
@@ -361,7 +370,7 @@ def maxpool_bits(x_bits: torch.Tensor, C: int, flip_bits: torch.Tensor | None, p
         raise ValueError("out must be a contiguous int32 device tensor [B][Hp][Wp][Cw]")
     _check("bnn_maxpool_bits", lib.bnn_maxpool_bits(x_bits.data_ptr(), B, H, W, C, ph, pw, stride,
                                                    flip_bits.data_ptr() if flip_bits is not None else None,
-                                                   out.data_ptr(), _stream()))
+                                                   out.data_ptr(), _stream(out)))
     return out
 
 
@@ -378,7 +387,7 @@ def gemm_i8_mfma(A: torch.Tensor, B: torch.Tensor, out: torch.Tensor | None = No
         out = torch.empty((M, N), dtype=torch.int32, device=A.device)
     _dev(out, torch.int32, "out")
     _check("bnn_gemm_i8_mfma", lib.bnn_gemm_i8_mfma(A.data_ptr(), _ld(A), B.data_ptr(), _ld(B), out.data_ptr(),
-                                                   _ld(out), M, N, K, _stream()))
+                                                   _ld(out), M, N, K, _stream(out)))
     return out
 
 
@@ -389,5 +398,5 @@ def unpack_i8(bits: torch.Tensor, K: int, ld_out: int | None = None) -> torch.Te
     rows = bits.shape[0]
     ld = ld_out if ld_out is not None else (K + 15) // 16 * 16
     buf = torch.empty((rows, ld), dtype=torch.int8, device=bits.device)
-    _check("bnn_unpack_i8", lib.bnn_unpack_i8(bits.data_ptr(), _ld(bits), rows, K, buf.data_ptr(), ld, _stream()))
+    _check("bnn_unpack_i8", lib.bnn_unpack_i8(bits.data_ptr(), _ld(bits), rows, K, buf.data_ptr(), ld, _stream(buf)))
     return buf[:, :K] if ld != K else buf

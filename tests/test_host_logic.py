@@ -37,6 +37,10 @@ def test_library_loads_and_exports_every_declared_symbol():
 def test_words_per_row():
     assert [bnn.words_per_row(k) for k in (0, 1, 31, 32, 33, 784, 4096)] == [0, 1, 1, 1, 2, 25, 128]
     assert bnn.words_per_row(-1) == -1
+    # the binding restates the rule; the library's own answer must agree
+    lib = binding.load_library()
+    for k in (-5, -1, 0, 1, 31, 32, 33, 63, 64, 65, 784, 4097, 2**31 - 2, 2**40 + 1):
+        assert lib.bnn_words_per_row(k) == bnn.words_per_row(k)
 
 
 def test_argument_validation_happens_before_any_launch():
