@@ -40,6 +40,7 @@ __device__ inline uint32_t quad_word(const uint4& q, int s) { return s == 0 ? q.
 
 // Epilogue of a wavefront that owns WM x WN blocks of 32 x 32 fp32 accumulators at block
 // position (wm, wn) of a (64*WM) x (64*WN) workgroup tile whose first row / column is row0 / col0.
+// Used for every int32 output and for the fused output of the planes product.
 // pop_a[tile row] / pop_b[tile column] hold 2*popcount (binary) or the plain row sum of the 8-bit
 // inputs (planes, pop_b unused); pop_af[tile row] = pop_a / 4 (binary) or / 2 (planes) as float;
 // thr_s[tile column] / flip_s[tile column / 32]: the tile's thresholds and flip words (fused only,
@@ -53,7 +54,7 @@ __device__ inline void mfma_epilogue(const v16f (&acc)[WM][WN], const int* pop_a
     // Result from the matrix-engine sum S:  binary  K - 2pa - 2pb + 4S,   planes  2S - rowsum.
     // Accumulator register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32 of its 32x32 block.
     constexpr int kShift = PLANES ? 1 : 2;
-    if (!FUSED) {
+    if constexpr (!FUSED) {
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
             const int nl = wn * 32 * WN + j * 32 + fr;
@@ -75,25 +76,25 @@ __device__ inline void mfma_epilogue(const v16f (&acc)[WM][WN], const int* pop_a
                 }
         }
     } else {
-        // bit(m, n) = (result >= thr[n]) XOR flip[n], i.e.
-        //   binary: S >= ceil((thr - K + 2pb + 2pa) / 4),   planes: S >= ceil((thr + rowsum) / 2).
+        // Fused epilogue of the planes product (the binary product has mfma_epilogue_bits below):
+        //   bit(m, n) = (2S - rowsum >= thr[n]) XOR flip[n], i.e. S >= ceil((thr + rowsum) / 2).
         // A ballot over one accumulator register gives, in its low half, the 32-column word of
         // the row held by lanes 0-31 and, in its high half, that of the row 4 below.  The words
         // of one 32-row block are gathered with v_writelane so that lane r (block j = 0) and
         // lane 32 + r (block j = 1) end up holding row r's two words: one store per block row.
+        static_assert(PLANES, "the binary product's fused epilogue is mfma_epilogue_bits");
         static_assert(WN == 2, "the fused epilogue pairs the two column blocks with the two lane halves");
         // While every term stays below 2^22 the comparison is done in float, where it is exact
-        // (all terms are multiples of 1/4): S >= (thr - K + 2pb)/4 + 2pa/4, resp. S >= thr/2 + rowsum/2.
-        // That is one add and one compare per element instead of four integer operations.
-        const bool fp_exact = PLANES ? (255 * int64_t(K) < (int64_t(1) << 22)) : (K <= (1 << 21));
-        int u3[WN];
+        // (all terms are multiples of 1/2): S >= thr/2 + rowsum/2.  That is one add and one compare
+        // per element instead of four integer operations.
+        const bool fp_exact = 255 * int64_t(K) < (int64_t(1) << 22);
+        int u1[WN];
         float tj[WN];
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
             const int nl = wn * 32 * WN + j * 32 + fr;
-            const int cj = PLANES ? thr_s[nl] : thr_s[nl] - K + pop_b[nl];
-            u3[j] = cj + (PLANES ? 1 : 3);
-            tj[j] = (PLANES ? 0.5f : 0.25f) * float(cj);
+            u1[j] = thr_s[nl] + 1;
+            tj[j] = 0.5f * float(thr_s[nl]);
         }
         // Flip and validity are applied to whole output words after the gather: lane l holds the
         // word of column block l / 32, whose flip word is flip_s[...] and whose valid bits are the
@@ -120,7 +121,7 @@ __device__ inline void mfma_epilogue(const v16f (&acc)[WM][WN], const int* pop_a
 #pragma unroll
                         for (int j = 0; j < WN; ++j) {
                             const float sacc = acc[i][j][4 * vq + e];
-                            const bool p = FP ? (sacc >= tj[j] + pf) : (int(sacc) >= ((u3[j] + pa) >> kShift));
+                            const bool p = FP ? (sacc >= tj[j] + pf) : (int(sacc) >= ((u1[j] + pa) >> 1));
                             const uint64_t mask = __ballot(p);
                             words = bnn_llvm_writelane(int(uint32_t(mask)), 32 * j + 8 * vq + e, words);
                             words = bnn_llvm_writelane(int(uint32_t(mask >> 32)), 32 * j + 8 * vq + 4 + e, words);
@@ -133,6 +134,102 @@ __device__ inline void mfma_epilogue(const v16f (&acc)[WM][WN], const int* pop_a
         };
         if (fp_exact) pack_and_store(std::true_type{});
         else pack_and_store(std::false_type{});
+    }
+}
+
+// Largest K for which the fused binary epilogue below may fold its threshold into the accumulators:
+// every term is a multiple of 1/8 and the largest magnitude is about 2K, exact in fp32 below 2^21.
+constexpr int kMfmaFoldMaxK = 1 << 19;
+
+// Column term of the folded threshold (see mfma_epilogue_bits): 1/8 - (thr - K + 2*popcount(B_n)) / 4,
+// pop_b2 = 2*popcount(B_n), thr clamped to [-K-1, K+1].  Exact in fp32 for K <= kMfmaFoldMaxK.
+__device__ inline float fold_column_term(int thr, int K, int pop_b2) {
+    return 0.125f - 0.25f * float(thr - K + pop_b2);
+}
+
+// Fused epilogue (binary product) of a wavefront whose accumulators hold the TRANSPOSED blocks:
+// the kernel issued its MFMAs with the operands swapped, so accumulator register v of lane l is
+// column 8*(v/4) + 4*(l/32) + v%4 and row l%32 of its 32 x 32 block - a lane holds 16 columns of
+// ONE output row, and the output bits of a row can be packed inside the lane, without ballots.
+//
+//   bit(m, n) = (K - 2pa - 2pb + 4S >= thr) XOR flip  =  (S - pa/2 - (thr - K + 2pb)/4 + 1/8 > 0) XOR flip
+//
+// (all terms multiples of 1/4, so adding 1/8 turns >= 0 into > 0 and the sum is never zero).
+// For K <= kMfmaFoldMaxK the row term -pa/2 and the column term colfix_s[n] (fold_column_term)
+// are added to all 1024 accumulators of a block by one v_mfma_f32_32x32x2_f32 (a rank-2 update:
+// column term x 1 + 1 x row term, exact in fp32), after which the output bit is the complement of
+// the accumulator's sign bit: one v_alignbit per accumulator shifts it into the lane's word.
+// Larger K compare in integers.  The two lane halves hold alternate groups of 4 columns; one
+// v_permlane32_swap brings the halves of column block 0 to lanes 0-31 and those of block 1 to
+// lanes 32-63, so that, as in mfma_epilogue, lane l stores the word of column block l / 32.
+// pop_a / pop_af / pop_b / thr_s / flip_s as in mfma_epilogue.
+template <int WM, int WN>
+__device__ inline void mfma_epilogue_bits(v16f (&acc)[WM][WN], const int* pop_a, const float* pop_af,
+                                          const int* pop_b, const int* thr_s, const uint32_t* flip_s,
+                                          const float* colfix_s, const BnSignArgs& bn, int M, int N, int K,
+                                          int row0, int col0, int wm, int wn, int fr, int fh) {
+    static_assert(WN == 2, "the two column blocks are paired with the two lane halves");
+    const int64_t nw = (int64_t(N) + 31) >> 5;
+    const int64_t w = ((int64_t(col0) + wn * 32 * WN) >> 5) + fh;       // word column of this lane
+    const uint32_t flip_word = flip_s[wn * WN + fh];                    // col0 is a multiple of 32
+    const int cols_left = N - (col0 + wn * 32 * WN + fh * 32);
+    const uint32_t live_word = cols_left >= 32 ? ~0u : cols_left <= 0 ? 0u : ((1u << cols_left) - 1u);
+    const bool fold = K <= kMfmaFoldMaxK;
+    // Operands of the rank-2 update: lane (r, h) holds element [r][k = h] of the 32 x 2 left factor
+    // (column term, 1) and element [k = h][r] of the 2 x 32 right factor (1, row term).
+    float left[WN];
+#pragma unroll
+    for (int j = 0; j < WN; ++j) left[j] = fh == 0 ? colfix_s[wn * 32 * WN + j * 32 + fr] : 1.0f;
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+        const int ml = wm * 32 * WM + i * 32 + fr;                       // this lane's row of the tile
+        uint32_t part[WN];                                               // this lane's 16 columns, spread out
+        if (fold) {
+            const float right = fh == 0 ? 1.0f : -pop_af[ml];
+#pragma unroll
+            for (int j = 0; j < WN; ++j) {
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(left[j], right, acc[i][j], 0, 0, 0);
+                uint32_t neg = 0u;                                       // bit k = sign of register k
+#pragma unroll
+                for (int v = 15; v >= 0; --v)
+                    neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[i][j][v]), 31);
+                part[j] = ~neg & 0xFFFFu;
+            }
+        } else {
+            const int base_m = K - pop_a[ml];
+#pragma unroll
+            for (int j = 0; j < WN; ++j) {
+                uint32_t bits = 0u;
+#pragma unroll
+                for (int g = 3; g >= 0; --g) {
+                    const int nl = wn * 32 * WN + j * 32 + 8 * g + 4 * fh;
+                    const int4 pb2 = *reinterpret_cast<const int4*>(&pop_b[nl]);
+                    const int4 th = *reinterpret_cast<const int4*>(&thr_s[nl]);
+#pragma unroll
+                    for (int e = 3; e >= 0; --e) {
+                        const int pb = e == 0 ? pb2.x : e == 1 ? pb2.y : e == 2 ? pb2.z : pb2.w;
+                        const int t = e == 0 ? th.x : e == 1 ? th.y : e == 2 ? th.z : th.w;
+                        const int dot = base_m - pb + (int(acc[i][j][4 * g + e]) << 2);
+                        bits = (bits << 1) | (dot >= t ? 1u : 0u);
+                    }
+                }
+                part[j] = bits;
+            }
+        }
+        // Bit 4g + e of part[j] is column 8g + 4*fh + e of block j: move nibble g to bit 8g + 4*fh.
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            uint32_t x = part[j];
+            x = (x | (x << 8)) & 0x00FF00FFu;
+            x = (x | (x << 4)) & 0x0F0F0F0Fu;
+            part[j] = x << (4 * fh);
+        }
+        // Lanes 32-63 of part[0] <-> lanes 0-31 of part[1]: afterwards lane l holds, in the two
+        // registers, the two halves of the word of column block l / 32.
+        const auto sw = __builtin_amdgcn_permlane32_swap(part[0], part[1], false, false);
+        const uint32_t word = sw[0] | sw[1];
+        const int m = row0 + ml;
+        if (m < M && w < nw) bn.out[int64_t(m) * bn.ld_out + w] = (word ^ flip_word) & live_word;
     }
 }
 

@@ -71,8 +71,12 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
     __shared__ __attribute__((aligned(16))) int pop_a[BM];
     __shared__ __attribute__((aligned(16))) int pop_b[BN];
     __shared__ __attribute__((aligned(16))) float pop_af[FUSED ? BM : 4];   // row term of the float threshold
-    __shared__ int thr_s[FUSED ? BN : 1];                  // the tile's thresholds and flip words, fetched
+    __shared__ __attribute__((aligned(16))) int thr_s[FUSED ? BN : 1];                  // the tile's thresholds and flip words, fetched
     __shared__ uint32_t flip_s[FUSED ? BN / 32 : 1];       // before the K loop (read in the epilogue)
+    // The fused binary kernel multiplies with the operands swapped: its accumulator blocks are the
+    // transposes of the output blocks, which lets the epilogue pack a row's bits inside a lane.
+    constexpr bool BITS = FUSED && !PLANES;
+    __shared__ float colfix_s[BITS ? BN : 1];              // column term of the folded threshold
 
     int tile_m, tile_n;
     tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
@@ -296,9 +300,14 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
 #pragma unroll
                 for (int i = 0; i < WM; ++i)
 #pragma unroll
-                    for (int j = 0; j < WN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                            fa[i], fb[j], acc[i][j], 4 /* A: fp4 */, 4 /* B: fp4 */, 0, scale_a, 0, scale_b);
+                    for (int j = 0; j < WN; ++j) {
+                        if (BITS)
+                            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                                fb[j], fa[i], acc[i][j], 4 /* fp4 */, 4 /* fp4 */, 0, 0, 0, 0);
+                        else
+                            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                                fa[i], fb[j], acc[i][j], 4 /* A: fp4 */, 4 /* B: fp4 */, 0, scale_a, 0, scale_b);
+                    }
             }
         }
 
@@ -332,12 +341,19 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void xnor_gemm_mfma_kernel(
         int c = cnt_b[l];
         c += __builtin_amdgcn_update_dpp(0, c, 0xB1, 0xF, 0xF, true);
         c += __builtin_amdgcn_update_dpp(0, c, 0x4E, 0xF, 0xF, true);
-        if (st_q == 0) pop_b[st_r + l * ST_ROWS] = 2 * c;
+        if (st_q == 0) {
+            pop_b[st_r + l * ST_ROWS] = 2 * c;
+            if (BITS) colfix_s[st_r + l * ST_ROWS] = fold_column_term(thr_s[st_r + l * ST_ROWS], K, 2 * c);
+        }
     }
     __syncthreads();
 
-    mfma_epilogue<WM, WN, FUSED, PLANES>(acc, pop_a, pop_af, pop_b, thr_s, flip_s, C, ldc, bn, M, N, K, row0, col0, wm, wn,
-                                         fr, fh);
+    if constexpr (BITS)
+        mfma_epilogue_bits<WM, WN>(acc, pop_a, pop_af, pop_b, thr_s, flip_s, colfix_s, bn, M, N, K, row0, col0, wm, wn,
+                                   fr, fh);
+    else
+        mfma_epilogue<WM, WN, FUSED, PLANES>(acc, pop_a, pop_af, pop_b, thr_s, flip_s, C, ldc, bn, M, N, K, row0, col0,
+                                             wm, wn, fr, fh);
 }
 
 template <int WM, bool FUSED, bool PLANES, bool CONV>

@@ -111,8 +111,9 @@ __global__ __launch_bounds__(256, 3) void xnor_gemm_mfma_shortk_kernel(
     __shared__ __attribute__((aligned(16))) int pop_a[2][BM];
     __shared__ __attribute__((aligned(16))) float pop_af[2][FUSED ? BM : 4];
     __shared__ __attribute__((aligned(16))) int pop_b[BN];
-    __shared__ int thr_s[FUSED ? BN : 1];
+    __shared__ __attribute__((aligned(16))) int thr_s[FUSED ? BN : 1];
     __shared__ uint32_t flip_s[FUSED ? BN / 32 : 1];
+    __shared__ float colfix_s[FUSED ? BN : 1];          // column term of the folded threshold
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -232,6 +233,8 @@ __global__ __launch_bounds__(256, 3) void xnor_gemm_mfma_shortk_kernel(
     };
     if (group < tiles_m) stage_a(0);
     __syncthreads();
+    // Read by the first epilogue, which follows another barrier.
+    if (FUSED && tid < BN) colfix_s[tid] = fold_column_term(thr_s[tid], K, pop_b[tid]);
 
     // Operand slots of this lane: plane (q, fh), rows wm*64 + 32*i + fr (A) / wn*64 + 32*j + fr (B).
     const uint2* rd_a = lds_a + fh * PLANE + wm * 32 * WM + fr;
@@ -273,9 +276,15 @@ __global__ __launch_bounds__(256, 3) void xnor_gemm_mfma_shortk_kernel(
 #pragma unroll
                 for (int i = 0; i < WM; ++i)
 #pragma unroll
-                    for (int j = 0; j < WN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                            fa[i], fb[j], acc[i][j], 4 /* A: fp4 */, 4 /* B: fp4 */, 0, 0, 0, 0);
+                    for (int j = 0; j < WN; ++j) {
+                        // fused: operands swapped, the accumulators hold the transposed blocks (mfma_epilogue_bits)
+                        if (FUSED)
+                            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                                fb[j], fa[i], acc[i][j], 4 /* fp4 */, 4 /* fp4 */, 0, 0, 0, 0);
+                        else
+                            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                                fa[i], fb[j], acc[i][j], 4 /* A: fp4 */, 4 /* B: fp4 */, 0, 0, 0, 0);
+                    }
             }
 #pragma unroll
             for (int i = 0; i < WM; ++i) a_cur[i] = a_nxt[i];
@@ -285,8 +294,12 @@ __global__ __launch_bounds__(256, 3) void xnor_gemm_mfma_shortk_kernel(
 
         __syncthreads();                            // every wavefront has read this tile's planes
         if (more) stage_a(buf ^ 1);                 // next tile's bits and row sums (the other pop_a half)
-        mfma_epilogue<WM, WN, FUSED, false>(acc, pop_a[buf], pop_af[buf], pop_b, thr_s, flip_s, C, ldc, bn, M, N, K,
-                                            tile_m * BM, col0, wm, wn, fr, fh);
+        if constexpr (FUSED)
+            mfma_epilogue_bits<WM, WN>(acc, pop_a[buf], pop_af[buf], pop_b, thr_s, flip_s, colfix_s, bn, M, N, K,
+                                       tile_m * BM, col0, wm, wn, fr, fh);
+        else
+            mfma_epilogue<WM, WN, false, false>(acc, pop_a[buf], pop_af[buf], pop_b, thr_s, flip_s, C, ldc, bn, M, N, K,
+                                                tile_m * BM, col0, wm, wn, fr, fh);
         __syncthreads();                            // next tile staged; this tile's row sums no longer needed
     }
 }

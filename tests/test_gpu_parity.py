@@ -294,7 +294,7 @@ def test_mfma_kernels_at_the_exact_accumulation_limit(kernel):
     pb = words_to_dev(oracle.pack_bits(np.ascontiguousarray(Bm.T)))
     got = bnn.xnor_gemm(pa, pb, K, kernel=GEMM_KERNELS[kernel]).cpu().numpy()
     assert (got == want).all()
-    # fused form at this K compares in integers (the float comparison is exact only up to K = 2^21)
+    # fused form at this K compares in integers (thresholds are folded into fp32 sums only up to K = 2^19)
     thr = torch.tensor([K, 0, -K + 2], dtype=torch.int32, device=DEV)
     flip = torch.tensor([0b100], dtype=torch.int32, device=DEV)
     bits = words_to_host(bnn.xnor_gemm_bn_sign_pack(pa, pb, K, thr, flip, kernel=GEMM_KERNELS[kernel]))
@@ -312,10 +312,11 @@ def test_mfma_kernels_at_the_exact_accumulation_limit(kernel):
     assert (bnn.xnor_gemm(pa2, pb2, K2).cpu().numpy() == want + oracle.matmul_pm1(A2[:, K:], B2[K:, :])).all()
 
 
-@pytest.mark.parametrize("K", [1 << 21, (1 << 21) + 32])
+@pytest.mark.parametrize("K", [1 << 19, (1 << 19) + 32, 1 << 21])
 def test_fused_layer_on_both_sides_of_the_float_compare_limit(K):
-    """Up to K = 2^21 the fused epilogue of the matrix-engine kernel compares in float, beyond in integers;
-    both must give the folded BatchNorm + Sign bits."""
+    """Up to K = 2^19 the fused epilogue of the matrix-engine kernel folds the threshold into its fp32
+    accumulators and reads the output bit off their sign, beyond it compares in integers; both must give
+    the folded BatchNorm + Sign bits, also for thresholds at and next to attained values."""
     M, N = 9, 40
     rng = np.random.default_rng(K % 1000)
     A, Bm = synth.pm1(rng, (M, K)), synth.pm1(rng, (K, N))
