@@ -101,6 +101,25 @@ def gemm_only(args, bnn, torch, dev):
                       "binary_tops": ops / ms / 1e9}), flush=True)
 
 
+def stream_only(args, bnn, torch, dev):
+    """One streaming kernel (Sign packer or BN+Sign epilogue) on a rows x cols input: one JSON line."""
+    rows, cols = (int(v) for v in args.shape.split(","))
+    nw = (cols + 31) // 32
+    out = torch.empty((rows, nw), dtype=torch.int32, device=dev)
+    if args.stream == "pack_sign":
+        x = torch.empty((rows, cols), dtype=torch.float32, device=dev).normal_()
+        fn = lambda: bnn.pack_sign(x, out=out)
+    else:
+        c = torch.randint(-cols, cols + 1, (rows, cols), dtype=torch.int32, device=dev)
+        thr = torch.randint(-8, 9, (cols,), dtype=torch.int32, device=dev)
+        flip = torch.randint(-2 ** 31, 2 ** 31 - 1, (nw,), dtype=torch.int32, device=dev)
+        fn = lambda: bnn.bn_sign_pack(c, thr, flip, out=out)
+    ms, _ = time_launches(fn, args.steps, warmup=args.warmup)
+    nbytes = rows * cols * 4 + rows * nw * 4
+    print(json.dumps({"workload": f"{args.stream}_{rows}x{cols}", "steps": args.steps, "warmup": args.warmup,
+                      "avg_launch_ms": ms, "algorithmic_bytes": nbytes, "GBps": nbytes / ms / 1e6}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -122,6 +141,9 @@ def main():
     ap.add_argument("--kernel", default="auto", choices=["auto", "naive", "tiled128", "ksplit", "tiled64", "mfma", "mfma128", "mfma_shortk", "i8"],
                     help="kernel for --gemm (i8 = the int8 MFMA variant on unpacked operands)")
     ap.add_argument("--fused", action="store_true", help="with --gemm: the fused BN+Sign entry point instead")
+    ap.add_argument("--stream", default=None, choices=["pack_sign", "bn_sign_pack"],
+                    help="time only this streaming kernel on a --shape input (for profiler runs)")
+    ap.add_argument("--shape", default="32768,8192", metavar="ROWS,COLS", help="input shape for --stream")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -140,6 +162,9 @@ def main():
 
     if args.gemm:
         gemm_only(args, bnn, torch, dev)
+        return
+    if args.stream:
+        stream_only(args, bnn, torch, dev)
         return
 
     # ---------------- workload: MNIST-shaped MLP, batch 10000, synthetic -------------

@@ -12,6 +12,10 @@
 // loads: lane l of a fragment takes row (l % 32), bytes [16*(l/32), +16) of the
 // 32-deep K step.  A and B fragments use the same lane -> k assignment, so the
 // sum over k is complete whatever order the hardware consumes them in.
+// LDS holds one plane of 16-byte slots per 16-byte chunk of the K-tile (slot r =
+// that chunk of tile row r), so a fragment read is 32 consecutive slots; two pad
+// slots per plane keep the four chunks a row's staging threads write in
+// different banks.
 //
 // bnn_unpack_i8 expands packed bits to this operand format.
 #include "bnn_internal.h"
@@ -23,7 +27,6 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kI8KT = 64;                 // bytes of K per staged tile
 constexpr int kI8Chunks = kI8KT / 16;     // 16-byte chunks per tile row
-constexpr int kI8RowSlots = kI8Chunks + 1;  // one chunk of padding per row against bank conflicts
 
 // 16 bytes of row `row` starting at byte k0 of the matrix row; zero outside
 // the matrix and for k >= K.
@@ -51,8 +54,9 @@ __global__ __launch_bounds__(256) void gemm_i8_mfma_kernel(
     int32_t* __restrict__ C, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n) {
     constexpr int BM = 64 * WM, BN = 64 * WN;
     constexpr int LOADS_A = BM * kI8Chunks / 256, LOADS_B = BN * kI8Chunks / 256;
-    __shared__ v4i lds_a[2][BM * kI8RowSlots];
-    __shared__ v4i lds_b[2][BN * kI8RowSlots];
+    constexpr int PLANE_A = BM + 2, PLANE_B = BN + 2;      // slots per chunk plane
+    __shared__ v4i lds_a[2][kI8Chunks * PLANE_A];
+    __shared__ v4i lds_b[2][kI8Chunks * PLANE_B];
 
     // Consecutive workgroups go to different dies; give each die a contiguous
     // range of tiles so its L2 keeps a few operand panels.
@@ -83,9 +87,9 @@ __global__ __launch_bounds__(256) void gemm_i8_mfma_kernel(
     };
     auto stage = [&](int buf) {
 #pragma unroll
-        for (int l = 0; l < LOADS_A; ++l) lds_a[buf][(st_r + l * ST_ROWS) * kI8RowSlots + st_c] = ra[l];
+        for (int l = 0; l < LOADS_A; ++l) lds_a[buf][st_c * PLANE_A + st_r + l * ST_ROWS] = ra[l];
 #pragma unroll
-        for (int l = 0; l < LOADS_B; ++l) lds_b[buf][(st_r + l * ST_ROWS) * kI8RowSlots + st_c] = rb[l];
+        for (int l = 0; l < LOADS_B; ++l) lds_b[buf][st_c * PLANE_B + st_r + l * ST_ROWS] = rb[l];
     };
 
     v16i acc[WM][WN];
@@ -111,10 +115,10 @@ __global__ __launch_bounds__(256) void gemm_i8_mfma_kernel(
             v4i a[WM], b[WN];
 #pragma unroll
             for (int i = 0; i < WM; ++i)
-                a[i] = lds_a[buf][(wm * 32 * WM + i * 32 + fr) * kI8RowSlots + ks * 2 + fk];
+                a[i] = lds_a[buf][(ks * 2 + fk) * PLANE_A + wm * 32 * WM + i * 32 + fr];
 #pragma unroll
             for (int j = 0; j < WN; ++j)
-                b[j] = lds_b[buf][(wn * 32 * WN + j * 32 + fr) * kI8RowSlots + ks * 2 + fk];
+                b[j] = lds_b[buf][(ks * 2 + fk) * PLANE_B + wn * 32 * WN + j * 32 + fr];
 #pragma unroll
             for (int i = 0; i < WM; ++i)
 #pragma unroll
@@ -174,7 +178,7 @@ extern "C" int bnn_gemm_i8_mfma(const int8_t* A, int64_t lda, const int8_t* B, i
     if (!aligned_to(C, 4)) return BNN_ERR_ALIGNMENT;
     if (K > 0 && (!aligned_to(A, 16) || !aligned_to(B, 16) || lda % 16 != 0 || ldb % 16 != 0))
         return BNN_ERR_ALIGNMENT;
-    constexpr int WM = 2, WN = 2;
+    constexpr int WM = 4, WN = 2;
     const int64_t tiles_m = ceil_div(M, 64 * WM), tiles_n = ceil_div(N, 64 * WN);
     if (tiles_m * tiles_n > kMaxDim) return BNN_ERR_UNSUPPORTED;
     hipLaunchKernelGGL((gemm_i8_mfma_kernel<WM, WN>), dim3(unsigned(tiles_m * tiles_n)), dim3(256), 0,
