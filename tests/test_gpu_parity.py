@@ -405,6 +405,63 @@ def test_xnor_gemm_large_square_hadamard_and_sampled_rows(kernel):
     assert (np.abs(C) <= n).all() and (C % 2 == 0).all()
 
 
+def test_matrices_of_more_than_2_31_elements():
+    """Maximum sizes: an int32 result of 2.16e9 elements (8.6 GB, element offsets beyond 2^31), the
+    streaming epilogue and the Sign packer on matrices of that size, and the fused layer writing the
+    same rows.  Rows are sampled at the start, around element 2^31 and at the ragged end."""
+    M, N, K = 65536 + 130, 32768 + 70, 64
+    rng = np.random.default_rng(231)
+    A, Bm = synth.pm1(rng, (M, K)), synth.pm1(rng, (K, N))
+    bn = synth.bn_params(rng, N, K, adversarial=True)
+    da = words_to_dev(oracle.pack_bits(A))
+    db = words_to_dev(oracle.pack_bits(np.ascontiguousarray(Bm.T)))
+    thr, flip = _fold_to_dev(bn, K)
+    first_past = (1 << 31) // N                         # the row that holds element 2^31
+    rows = np.unique(np.concatenate([np.arange(3), np.arange(first_past - 2, first_past + 3), np.arange(M - 140, M)]))
+    rows_t = torch.from_numpy(rows).to(DEV)
+    S_want, a_want = oracle.dense_layer(A[rows], Bm, bn, eps=EPS)
+    bits_want = oracle.pack_bits(a_want)
+    C = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    for kernel in ("auto", "naive", "tiled128", "tiled64", "mfma", "mfma128"):
+        C.fill_(0x5EED5EED)
+        bnn.xnor_gemm(da, db, K, out=C, kernel=GEMM_KERNELS[kernel])
+        assert (C[rows_t].cpu().numpy() == S_want).all(), kernel
+        assert int(C.max()) <= K and int(C.min()) >= -K, kernel         # every element was written
+    bits = bnn.bn_sign_pack(C, thr, flip)
+    assert (words_to_host(bits[rows_t]) == bits_want).all()
+    for kernel in ("auto", "tiled128", "mfma", "mfma128"):
+        fused = bnn.xnor_gemm_bn_sign_pack(da, db, K, thr, flip, kernel=GEMM_KERNELS[kernel])
+        assert torch.equal(fused, bits), kernel
+    del bits, fused
+    g = torch.Generator(device=DEV)
+    g.manual_seed(231)
+    x = C.view(torch.float32)                            # reuse the 8.6 GB: overwritten with N(0,1) draws
+    x.normal_(generator=g)
+    x[rows_t[0], :5] = torch.tensor([0.0, -0.0, float("nan"), 1e-45, -1e-45], device=DEV)
+    packed = bnn.pack_sign(x)
+    assert (words_to_host(packed[rows_t]) == oracle.pack_bits(oracle.sign(x[rows_t].cpu().numpy()))).all()
+
+
+def test_packed_operand_of_more_than_4_GiB():
+    """A packed A of 65666 x 2^19 bits (4.3 GB: byte offsets beyond 2^32) against a small B; the operand is
+    drawn on the device from a seeded generator and the oracle multiplies sampled rows of it."""
+    M, N, K = 65536 + 130, 40, 1 << 19
+    kw = K // 32
+    g = torch.Generator(device=DEV)
+    g.manual_seed(232)
+    da = torch.randint(-2 ** 31, 2 ** 31 - 1, (M, kw), dtype=torch.int32, device=DEV, generator=g)
+    rng = np.random.default_rng(232)
+    Bm = synth.pm1(rng, (K, N))
+    db = words_to_dev(oracle.pack_bits(np.ascontiguousarray(Bm.T)))
+    rows = np.unique(np.concatenate([np.arange(2), [32767, 32768, 32769], np.arange(M - 6, M)]))
+    rows_t = torch.from_numpy(rows).to(DEV)
+    A_rows = oracle.unpack_bits(words_to_host(da[rows_t]), K)
+    want = oracle.matmul_pm1(A_rows, Bm)
+    for kernel in ("auto", "tiled64", "mfma128"):
+        got = bnn.xnor_gemm(da, db, K, kernel=GEMM_KERNELS[kernel])
+        assert (got[rows_t].cpu().numpy() == want).all(), kernel
+
+
 # ------------------------------------------------------------------ bn_sign_pack
 
 def _fold_to_dev(bn, K):
