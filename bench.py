@@ -38,7 +38,7 @@ PEAK_FP4_MFMA_TFLOPS = 10100.0                            # dense fp4/fp6 MFMA, 
 # HBM bytes per launch of the dominant kernel (fetched + written), from the FETCH_SIZE / WRITE_SIZE counter
 # runs summarised in profiles/xnor_gemm_mfma_mlp_batch10000.txt and profiles/xnor_gemm_tiled128_mlp_batch10000.txt.
 WARM_SECONDS = 0.05
-PROFILED_TRAFFIC_BYTES = {("mfma", True): 23.2e6 + 5.2e6, ("valu", False): 32.9e6 + 166.4e6}
+PROFILED_TRAFFIC_BYTES = {("mfma", True): 23.1e6 + 5.2e6, ("valu", False): 32.9e6 + 166.4e6}
 
 
 def log(*a):
