@@ -738,6 +738,42 @@ def test_mlp_chain_every_intermediate_small_batch():
         assert (net.s[l].cpu().numpy() == tr["s"][l]).all(), f"s_{l}"
 
 
+def test_mlp_forward_captured_in_a_hip_graph_replays_bit_exact():
+    """The library allocates nothing and never synchronises, so a forward pass can be captured in a HIP
+    graph.  Every replay, on fresh inputs written into the captured input buffer and with eager work and
+    synchronisations in between, must give the oracle's scores and activations."""
+    batch = 600
+    x0, weights, bns = synth.config_mlp(batch=batch, adversarial=True)
+    wr = [torch.from_numpy(np.ascontiguousarray(w.T).astype(np.float32)).to(DEV) for w in weights]
+    net = bnn.BinaryMLP(wr, bns, EPS, batch)
+    x_static = torch.from_numpy(x0).to(DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                        # warm-up outside the capture, as torch asks
+        net.forward(x_static)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        net.forward(x_static)
+    rng = np.random.default_rng(600)
+    for replay in range(4):
+        x = synth.real_input(rng, x0.shape)
+        tr = oracle.mlp_forward(x, weights, bns, eps=EPS)
+        x_static.copy_(torch.from_numpy(x))
+        for buf in net.s + net.a_bits:
+            if buf is not None:
+                buf.fill_(0x3C3C3C3C)                        # nothing may survive from the previous replay
+        graph.replay()
+        torch.cuda.synchronize()
+        assert (net.s[-1].cpu().numpy() == tr["s"][-1]).all(), f"scores, replay {replay}"
+        for l in range(1, len(weights)):
+            assert (words_to_host(net.a_bits[l]) == oracle.pack_bits(tr["a"][l])).all(), f"a^b_{l}, replay {replay}"
+        # eager work of the same library between the replays
+        net.forward(torch.from_numpy(x0).to(DEV))
+        torch.cuda.synchronize()
+        assert (net.s[-1].cpu().numpy() == oracle.mlp_forward(x0, weights, bns, eps=EPS)["s"][-1]).all()
+
+
 def test_mlp_full_batch_sampled_rows():
     """Batch 10000 as benchmarked; samples (rows) are independent, so the oracle runs on 500 of them."""
     x, weights, bns = synth.config_mlp()
