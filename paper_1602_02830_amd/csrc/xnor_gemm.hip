@@ -227,26 +227,32 @@ __global__ __launch_bounds__(256, 3) void xnor_gemm_tiled_kernel(
 }
 
 // ----------------------------------------------------------------------------
-// ksplit: skinny outputs.  An aligned group of 8 lanes owns one row of the long operand X and
-// up to 16 rows of the short operand Y; the 8 lanes split K by 16-byte quads (so a group reads
-// 128 contiguous bytes of its X row per load), each lane keeps 16 partial sums, and the group
-// combines them with three DPP permutes per sum.  K advances in chunks of 256 words: the
-// workgroup stages the chunk of Y in LDS (every group needs all of it) while each lane's 8 quads
-// of X are in flight, so one chunk costs a single global-memory round trip.  out(x, y) is
+// ksplit: skinny outputs.  An aligned group of LPR = 8 or 16 lanes owns one row of the long
+// operand X and up to 16 rows of the short operand Y; the lanes split K by 16-byte quads (so a
+// group reads 128 or 256 contiguous bytes of its X row per load), each lane keeps 16 partial sums,
+// and the group combines them with three or four DPP permutes per sum.  K advances in chunks of
+// 256 words: the workgroup stages the chunk of Y in LDS (every group needs all of it) while each
+// lane's quads of X are in flight, so one chunk costs a single global-memory round trip.  16 lanes
+// per row halve the serial work of a lane and double the workgroups (10000 x 10, K = 4096:
+// 7.0 -> 5.5 us); the launcher uses them while the grid stays small.  out(x, y) is
 // stored at C[x * sx + y * sy], which lets the same kernel serve few columns (X = A) and few
 // rows (X = B).
 // ----------------------------------------------------------------------------
 constexpr int kSkinnyCols = 16;
 constexpr int kSkinnyChunkQuads = 64;     // 256 words of K per chunk
+constexpr int64_t kKsplitWideMaxGroups = 1024;   // row groups of 16 up to which a row gets 16 lanes
 
-template <bool VEC>
+template <bool VEC, int LPR>
 __global__ __launch_bounds__(256) void xnor_gemm_ksplit_kernel(
     const uint32_t* __restrict__ X, int64_t ldx, int nx, const uint32_t* __restrict__ Y, int64_t ldy, int ny,
     int32_t* __restrict__ C, int64_t sx, int64_t sy, int K) {
     __shared__ uint4 lds_y[kSkinnyCols * kSkinnyChunkQuads];          // [row][quad]
     const int tid = threadIdx.x;
-    const int q = tid & 7;
-    const int row = blockIdx.x * 32 + (tid >> 3);                     // 32 groups per workgroup
+    static_assert(LPR == 8 || LPR == 16, "aligned groups of 8 or 16 lanes per row");
+    constexpr int ROWS = 256 / LPR;                                   // rows (lane groups) per workgroup
+    constexpr int STEPS = kSkinnyChunkQuads / LPR;                    // quads per lane and chunk
+    const int q = tid & (LPR - 1);
+    const int row = blockIdx.x * ROWS + tid / LPR;
     const int y0 = blockIdx.y * kSkinnyCols;
     const int kw = (K + 31) >> 5;
     const uint32_t tmask = tail_mask(K);
@@ -266,12 +272,12 @@ __global__ __launch_bounds__(256) void xnor_gemm_ksplit_kernel(
     const uint32_t* xrow = X + int64_t(xr) * ldx;
 
     for (int q0 = 0; q0 < n_quads; q0 += kSkinnyChunkQuads) {
-        // This lane's quads of the chunk: q, q + 8, ..., q + 56 (zero beyond the row's end).
-        uint4 a[kSkinnyChunkQuads / 8] = {};
+        // This lane's quads of the chunk: q, q + LPR, q + 2*LPR, ... (zero beyond the row's end).
+        uint4 a[STEPS] = {};
         if (n_full > 0) {
 #pragma unroll
-            for (int t = 0; t < kSkinnyChunkQuads / 8; ++t)
-                a[t] = load_quad_unchecked<VEC>(xrow, min(q0 + q + 8 * t, n_full - 1));
+            for (int t = 0; t < STEPS; ++t)
+                a[t] = load_quad_unchecked<VEC>(xrow, min(q0 + q + LPR * t, n_full - 1));
         }
         const bool tail_here = n_full < n_quads && n_full >= q0 && n_full < q0 + kSkinnyChunkQuads;
         uint4 a_tail = make_uint4(0u, 0u, 0u, 0u);
@@ -296,22 +302,22 @@ __global__ __launch_bounds__(256) void xnor_gemm_ksplit_kernel(
             lds_y[idx] = v;
         }
 #pragma unroll
-        for (int t = 0; t < kSkinnyChunkQuads / 8; ++t) {
-            const int qi = q0 + q + 8 * t;
+        for (int t = 0; t < STEPS; ++t) {
+            const int qi = q0 + q + LPR * t;
             a[t] = zero_unless(n_full > 0 && qi < n_full, a[t]);
             if (qi == n_full) a[t] = a_tail;
         }
         __syncthreads();
         // Steps and columns that do not exist are skipped (both bounds are wavefront-uniform).
-        const int steps = (min(kSkinnyChunkQuads, n_quads - q0) + 7) >> 3;
+        const int steps = (min(kSkinnyChunkQuads, n_quads - q0) + LPR - 1) / LPR;
         const int cols = min(kSkinnyCols, ny - y0);
 #pragma unroll
-        for (int t = 0; t < kSkinnyChunkQuads / 8; ++t) {
+        for (int t = 0; t < STEPS; ++t) {
             if (t < steps) {
 #pragma unroll
                 for (int j = 0; j < kSkinnyCols; ++j) {
                     if (j < cols) {
-                        const uint4 b = lds_y[j * kSkinnyChunkQuads + q + 8 * t];
+                        const uint4 b = lds_y[j * kSkinnyChunkQuads + q + LPR * t];
                         acc[j] += __popc(a[t].x ^ b.x) + __popc(a[t].y ^ b.y) + __popc(a[t].z ^ b.z) +
                                   __popc(a[t].w ^ b.w);
                     }
@@ -324,13 +330,14 @@ __global__ __launch_bounds__(256) void xnor_gemm_ksplit_kernel(
         int v = acc[j];
         v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);    // lane ^ 1
         v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);    // lane ^ 2
-        v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);   // other quad of the group
+        v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);   // other quad of the 8 lanes
+        if (LPR == 16) v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, true);   // other 8 lanes of the 16
         acc[j] = v;
     }
-    // Lane q of the group stores columns q and q + 8.
+    // Lane q of the group stores columns q, q + LPR, ... below 16.
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int j = q + 8 * h;
+    for (int h = 0; h < kSkinnyCols / LPR; ++h) {
+        const int j = q + LPR * h;
         int v = 0;
 #pragma unroll
         for (int jj = 0; jj < kSkinnyCols; ++jj) v = (jj == j) ? acc[jj] : v;
@@ -449,14 +456,26 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
             const int64_t sx = a_long ? ldc : 1, sy = a_long ? 1 : ldc;
             const int64_t passes = ceil_div(ny, kSkinnyCols);
             if (passes > 65535) return BNN_ERR_UNSUPPORTED;
-            const dim3 grid(unsigned(ceil_div(nx, 32)), unsigned(passes));
             const bool vec = aligned_to(A, 16) && aligned_to(B, 16) && lda % 4 == 0 && ldb % 4 == 0;
-            if (vec)
-                hipLaunchKernelGGL(xnor_gemm_ksplit_kernel<true>, grid, dim3(256), 0, s, X, ldx, nx, Y, ldy, ny, C,
-                                   sx, sy, k);
-            else
-                hipLaunchKernelGGL(xnor_gemm_ksplit_kernel<false>, grid, dim3(256), 0, s, X, ldx, nx, Y, ldy, ny,
-                                   C, sx, sy, k);
+            // 16 lanes per row (16 rows per workgroup) while that still gives every compute unit few
+            // workgroups: twice the workgroups, half the serial work per lane.
+            if (ceil_div(nx, 16) <= kKsplitWideMaxGroups) {
+                const dim3 grid(unsigned(ceil_div(nx, 16)), unsigned(passes));
+                if (vec)
+                    hipLaunchKernelGGL((xnor_gemm_ksplit_kernel<true, 16>), grid, dim3(256), 0, s, X, ldx, nx, Y, ldy,
+                                       ny, C, sx, sy, k);
+                else
+                    hipLaunchKernelGGL((xnor_gemm_ksplit_kernel<false, 16>), grid, dim3(256), 0, s, X, ldx, nx, Y, ldy,
+                                       ny, C, sx, sy, k);
+            } else {
+                const dim3 grid(unsigned(ceil_div(nx, 32)), unsigned(passes));
+                if (vec)
+                    hipLaunchKernelGGL((xnor_gemm_ksplit_kernel<true, 8>), grid, dim3(256), 0, s, X, ldx, nx, Y, ldy,
+                                       ny, C, sx, sy, k);
+                else
+                    hipLaunchKernelGGL((xnor_gemm_ksplit_kernel<false, 8>), grid, dim3(256), 0, s, X, ldx, nx, Y, ldy,
+                                       ny, C, sx, sy, k);
+            }
             break;
         }
         case KERNEL_MFMA:
