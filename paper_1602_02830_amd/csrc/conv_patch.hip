@@ -1,0 +1,289 @@
+// Binary "same" convolution (stride 1, output size = input size, kh = kw = 2*pad + 1: the 3 x 3,
+// pad 1 layers of the paper's ConvNets, Sec. 3.3) with the input patch of a tile resident in LDS.
+//
+// The GEMM view of the layer is C[pixel][filter] = XnorDotProduct(receptive field, filter) (Alg. 4)
+// with K = kh*kw*Cin.  The receptive fields of neighbouring pixels overlap kh*kw-fold, so instead
+// of staging every K-tile of the (implicit) im2col matrix, a workgroup loads each input pixel its
+// tile needs ONCE: a tile is BM consecutive output pixels = R whole image rows (or R / H whole
+// images), its patch those rows plus a halo of `pad` pixels all around, kept in LDS for the
+// workgroup's life.  Halo cells outside the image hold all-ones words (+1, zero padding through
+// Eq. (1)).  The A operand of an MFMA step for tap (ky, kx) is then a plain LDS read at
+//     slot(pixel) + ky * PW + kx          (PW = W + 2*pad, patch row pitch in pixels)
+// with no per-tap bounds logic, and only the filters (B) stream through LDS K-tile by K-tile.
+// Arithmetic, widening, fix-up and epilogues are those of xnor_gemm_mfma.hip; the row popcounts are
+// sums of per-pixel popcounts over the taps.
+//
+// Patch layout: planes [channel quad cq][half h] of 8-byte slots, slot s = words 4*cq + 2*h, +1 of
+// patch pixel s; lanes of an operand read consecutive pixels, hence consecutive slots.
+// B K-tile layout: planes [quad][half] of 8-byte slots, as in the short-K kernel.
+//
+// Geometry this kernel takes (the launcher checks; everything else goes to the gathering kernels):
+// stride 1, Ho = H, Wo = W, Cin % 128 == 0, BM % W == 0 and, with R = BM / W, H % R == 0 or
+// R % H == 0; filters 16-byte aligned with ldb % 4 == 0; patch within kPatchMaxBytes of LDS.
+#include "bnn_internal.h"
+#include "gemm_staging.h"
+#include "mfma_fp4.h"
+
+namespace bnn {
+
+constexpr int kPatchMaxBytes = 40 * 1024;
+
+struct PatchGeom {
+    int groups;        // images (or row blocks) in a tile
+    int rows;          // output rows per group
+    int prows, pw;     // patch rows per group, patch row pitch (pixels)
+    int slots;         // groups * prows * pw
+    int cqn;           // channel quads per pixel (Cw / 4)
+    int kq;            // quads of K per filter row: kh * kw * cqn
+};
+
+template <int WM, bool FUSED>
+__global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
+    const uint32_t* __restrict__ in, const uint32_t* __restrict__ B, int64_t ldb, int32_t* __restrict__ C,
+    int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n, BnSignArgs bn, ConvArgs cv, PatchGeom pg,
+    int n_images) {
+    constexpr int WN = 2, BM = 64 * WM, BN = 64 * WN;
+    constexpr int PLANE_B = BN + 2;                     // 8-byte slots per B plane (2 pad slots)
+    constexpr int ST_ROWS = 256 / 4;                    // filter rows per staging pass (4 threads per row)
+    constexpr int LOADS_B = BN / ST_ROWS;
+    extern __shared__ uint2 patch[];                    // [cqn][2][slots], then int pix_pop[slots]
+    __shared__ uint2 lds_b[2][8 * PLANE_B];
+    __shared__ __attribute__((aligned(16))) int pop_a[BM];
+    __shared__ __attribute__((aligned(16))) float pop_af[FUSED ? BM : 4];
+    __shared__ __attribute__((aligned(16))) int pop_b[BN];
+    __shared__ __attribute__((aligned(16))) int thr_s[FUSED ? BN : 1];
+    __shared__ uint32_t flip_s[FUSED ? BN / 32 : 1];
+    __shared__ float colfix_s[FUSED ? BN : 1];
+    int* pix_pop = reinterpret_cast<int*>(patch + size_t(2) * pg.cqn * pg.slots);
+
+    int tile_m, tile_n;
+    tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+    const int row0 = tile_m * BM, col0 = tile_n * BN;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int fr = lane & 31, fh = lane >> 5;
+
+    // ---- patch: every slot once ------------------------------------------------------------
+    // The tile's first output pixel is (image b0, row y0, column 0); group g covers image rows
+    // y0 .. y0 + rows - 1 of image b0 (one group) or all rows of image b0 + g (several groups).
+    const int hw = cv.H * cv.W;
+    const int b0 = row0 / hw, y0 = (row0 - b0 * hw) / cv.W;
+    const int group_slots = pg.prows * pg.pw;
+    for (int s = tid; s < pg.slots; s += 256) {
+        const int g = s / group_slots, t = s - g * group_slots;
+        const int py = t / pg.pw, px = t - py * pg.pw;
+        const int b = b0 + g, y = y0 + py - cv.pad, x = px - cv.pad;
+        const bool inside = b < n_images && y >= 0 && y < cv.H && x >= 0 && x < cv.W;
+        const uint32_t pix = inside ? uint32_t((b * cv.H + y) * cv.W + x) : 0u;
+        const uint32_t* p = in + size_t(pix) * uint32_t(cv.Cw);
+        int pop = 0;
+        for (int cq = 0; cq < pg.cqn; ++cq) {
+            uint4 v = *reinterpret_cast<const uint4*>(p + 4 * cq);
+            if (!inside) v = make_uint4(~0u, ~0u, ~0u, ~0u);
+            patch[(2 * cq) * pg.slots + s] = make_uint2(v.x, v.y);
+            patch[(2 * cq + 1) * pg.slots + s] = make_uint2(v.z, v.w);
+            pop += popc4(v);
+        }
+        pix_pop[s] = pop;
+    }
+
+    // ---- B staging: K-tiles of 4 quads, as planes [quad][half] ---------------------------------
+    const int st_q = tid & 3, st_r = tid >> 2;
+    const uint32_t* pb[LOADS_B];
+#pragma unroll
+    for (int l = 0; l < LOADS_B; ++l) pb[l] = B + int64_t(min(col0 + st_r + l * ST_ROWS, N - 1)) * ldb;
+    uint4 rb[LOADS_B];
+    int cnt_b[LOADS_B];
+#pragma unroll
+    for (int l = 0; l < LOADS_B; ++l) cnt_b[l] = 0;
+    const int n_ktiles = (pg.kq + 3) >> 2;
+    auto fetch_b = [&](int kt) {
+        const int quad = min(4 * kt + st_q, pg.kq - 1);           // clamped; zeroed at staging if past the row
+#pragma unroll
+        for (int l = 0; l < LOADS_B; ++l) rb[l] = *reinterpret_cast<const uint4*>(pb[l] + 4 * quad);
+    };
+    auto stage_b = [&](int kt, int buf) {
+        const bool live = 4 * kt + st_q < pg.kq;
+#pragma unroll
+        for (int l = 0; l < LOADS_B; ++l) {
+            const uint4 v = zero_unless(live, rb[l]);
+            cnt_b[l] += popc4(v);
+            lds_b[buf][(2 * st_q) * PLANE_B + st_r + l * ST_ROWS] = make_uint2(v.x, v.y);
+            lds_b[buf][(2 * st_q + 1) * PLANE_B + st_r + l * ST_ROWS] = make_uint2(v.z, v.w);
+        }
+    };
+
+    if (FUSED) {
+        if (tid < BN) thr_s[tid] = col0 + tid < N ? max(-K - 1, min(K + 1, bn.thr[col0 + tid])) : 0;
+        if (tid < BN / 32) flip_s[tid] = col0 + 32 * tid < N ? bn.flip_bits[(col0 >> 5) + tid] : 0u;
+    }
+    fetch_b(0);
+    stage_b(0, 0);
+    __syncthreads();                                    // patch, pixel popcounts and the first B tile are in LDS
+
+    // Patch slot of output pixel r of the tile: group r / (rows * W), row and column inside it.
+    auto slot_of = [&](int r) {
+        const int per_group = pg.rows * cv.W;
+        const int g = r / per_group, t = r - g * per_group;
+        const int yl = t / cv.W, x = t - yl * cv.W;
+        return g * group_slots + yl * pg.pw + x;
+    };
+    // Row popcounts: sum of the pixel popcounts under the kh x kw window (read before the epilogue,
+    // which follows at least one more barrier).
+    if (tid < BM) {
+        const int s0 = slot_of(tid);
+        int sum = 0;
+        for (int ky = 0; ky < cv.kh; ++ky)
+            for (int kx = 0; kx < cv.kw; ++kx) sum += pix_pop[s0 + ky * pg.pw + kx];
+        pop_a[tid] = 2 * sum;
+        if (FUSED) pop_af[tid] = 0.5f * float(sum);
+    }
+
+    // This lane's A operands: pixel wm*32*WM + i*32 + fr, words of lane half fh.
+    const uint2* rd_a[WM];
+#pragma unroll
+    for (int i = 0; i < WM; ++i) rd_a[i] = patch + fh * pg.slots + slot_of(wm * 32 * WM + i * 32 + fr);
+    const int rd_b = fh * PLANE_B + wn * 32 * WN + fr;
+
+    v16f acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    // (tap row, tap column, channel quad) of the next quad of K, stepped with carries.
+    int ky = 0, kx = 0, cq = 0;
+    for (int kt = 0; kt < n_ktiles; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < n_ktiles) fetch_b(kt + 1);
+        const int quads_here = min(4, pg.kq - 4 * kt);
+#pragma unroll
+        for (int qq = 0; qq < 4; ++qq) {
+            if (qq >= quads_here) break;
+            const int a_off = (2 * cq) * pg.slots + ky * pg.pw + kx;
+            uint2 aw[WM], bw[WN];
+#pragma unroll
+            for (int i = 0; i < WM; ++i) aw[i] = rd_a[i][a_off];
+#pragma unroll
+            for (int j = 0; j < WN; ++j) bw[j] = lds_b[buf][(2 * qq) * PLANE_B + rd_b + j * 32];
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                v8i fa[WM], fb[WN];
+#pragma unroll
+                for (int i = 0; i < WM; ++i) fa[i] = widen_fp4_a(s == 0 ? aw[i].x : aw[i].y);
+#pragma unroll
+                for (int j = 0; j < WN; ++j) fb[j] = widen_fp4_b(s == 0 ? bw[j].x : bw[j].y);
+#pragma unroll
+                for (int i = 0; i < WM; ++i)
+#pragma unroll
+                    for (int j = 0; j < WN; ++j) {
+                        // fused: operands swapped, the accumulators hold the transposed blocks (mfma_epilogue_bits)
+                        if (FUSED)
+                            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                                fb[j], fa[i], acc[i][j], 4 /* fp4 */, 4 /* fp4 */, 0, 0, 0, 0);
+                        else
+                            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                                fa[i], fb[j], acc[i][j], 4 /* A: fp4 */, 4 /* B: fp4 */, 0, 0, 0, 0);
+                    }
+            }
+            if (++cq == pg.cqn) {
+                cq = 0;
+                if (++kx == cv.kw) {
+                    kx = 0;
+                    ++ky;
+                }
+            }
+        }
+        // Keep the staging of the next B tile (and the wait for its loads) behind the MFMA steps.
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+#pragma unroll
+            for (int j = 0; j < WN; ++j) asm volatile("" : "+v"(acc[i][j]) : : "memory");
+        if (kt + 1 < n_ktiles) stage_b(kt + 1, buf ^ 1);
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int l = 0; l < LOADS_B; ++l) {
+        int c = cnt_b[l];
+        c += __builtin_amdgcn_update_dpp(0, c, 0xB1, 0xF, 0xF, true);       // lane ^ 1
+        c += __builtin_amdgcn_update_dpp(0, c, 0x4E, 0xF, 0xF, true);       // lane ^ 2
+        if (st_q == 0) {
+            pop_b[st_r + l * ST_ROWS] = 2 * c;
+            if (FUSED) colfix_s[st_r + l * ST_ROWS] = fold_column_term(thr_s[st_r + l * ST_ROWS], K, 2 * c);
+        }
+    }
+    __syncthreads();
+
+    if constexpr (FUSED)
+        mfma_epilogue_bits<WM, WN>(acc, pop_a, pop_af, pop_b, thr_s, flip_s, colfix_s, bn, M, N, K, row0, col0, wm, wn,
+                                   fr, fh);
+    else
+        mfma_epilogue<WM, WN, false, false>(acc, pop_a, pop_af, pop_b, thr_s, flip_s, C, ldc, bn, M, N, K, row0, col0,
+                                            wm, wn, fr, fh);
+}
+
+// Fills the patch geometry for tiles of BM output pixels; false if this convolution does not fit.
+static bool patch_geometry(const ConvArgs& cv, int BM, PatchGeom& pg) {
+    if (cv.stride != 1 || cv.Ho != cv.H || cv.Wo != cv.W) return false;
+    if (cv.kh != 2 * cv.pad + 1 || cv.kw != 2 * cv.pad + 1) return false;
+    if (cv.W > BM || BM % cv.W != 0 || cv.Cw % 4 != 0) return false;
+    const int R = BM / cv.W;
+    if (cv.H % R == 0) {
+        pg.groups = 1;
+        pg.rows = R;
+    } else if (R % cv.H == 0) {
+        pg.groups = R / cv.H;
+        pg.rows = cv.H;
+    } else {
+        return false;
+    }
+    pg.prows = pg.rows + 2 * cv.pad;
+    pg.pw = cv.W + 2 * cv.pad;
+    pg.slots = pg.groups * pg.prows * pg.pw;
+    pg.cqn = cv.Cw / 4;
+    pg.kq = cv.kh * cv.kw * pg.cqn;
+    return int64_t(pg.slots) * (cv.Cw * 4 + 4) <= kPatchMaxBytes;
+}
+
+template <int WM, bool FUSED>
+static int launch_patch(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc, int64_t M,
+                        int64_t N, int64_t K, BnSignArgs bn, ConvArgs cv, PatchGeom pg, void* stream) {
+    const int64_t tiles_m = ceil_div(M, 64 * WM), tiles_n = ceil_div(N, 128);
+    if (tiles_m * tiles_n > kMaxDim) return BNN_ERR_UNSUPPORTED;
+    const size_t lds_bytes = size_t(pg.slots) * (size_t(cv.Cw) * 4 + 4);
+    const int n_images = int(M / (int64_t(cv.H) * cv.W));
+    hipLaunchKernelGGL((conv_patch_mfma_kernel<WM, FUSED>), dim3(unsigned(tiles_m * tiles_n)), dim3(256), lds_bytes,
+                       static_cast<hipStream_t>(stream), in, B, ldb, C, ldc, int(M), int(N), int(K), int(tiles_m),
+                       int(tiles_n), bn, cv, pg, n_images);
+    return check_launch();
+}
+
+// BNN_ERR_UNSUPPORTED if the geometry is not one this kernel takes (the caller then uses the
+// gathering kernels).  Tile choice as for the plain product: 256 pixels x 128 filters when that grid
+// fills the chip's 512 workgroup slots, else 128 x 128.
+template <bool FUSED>
+static int launch_conv_patch_any(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc,
+                                 int64_t M, int64_t N, int64_t K, BnSignArgs bn, ConvArgs cv, void* stream) {
+    if (!aligned_to(B, 16) || ldb % 4 != 0) return BNN_ERR_UNSUPPORTED;
+    PatchGeom pg;
+    const bool big = ceil_div(M, 256) * ceil_div(N, 128) >= 512;
+    if (big && patch_geometry(cv, 256, pg)) return launch_patch<4, FUSED>(in, B, ldb, C, ldc, M, N, K, bn, cv, pg, stream);
+    if (patch_geometry(cv, 128, pg)) return launch_patch<2, FUSED>(in, B, ldb, C, ldc, M, N, K, bn, cv, pg, stream);
+    return BNN_ERR_UNSUPPORTED;
+}
+
+int launch_conv_patch(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc, int64_t M,
+                      int64_t N, int64_t K, ConvArgs cv, void* stream) {
+    return launch_conv_patch_any<false>(in, B, ldb, C, ldc, M, N, K, BnSignArgs{}, cv, stream);
+}
+
+int launch_conv_patch_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
+                            BnSignArgs bn, ConvArgs cv, void* stream) {
+    return launch_conv_patch_any<true>(in, B, ldb, nullptr, 0, M, N, K, bn, cv, stream);
+}
+
+}  // namespace bnn

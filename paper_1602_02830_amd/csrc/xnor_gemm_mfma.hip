@@ -428,8 +428,17 @@ int launch_conv_mfma_shortk(const uint32_t* in, const uint32_t* B, int64_t ldb, 
 int launch_conv_mfma_shortk_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, int64_t M, int64_t N,
                                   int64_t K, BnSignArgs bn, ConvArgs cv, void* stream);
 
+// "Same" convolutions whose tiles are whole image rows or whole images keep their input patch in
+// LDS (conv_patch.hip); its launchers return BNN_ERR_UNSUPPORTED for every other geometry.
+int launch_conv_patch(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc, int64_t M,
+                      int64_t N, int64_t K, ConvArgs cv, void* stream);
+int launch_conv_patch_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
+                            BnSignArgs bn, ConvArgs cv, void* stream);
+
 int launch_conv_mfma(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc, int64_t M,
                      int64_t N, int64_t K, ConvArgs cv, void* stream) {
+    const int st = launch_conv_patch(in, B, ldb, C, ldc, M, N, K, cv, stream);
+    if (st != BNN_ERR_UNSUPPORTED) return st;
     if (conv_shortk_supports(B, ldb, K)) return launch_conv_mfma_shortk(in, B, ldb, C, ldc, M, N, K, cv, stream);
     if (conv_wants_small_tiles(M, N))
         return launch_mfma<2, false, false, true>(in, 0, B, ldb, C, ldc, M, N, K, BnSignArgs{}, cv, stream);
@@ -438,6 +447,8 @@ int launch_conv_mfma(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t
 
 int launch_conv_mfma_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
                            BnSignArgs bn, ConvArgs cv, void* stream) {
+    const int st = launch_conv_patch_fused(in, B, ldb, M, N, K, bn, cv, stream);
+    if (st != BNN_ERR_UNSUPPORTED) return st;
     if (conv_shortk_supports(B, ldb, K)) return launch_conv_mfma_shortk_fused(in, B, ldb, M, N, K, bn, cv, stream);
     if (conv_wants_small_tiles(M, N))
         return launch_mfma<2, true, false, true>(in, 0, B, ldb, nullptr, 0, M, N, K, bn, cv, stream);

@@ -635,6 +635,14 @@ def test_conv_layers_full_batch_sampled_images(fused):
     (3, 9, 9, 256, 64, 2, 2, 1, 0),
     (2, 5, 5, 1152, 32, 1, 1, 1, 0),
     (7, 3, 50, 128, 130, 3, 3, 1, 2),
+    # "same" convolutions whose tiles are whole image rows or whole images: the LDS-patch kernel
+    (3, 16, 16, 256, 130, 3, 3, 1, 1),      # 8 image rows per tile
+    (5, 8, 8, 128, 40, 3, 3, 1, 1),         # 2 images per tile, the last tile holds one
+    (2, 4, 4, 128, 33, 3, 3, 1, 1),         # 8 images per tile, 2 exist
+    (1, 64, 64, 128, 64, 5, 5, 1, 2),       # 5 x 5 window, 2 image rows per tile
+    (2, 32, 32, 128, 70, 1, 1, 1, 0),       # 1 x 1 window, no halo
+    (3, 6, 128, 128, 20, 3, 3, 1, 1),       # one image row per tile
+    (9, 16, 16, 384, 200, 3, 3, 1, 1),      # 3 channel quads per pixel, K-tiles that straddle taps
 ])
 def test_implicit_conv_matches_direct_convolution(shape):
     """Implicit-GEMM conv (no im2col matrix) == the oracle's direct convolution; fused form ==
