@@ -207,8 +207,9 @@ int bnn_conv_im2col_pack(const uint32_t *in, int64_t B, int64_t H, int64_t W,
 
 /*
  * A whole binary convolution layer without the intermediate matrix (implicit GEMM): the
- * receptive fields described under bnn_conv_im2col_pack are gathered by the product's tile
- * loader straight from the packed NHWC input.
+ * receptive fields described under bnn_conv_im2col_pack are taken straight from the packed NHWC
+ * input - from a patch of it held on chip for same-size stride-1 convolutions, gathered by the
+ * product's tile loader otherwise.
  *   S[(b*Ho + oy)*Wo + ox][co] = sum_{ky,kx,ci} in(b, oy*stride+ky-pad, ox*stride+kx-pad, ci) * Wt[co][ky][kx][ci]
  *   in   packed NHWC [B][H][W][Cin/32] uint32, out-of-image taps read as +1
  *   Wb   packed filters [Cout][ldw], row co = Wt[co] flattened as (ky, kx, ci), ldw >= kh*kw*Cin/32

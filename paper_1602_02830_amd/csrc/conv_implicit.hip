@@ -3,7 +3,9 @@
 // bnn_conv_xnor / bnn_conv_bn_sign_pack: a kh x kw binary convolution (3 x 3 in the paper's
 // nets, Sec. 3.3) as the XnorDotProduct of Alg. 4 over receptive fields that the GEMM's tile
 // loader gathers straight from the packed NHWC input (taps outside the image are +1: zero
-// padding through Eq. (1)).  The kernel is the conv mode of the matrix-engine GEMM.
+// padding through Eq. (1)).  The kernels: the LDS-patch kernel (conv_patch.hip) for same-size
+// convolutions whose tiles are whole image rows or images, else the conv modes of the matrix-engine
+// GEMMs (xnor_gemm_mfma.hip, xnor_gemm_mfma_shortk.hip); launch_conv_mfma chooses.
 //
 // bnn_maxpool_bits: the paper's ConvNets pool the integer pre-activations before BatchNorm and
 // Sign.  Sign(BatchNorm(.)) is monotone per channel - non-decreasing where the folded flip bit
