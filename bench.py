@@ -368,6 +368,24 @@ def main():
                 f"{B / ms_imp * 1e3:,.0f} images/s); im2col + fused GEMM {ms_low:.3f} ms (im2col {ms_i:.3f}); equal: {same}")
             del imp, low, xb
         extras["conv_layers_batch256"] = conv
+
+        # The binary body of the paper's CIFAR-10 ConvNet (Sec. 2.2): five 3x3 convolutions with three
+        # poolings and three dense layers, batch 256, from the first layer's output bits to the scores.
+        xn, convs, fcs, fc_bns = synth.config_convnet()
+        Bn = xn.shape[0]
+        net = bnn.BinaryConvNet(
+            [(torch.from_numpy(Wt.astype(np.float32)).to(dev), bn, pooled)
+             for (Wt, bn), (_ci, _co, _hw, pooled) in zip(convs, synth.CONVNET_CONVS)],
+            [torch.from_numpy(np.ascontiguousarray(Bm.T).astype(np.float32)).to(dev) for Bm in fcs], fc_bns, eps, Bn, 32, 32)
+        xnb = bnn.pack_sign(torch.from_numpy(xn.reshape(-1, 128).astype(np.float32)).to(dev)).view(Bn, 32, 32, 4)
+        ms_net, _ = time_launches(lambda: net.forward(xnb), 50)
+        ops_net = sum(2.0 * Bn * hw * hw * 9 * ci * co for ci, co, hw, _p in synth.CONVNET_CONVS) + \
+            sum(2.0 * Bn * synth.CONVNET_FCS[l] * synth.CONVNET_FCS[l + 1] for l in range(3))
+        extras["convnet_body_batch256"] = {"ms": ms_net, "images_per_s": Bn / ms_net * 1e3,
+                                           "binary_tops": ops_net / ms_net / 1e9, "launches": 11}
+        log(f"ConvNet body (128C3-MP2-256C3-256C3-MP2-512C3-512C3-MP2-1024FC-1024FC-10) batch {Bn}: {ms_net:.3f} ms "
+            f"({Bn / ms_net * 1e3:,.0f} images/s, {ops_net / ms_net / 1e9:.0f} TOP/s)")
+        del net, xnb
         result["extras"] = extras
 
     print(json.dumps(result), flush=True)

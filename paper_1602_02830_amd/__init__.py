@@ -35,4 +35,4 @@ from .binding import (  # noqa: F401
     KERNEL_MFMA128,
     KERNEL_MFMA_SHORTK,
 )
-from .network import BinaryMLP, BinaryConvLayer  # noqa: F401
+from .network import BinaryMLP, BinaryConvLayer, BinaryConvNet  # noqa: F401

@@ -172,3 +172,54 @@ class BinaryConvLayer:
             B.maxpool_bits(out, self.Cout, self.flip, self.pool, self.pool, self.pool, out=self.pooled)
             return self.pooled
         return out
+
+
+class BinaryConvNet:
+    """The binary body of the paper's CIFAR-10 / SVHN ConvNet (Sec. 2.2, 2.3), from the first layer's
+    output bits to the class scores: 3x3 binary convolutions (fused with Sign(BatchNorm), max pooling on
+    the output bits where the architecture pools), then binary dense layers.  Every layer's packed NHWC
+    output is the next layer's input as it stands; the pooled bits of the last convolution, read row by
+    row, are the (y, x, channel)-ordered input of the first dense layer.
+
+    convs: list of (float32 device filters [Cout][3][3][Cin], bn, pooled) per convolution;
+    fcs:   list of float32 device weights [N][K]; fc_bns: bn per hidden dense layer.
+    """
+
+    def __init__(self, convs, fcs, fc_bns, eps: float, batch: int, H: int, W: int):
+        assert len(fc_bns) == len(fcs) - 1
+        self.batch = batch
+        self.convs = []
+        for w, bn, pooled in convs:
+            layer = BinaryConvLayer(w, bn, eps, batch, H, W, fused=True, implicit=True, pool=2 if pooled else 0)
+            self.convs.append(layer)
+            if pooled:
+                H, W = layer.Hp, layer.Wp
+        dev = fcs[0].device
+        self.K = [int(w.shape[1]) for w in fcs]
+        self.N = [int(w.shape[0]) for w in fcs]
+        if self.K[0] != H * W * self.convs[-1].Cout:
+            raise ValueError("first dense layer does not match the last feature map")
+        self.w_bits, self.thr, self.flip = [], [], []
+        for w in fcs:
+            buf = _packed_buffer(w.shape[0], w.shape[1], dev)
+            B.pack_sign(w, out=buf)
+            self.w_bits.append(buf)
+        for l, bn in enumerate(fc_bns):
+            thr, flip = B.bn_fold(*bn, eps, self.K[l])
+            self.thr.append(torch.from_numpy(thr).to(dev))
+            self.flip.append(torch.from_numpy(flip.view(np.int32)).to(dev))
+        self.a_bits = [_packed_buffer(batch, n, dev) for n in self.N[:-1]]
+        self.scores = torch.empty((batch, self.N[-1]), dtype=torch.int32, device=dev)
+
+    def forward(self, x_bits: torch.Tensor) -> torch.Tensor:
+        """x_bits: packed NHWC int32 [B][H][W][Cin/32].  Returns the int32 scores [B][classes]."""
+        a = x_bits
+        for layer in self.convs:
+            a = layer.forward(a)
+        a = a.reshape(self.batch, -1)                    # (y, x, channel words) of one image = one packed row
+        for l in range(len(self.w_bits) - 1):
+            B.xnor_gemm_bn_sign_pack(a, self.w_bits[l], self.K[l], self.thr[l], self.flip[l], out=self.a_bits[l])
+            a = self.a_bits[l]
+        B.xnor_gemm(a, self.w_bits[-1], self.K[-1], out=self.scores)
+        return self.scores
+

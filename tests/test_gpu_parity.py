@@ -727,6 +727,56 @@ def test_conv_pool_layers_full_batch_sampled_images():
             assert (out[img] == oracle.pack_bits(a_want.reshape(-1, C))).all()
 
 
+def _convnet_oracle(x, convs, fcs, fc_bns):
+    """The ConvNet body in the paper's order, from the oracle's layer functions: per convolution
+    conv -> (max pool of the pre-activations) -> BatchNorm -> Sign; then the dense layers."""
+    acts = []
+    a = x
+    for (Wt, bn), (_cin, _cout, _hw, pooled) in zip(convs, synth.CONVNET_CONVS):
+        a = oracle.conv_pool_layer(a, Wt, bn, pool=2, eps=EPS)[1] if pooled else oracle.conv_layer(a, Wt, bn, eps=EPS)[1]
+        acts.append(a)
+    v = a.reshape(a.shape[0], -1)
+    for Bm, bn in zip(fcs[:-1], fc_bns):
+        v = oracle.dense_layer(v, Bm, bn, eps=EPS)[1]
+        acts.append(v)
+    return acts, oracle.matmul_pm1(v, fcs[-1])
+
+
+def _convnet_on_gpu(x, convs, fcs, fc_bns):
+    B = x.shape[0]
+    dev_convs = [(torch.from_numpy(Wt.astype(np.float32)).to(DEV), bn, pooled)
+                 for (Wt, bn), (_ci, _co, _hw, pooled) in zip(convs, synth.CONVNET_CONVS)]
+    dev_fcs = [torch.from_numpy(np.ascontiguousarray(Bm.T).astype(np.float32)).to(DEV) for Bm in fcs]
+    net = bnn.BinaryConvNet(dev_convs, dev_fcs, fc_bns, EPS, B, 32, 32)
+    xb = words_to_dev(_pack_nhwc(x).reshape(-1, 4)).view(B, 32, 32, 4)
+    scores = net.forward(xb).cpu().numpy()
+    return net, scores
+
+
+def test_convnet_body_every_intermediate_small_batch():
+    """128C3-MP2-256C3-256C3-MP2-512C3-512C3-MP2-1024FC-1024FC-10 on 3 images: every layer's packed output
+    and the scores against the oracle's chain (pooling of pre-activations before BatchNorm + Sign)."""
+    x, convs, fcs, fc_bns = synth.config_convnet(batch=3, adversarial=True)
+    acts, scores_want = _convnet_oracle(x, convs, fcs, fc_bns)
+    net, scores = _convnet_on_gpu(x, convs, fcs, fc_bns)
+    for l, layer in enumerate(net.convs):
+        got = layer.pooled if layer.pool else layer.out_bits
+        C = acts[l].shape[-1]
+        assert (words_to_host(got.reshape(-1, C // 32)) == oracle.pack_bits(acts[l].reshape(-1, C))).all(), f"conv {l}"
+    for l, a in enumerate(net.a_bits):
+        assert (words_to_host(a) == oracle.pack_bits(acts[len(net.convs) + l])).all(), f"dense {l}"
+    assert (scores == scores_want).all()
+
+
+def test_convnet_body_full_batch_sampled_images():
+    """Batch 256 as benchmarked; images are independent, so the oracle runs the chain on a sample."""
+    x, convs, fcs, fc_bns = synth.config_convnet()
+    _net, scores = _convnet_on_gpu(x, convs, fcs, fc_bns)
+    for img in (0, 131, 255):
+        _acts, want = _convnet_oracle(x[img:img + 1], convs, fcs, fc_bns)
+        assert (scores[img] == want[0]).all(), f"image {img}"
+
+
 # ------------------------------------------------------------------ MLP chain
 
 def _mlp_on_gpu(x, weights, bns, batch):

@@ -125,6 +125,27 @@ def config_conv(layer: int, batch: int = CONV_BATCH, channels: int | None = None
     return x, Wt, bn
 
 
+# The binary body of the paper's CIFAR-10 / SVHN ConvNet (Sec. 2.2, 2.3): after the first
+# convolution (which sees the real-valued image) come 128C3 - MP2 - 256C3 - 256C3 - MP2 - 512C3 -
+# 512C3 - MP2 - 1024FC - 1024FC - 10, all on +-1 activations.  (Cin, Cout, H = W, pooled)
+CONVNET_CONVS = ((128, 128, 32, True), (128, 256, 16, False), (256, 256, 16, True),
+                 (256, 512, 8, False), (512, 512, 8, True))
+CONVNET_FCS = (4 * 4 * 512, 1024, 1024, 10)
+
+
+def config_convnet(batch: int = CONV_BATCH, adversarial: bool = False):
+    """x[B][32][32][128] +-1 (the first layer's output bits), conv filters Wt_l[Cout][3][3][Cin] with
+    BN over Cout, dense weights Bm_l[K][N] with BN for the two hidden dense layers."""
+    x = pm1(rng_for(5, 0), (batch, 32, 32, 128))
+    convs = []
+    for l, (cin, cout, _hw, _pool) in enumerate(CONVNET_CONVS):
+        Wt = pm1(rng_for(5, 10 + 2 * l), (cout, 3, 3, cin))
+        convs.append((Wt, bn_params(rng_for(5, 11 + 2 * l), cout, 9 * cin, adversarial)))
+    fcs = [pm1(rng_for(5, 40 + l), (CONVNET_FCS[l], CONVNET_FCS[l + 1])) for l in range(3)]
+    fc_bns = [bn_params(rng_for(5, 50 + l), CONVNET_FCS[l + 1], CONVNET_FCS[l], adversarial) for l in range(2)]
+    return x, convs, fcs, fc_bns
+
+
 # -- config 4: large square GEMM --------------------------------------------
 
 def config_gemm_square(n: int = GEMM_LARGE):
