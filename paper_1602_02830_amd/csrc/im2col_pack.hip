@@ -7,8 +7,11 @@
 //
 // HBM-bound on the write side: (kh*kw*Cin)/8 bytes written per output pixel;
 // reads mostly hit cache (each input pixel is used kh*kw times).
-//   words   - Cin % 32 == 0: every output word is a copy of one input word or
-//             all-ones; with Cin % 128 == 0 the copy is 16 bytes per thread.
+//   quads   - Cin % 128 == 0 (the paper's layers): 16-byte copies.  A thread keeps one 16-byte unit
+//             of the receptive field (its tap and channel quad, fixed for the kernel's life) and
+//             walks over output pixels with carried (row, column) coordinates, so the copy loop
+//             has no division; the threads of a pass write whole consecutive output rows.
+//   words   - Cin % 32 == 0: every output word is a copy of one input word or all-ones.
 //   bits    - any Cin: an output word gathers bit runs from up to 32 taps.
 #include "bnn_internal.h"
 
@@ -52,6 +55,43 @@ __global__ __launch_bounds__(256) void im2col_words_kernel(const uint32_t* __res
             *reinterpret_cast<uint4*>(dst) = v;
         } else {
             *dst = inside ? *src : ~0u;
+        }
+    }
+}
+
+// Cin % 128 == 0, 16-byte aligned buffers, at most 256 units of 16 bytes per receptive field.
+// Grid: (chunks of an image's output pixels, images).  P = 256 / units pixels per pass.
+__global__ __launch_bounds__(256) void im2col_quads_kernel(const uint32_t* __restrict__ in, ConvGeom g,
+                                                           uint32_t* __restrict__ out, int64_t ld_out,
+                                                           int units, int pixels_per_block) {
+    const int P = 256 / units;
+    const int p = threadIdx.x / units, r = threadIdx.x - p * units;
+    if (p >= P) return;                                  // 256 % units leftover threads
+    const int units_per_tap = g.Cw / 4;
+    const int tap = r / units_per_tap, cu = r - tap * units_per_tap;
+    const int ky = tap / g.kw, kx = tap - ky * g.kw;
+    const int n_pix = g.Ho * g.Wo;
+    const int q_end = min((int(blockIdx.x) + 1) * pixels_per_block, n_pix);
+    int q = int(blockIdx.x) * pixels_per_block + p;
+    int oy = q / g.Wo, ox = q - oy * g.Wo;
+    const int step_y = P / g.Wo, step_x = P - step_y * g.Wo;
+    const int64_t b = blockIdx.y;
+    const uint32_t* img = in + b * g.H * g.W * g.Cw + cu * 4;
+    uint32_t* dst = out + (b * n_pix + q) * ld_out + tap * g.Cw + cu * 4;
+    const int64_t dst_step = int64_t(P) * ld_out;
+    for (; q < q_end; q += P) {
+        const int y = oy * g.stride + ky - g.pad;
+        const int x = ox * g.stride + kx - g.pad;
+        uint4 v = make_uint4(~0u, ~0u, ~0u, ~0u);
+        if (y >= 0 && y < g.H && x >= 0 && x < g.W)
+            v = *reinterpret_cast<const uint4*>(img + (int64_t(y) * g.W + x) * g.Cw);
+        *reinterpret_cast<uint4*>(dst) = v;
+        dst += dst_step;
+        ox += step_x;
+        oy += step_y;
+        if (ox >= g.Wo) {
+            ox -= g.Wo;
+            ++oy;
         }
     }
 }
@@ -130,7 +170,16 @@ extern "C" int bnn_conv_im2col_pack(const uint32_t* in, int64_t B, int64_t H, in
     };
     if (Cin % 32 == 0) {
         const bool v4 = Cin % 128 == 0 && aligned_to(in, 16) && aligned_to(out, 16) && ld_out % 4 == 0;
-        if (v4) {
+        const int64_t row_units = kwords / 4, n_pix = Ho * Wo;
+        if (v4 && row_units <= 256 && n_pix <= kMaxDim - 4096 && B <= 65535) {
+            // Pixels per workgroup: a few passes each, and enough workgroups to fill the chip.
+            const int P = int(256 / row_units);
+            int64_t per_block = int64_t(P) * 8;
+            while (per_block > P && ceil_div(n_pix, per_block) * B < 2048) per_block -= P;
+            const dim3 grid(unsigned(ceil_div(n_pix, per_block)), unsigned(B));
+            hipLaunchKernelGGL(im2col_quads_kernel, grid, dim3(256), 0, s, in, g, out, ld_out, int(row_units),
+                               int(per_block));
+        } else if (v4) {
             const int64_t units = g.M * (kwords / 4);
             hipLaunchKernelGGL(im2col_words_kernel<4>, dim3(blocks_for(units)), dim3(256), 0, s, in, g, out,
                                ld_out, units);
