@@ -382,7 +382,7 @@ def main():
         ops_net = sum(2.0 * Bn * hw * hw * 9 * ci * co for ci, co, hw, _p in synth.CONVNET_CONVS) + \
             sum(2.0 * Bn * synth.CONVNET_FCS[l] * synth.CONVNET_FCS[l + 1] for l in range(3))
         extras["convnet_body_batch256"] = {"ms": ms_net, "images_per_s": Bn / ms_net * 1e3,
-                                           "binary_tops": ops_net / ms_net / 1e9, "launches": 11}
+                                           "binary_tops": ops_net / ms_net / 1e9, "launches": 8}
         log(f"ConvNet body (128C3-MP2-256C3-256C3-MP2-512C3-512C3-MP2-1024FC-1024FC-10) batch {Bn}: {ms_net:.3f} ms "
             f"({Bn / ms_net * 1e3:,.0f} images/s, {ops_net / ms_net / 1e9:.0f} TOP/s)")
         del net, xnb

@@ -229,6 +229,22 @@ int bnn_conv_bn_sign_pack(const uint32_t *in, int64_t B, int64_t H, int64_t W, i
                           int64_t ld_out, void *stream);
 
 /*
+ * The pooled layer of the paper's ConvNets in one launch: convolution, pool x pool max pooling
+ * (stride pool) of the pre-activations, BatchNorm, Sign (Sec. 2.2, 2.3; Alg. 4 for the last two).
+ *   out [B*(Ho/pool)*(Wo/pool)][ld_out] packed bits, the packed NHWC input of the next layer;
+ *   every other argument as in bnn_conv_bn_sign_pack.
+ * Bit-identical to bnn_conv_bn_sign_pack followed by bnn_maxpool_bits (see there for why pooling
+ * the output bits equals pooling the pre-activations).  Only pool = 2 on same-size stride-1
+ * convolutions whose tiles hold whole, even numbers of image rows is taken (even H and W; W a power
+ * of two up to 16, or 32 or 64; the requirements of bnn_conv_bn_sign_pack); anything else returns
+ * BNN_ERR_UNSUPPORTED before any launch: use the two calls then.
+ */
+int bnn_conv_pool_bn_sign_pack(const uint32_t *in, int64_t B, int64_t H, int64_t W, int64_t Cin,
+                               const uint32_t *Wb, int64_t ldw, int64_t Cout, int kh, int kw, int stride,
+                               int pad, int pool, const int32_t *thr, const uint32_t *flip_bits,
+                               uint32_t *out, int64_t ld_out, void *stream);
+
+/*
  * Max pooling for binarized layers.  The paper's ConvNets pool the pre-activations between a
  * convolution and its BatchNorm + Sign; since Sign(BatchNorm(.)) is monotone per channel, the bit
  * of the pooled pre-activation is the OR of the window's bits where the channel's folded flip

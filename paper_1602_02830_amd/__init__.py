@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     conv_im2col_pack,
     conv_xnor,
     conv_bn_sign_pack,
+    conv_pool_bn_sign_pack,
     maxpool_bits,
     pack_bitplanes,
     bitplane_gemm,

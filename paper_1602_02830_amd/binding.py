@@ -43,6 +43,8 @@ _SIGNATURES = {
     "bnn_conv_xnor": (_int, [_ptr, _i64, _i64, _i64, _i64, _ptr, _i64, _i64, _int, _int, _int, _int, _ptr, _i64, _ptr]),
     "bnn_conv_bn_sign_pack": (_int, [_ptr, _i64, _i64, _i64, _i64, _ptr, _i64, _i64, _int, _int, _int, _int, _ptr,
                                      _ptr, _ptr, _i64, _ptr]),
+    "bnn_conv_pool_bn_sign_pack": (_int, [_ptr, _i64, _i64, _i64, _i64, _ptr, _i64, _i64, _int, _int, _int, _int, _int,
+                                          _ptr, _ptr, _ptr, _i64, _ptr]),
     "bnn_maxpool_bits": (_int, [_ptr, _i64, _i64, _i64, _i64, _int, _int, _int, _ptr, _ptr, _ptr]),
     "bnn_gemm_i8_mfma": (_int, [_ptr, _i64, _ptr, _i64, _ptr, _i64, _i64, _i64, _i64, _ptr]),
     "bnn_unpack_i8": (_int, [_ptr, _i64, _i64, _i64, _ptr, _i64, _ptr]),
@@ -351,6 +353,37 @@ def conv_bn_sign_pack(x_bits: torch.Tensor, Cin: int, w_bits: torch.Tensor, thr:
            lib.bnn_conv_bn_sign_pack(x_bits.data_ptr(), B, H, W, Cin, w_bits.data_ptr(), _ld(w_bits), Cout, kh, kw,
                                      stride, pad, thr.data_ptr(), flip_bits.data_ptr(), out.data_ptr(), _ld(out),
                                      _stream(out)))
+    return out
+
+
+def conv_pool_bn_sign_pack(x_bits: torch.Tensor, Cin: int, w_bits: torch.Tensor, thr: torch.Tensor,
+                           flip_bits: torch.Tensor, kh: int = 3, kw: int = 3, stride: int = 1, pad: int = 1,
+                           pool: int = 2, out: torch.Tensor | None = None) -> torch.Tensor:
+    """bnn_conv_pool_bn_sign_pack: binary conv + max pooling + Sign(BatchNorm) in one launch ->
+    packed bits [B*(Ho/pool)*(Wo/pool)][ceil(Cout/32)].  Raises BnnError with status 3 (unsupported)
+    for geometries the fused kernel does not take."""
+    lib = load_library()
+    _check_nhwc_bits(x_bits, Cin)
+    _dev(w_bits, torch.int32, "w_bits")
+    B, H, W, _ = x_bits.shape
+    Cout = w_bits.shape[0]
+    Ho, Wo = (H + 2 * pad - kh) // stride + 1, (W + 2 * pad - kw) // stride + 1
+    nw = words_per_row(Cout)
+    if thr.dtype != torch.int32 or flip_bits.dtype != torch.int32 or not thr.is_cuda or not flip_bits.is_cuda:
+        raise ValueError("thr and flip_bits must be int32 device tensors")
+    if thr.numel() != Cout or flip_bits.numel() != nw or not thr.is_contiguous() or not flip_bits.is_contiguous():
+        raise ValueError("thr must be [Cout] and flip_bits [ceil(Cout/32)], contiguous")
+    if pool < 1:
+        raise ValueError("pool must be positive")
+    if out is None:
+        out = torch.empty((B * (Ho // pool) * (Wo // pool), nw), dtype=torch.int32, device=x_bits.device)
+    _dev(out, torch.int32, "out")
+    if out.shape[0] != B * (Ho // pool) * (Wo // pool) or out.shape[1] != nw:
+        raise ValueError("out must be [B*(Ho/pool)*(Wo/pool)][ceil(Cout/32)]")
+    _check("bnn_conv_pool_bn_sign_pack",
+           lib.bnn_conv_pool_bn_sign_pack(x_bits.data_ptr(), B, H, W, Cin, w_bits.data_ptr(), _ld(w_bits), Cout, kh,
+                                          kw, stride, pad, pool, thr.data_ptr(), flip_bits.data_ptr(),
+                                          out.data_ptr(), _ld(out), _stream(out)))
     return out
 
 

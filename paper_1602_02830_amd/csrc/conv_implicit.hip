@@ -7,6 +7,9 @@
 // convolutions whose tiles are whole image rows or images, else the conv modes of the matrix-engine
 // GEMMs (xnor_gemm_mfma.hip, xnor_gemm_mfma_shortk.hip); launch_conv_mfma chooses.
 //
+// bnn_conv_pool_bn_sign_pack: the same layer with the paper's 2 x 2 max pooling between the
+// convolution and BatchNorm + Sign, in one launch (LDS-patch kernel only).
+//
 // bnn_maxpool_bits: the paper's ConvNets pool the integer pre-activations before BatchNorm and
 // Sign.  Sign(BatchNorm(.)) is monotone per channel - non-decreasing where the folded flip bit
 // is 0, non-increasing where it is 1 - so Sign(BN(max over the window)) is the OR of the
@@ -22,6 +25,8 @@ int launch_conv_mfma(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t
                      int64_t N, int64_t K, ConvArgs cv, void* stream);
 int launch_conv_mfma_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
                            BnSignArgs bn, ConvArgs cv, void* stream);
+int launch_conv_patch_pool_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
+                                 BnSignArgs bn, ConvArgs cv, void* stream);
 
 // Validates a convolution and fills the geometry.  M = B*Ho*Wo, K = kh*kw*Cin.
 static int conv_geometry(const uint32_t* in, int64_t B, int64_t H, int64_t W, int64_t Cin, const uint32_t* Wb,
@@ -104,6 +109,23 @@ extern "C" int bnn_conv_bn_sign_pack(const uint32_t* in, int64_t B, int64_t H, i
     if (!thr || !flip_bits || !out) return BNN_ERR_INVALID_ARG;
     if (!aligned_to(thr, 4) || !aligned_to(flip_bits, 4) || !aligned_to(out, 4)) return BNN_ERR_ALIGNMENT;
     return launch_conv_mfma_fused(in, Wb, ldw, M, Cout, K, BnSignArgs{thr, flip_bits, out, ld_out}, cv, stream);
+}
+
+extern "C" int bnn_conv_pool_bn_sign_pack(const uint32_t* in, int64_t B, int64_t H, int64_t W, int64_t Cin,
+                                          const uint32_t* Wb, int64_t ldw, int64_t Cout, int kh, int kw, int stride,
+                                          int pad, int pool, const int32_t* thr, const uint32_t* flip_bits,
+                                          uint32_t* out, int64_t ld_out, void* stream) {
+    using namespace bnn;
+    ConvArgs cv;
+    int64_t M, K;
+    const int st = conv_geometry(in, B, H, W, Cin, Wb, ldw, Cout, kh, kw, stride, pad, cv, M, K);
+    if (st != BNN_OK) return st;
+    if (pool < 1 || ld_out < ceil_div(Cout, 32)) return BNN_ERR_INVALID_ARG;
+    if (pool != 2) return BNN_ERR_UNSUPPORTED;
+    if (M == 0 || Cout == 0) return BNN_OK;
+    if (!thr || !flip_bits || !out) return BNN_ERR_INVALID_ARG;
+    if (!aligned_to(thr, 4) || !aligned_to(flip_bits, 4) || !aligned_to(out, 4)) return BNN_ERR_ALIGNMENT;
+    return launch_conv_patch_pool_fused(in, Wb, ldw, M, Cout, K, BnSignArgs{thr, flip_bits, out, ld_out}, cv, stream);
 }
 
 extern "C" int bnn_maxpool_bits(const uint32_t* in, int64_t B, int64_t H, int64_t W, int64_t C, int ph, int pw,

@@ -17,6 +17,13 @@
 // patch pixel s; lanes of an operand read consecutive pixels, hence consecutive slots.
 // B K-tile layout: planes [quad][half] of 8-byte slots, as in the short-K kernel.
 //
+// Pooled layers (POOL = true): the paper's ConvNets max-pool the pre-activations 2 x 2 between a
+// convolution and its BatchNorm + Sign.  Sign(BatchNorm(.)) is monotone per channel, so the pooled
+// output bit is the OR of the window's four output bits where the folded flip bit is 0 and their
+// AND where it is 1.  A tile holds whole (even numbers of) image rows, so every window lies inside
+// one wavefront's rows: the horizontal neighbour is the next lane, the vertical one W lanes away
+// (W < 32) or in the accumulator block W / 32 further on, and only the pooled words are stored.
+//
 // Geometry this kernel takes (the launcher checks; everything else goes to the gathering kernels):
 // stride 1, Ho = H, Wo = W, Cin % 128 == 0, BM % W == 0 and, with R = BM / W, H % R == 0 or
 // R % H == 0; filters 16-byte aligned with ldb % 4 == 0; patch within kPatchMaxBytes of LDS.
@@ -37,7 +44,7 @@ struct PatchGeom {
     int kq;            // quads of K per filter row: kh * kw * cqn
 };
 
-template <int WM, bool FUSED>
+template <int WM, bool FUSED, bool POOL>
 __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
     const uint32_t* __restrict__ in, const uint32_t* __restrict__ B, int64_t ldb, int32_t* __restrict__ C,
     int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n, BnSignArgs bn, ConvArgs cv, PatchGeom pg,
@@ -218,7 +225,46 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
     }
     __syncthreads();
 
-    if constexpr (FUSED)
+    if constexpr (POOL) {
+        static_assert(FUSED, "pooling acts on output bits");
+        uint32_t words[WM];
+        mfma_output_words<WM, WN>(acc, pop_a, pop_af, pop_b, thr_s, flip_s, colfix_s, N, K, col0, wm, wn, fr, fh, words);
+        const uint32_t flip_word = flip_s[wn * WN + fh];
+        const int64_t nw = (int64_t(N) + 31) >> 5;
+        const int64_t w = ((int64_t(col0) + wn * 32 * WN) >> 5) + fh;
+        uint32_t any[WM], all[WM];
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+            // horizontal neighbour (x ^ 1): the next lane; vertical one for W < 32: W lanes away
+            const uint32_t h = uint32_t(__shfl_xor(int(words[i]), 1));
+            any[i] = words[i] | h;
+            all[i] = words[i] & h;
+            if (cv.W < 32) {
+                any[i] |= uint32_t(__shfl_xor(int(any[i]), cv.W));
+                all[i] &= uint32_t(__shfl_xor(int(all[i]), cv.W));
+            }
+        }
+        const int blocks_per_row = cv.W >> 5;           // W >= 32: image row y and y + 1 are blocks i and i + W / 32
+        const int hp = cv.H >> 1, wp = cv.W >> 1;
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+            uint32_t a = any[i], l = all[i];
+            if (cv.W >= 32) {
+#pragma unroll
+                for (int i2 = 0; i2 < WM; ++i2)
+                    if (i2 == i + blocks_per_row) {
+                        a |= any[i2];
+                        l &= all[i2];
+                    }
+            }
+            const int m = row0 + wm * 32 * WM + i * 32 + fr;
+            const int b = m / hw, rem = m - b * hw;
+            const int y = rem / cv.W, x = rem - y * cv.W;
+            const uint32_t pooled = (a & ~flip_word) | (l & flip_word);
+            if (m < M && w < nw && !(y & 1) && !(x & 1))
+                bn.out[(int64_t(b) * hp + (y >> 1)) * wp * bn.ld_out + int64_t(x >> 1) * bn.ld_out + w] = pooled;
+        }
+    } else if constexpr (FUSED)
         mfma_epilogue_bits<WM, WN>(acc, pop_a, pop_af, pop_b, thr_s, flip_s, colfix_s, bn, M, N, K, row0, col0, wm, wn,
                                    fr, fh);
     else
@@ -249,14 +295,14 @@ static bool patch_geometry(const ConvArgs& cv, int BM, PatchGeom& pg) {
     return int64_t(pg.slots) * (cv.Cw * 4 + 4) <= kPatchMaxBytes;
 }
 
-template <int WM, bool FUSED>
+template <int WM, bool FUSED, bool POOL>
 static int launch_patch(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc, int64_t M,
                         int64_t N, int64_t K, BnSignArgs bn, ConvArgs cv, PatchGeom pg, void* stream) {
     const int64_t tiles_m = ceil_div(M, 64 * WM), tiles_n = ceil_div(N, 128);
     if (tiles_m * tiles_n > kMaxDim) return BNN_ERR_UNSUPPORTED;
     const size_t lds_bytes = size_t(pg.slots) * (size_t(cv.Cw) * 4 + 4);
     const int n_images = int(M / (int64_t(cv.H) * cv.W));
-    hipLaunchKernelGGL((conv_patch_mfma_kernel<WM, FUSED>), dim3(unsigned(tiles_m * tiles_n)), dim3(256), lds_bytes,
+    hipLaunchKernelGGL((conv_patch_mfma_kernel<WM, FUSED, POOL>), dim3(unsigned(tiles_m * tiles_n)), dim3(256), lds_bytes,
                        static_cast<hipStream_t>(stream), in, B, ldb, C, ldc, int(M), int(N), int(K), int(tiles_m),
                        int(tiles_n), bn, cv, pg, n_images);
     return check_launch();
@@ -271,9 +317,18 @@ static int launch_conv_patch_any(const uint32_t* in, const uint32_t* B, int64_t 
     if (!aligned_to(B, 16) || ldb % 4 != 0) return BNN_ERR_UNSUPPORTED;
     PatchGeom pg;
     const bool big = ceil_div(M, 256) * ceil_div(N, 128) >= 512;
-    if (big && patch_geometry(cv, 256, pg)) return launch_patch<4, FUSED>(in, B, ldb, C, ldc, M, N, K, bn, cv, pg, stream);
-    if (patch_geometry(cv, 128, pg)) return launch_patch<2, FUSED>(in, B, ldb, C, ldc, M, N, K, bn, cv, pg, stream);
+    if (big && patch_geometry(cv, 256, pg))
+        return launch_patch<4, FUSED, false>(in, B, ldb, C, ldc, M, N, K, bn, cv, pg, stream);
+    if (patch_geometry(cv, 128, pg)) return launch_patch<2, FUSED, false>(in, B, ldb, C, ldc, M, N, K, bn, cv, pg, stream);
     return BNN_ERR_UNSUPPORTED;
+}
+
+// 2 x 2 pooling inside a tile of BM = 64 * WM pixels: even H and W, W a power of two below 32 or 32 * k
+// with the row pair inside one wavefront's WM blocks, and an even number of image rows per tile.
+static bool pool_fits(const ConvArgs& cv, const PatchGeom& pg, int WM) {
+    if ((cv.H & 1) || (cv.W & 1) || (pg.rows & 1)) return false;
+    if (cv.W < 32) return (cv.W & (cv.W - 1)) == 0;
+    return cv.W % 32 == 0 && 2 * (cv.W / 32) <= WM;
 }
 
 int launch_conv_patch(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t* C, int64_t ldc, int64_t M,
@@ -284,6 +339,23 @@ int launch_conv_patch(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_
 int launch_conv_patch_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
                             BnSignArgs bn, ConvArgs cv, void* stream) {
     return launch_conv_patch_any<true>(in, B, ldb, nullptr, 0, M, N, K, bn, cv, stream);
+}
+
+// Convolution, 2 x 2 max pooling (stride 2), BatchNorm, Sign in one launch; bn.out is the pooled
+// packed NHWC map [B][H/2][W/2][ld_out].  BNN_ERR_UNSUPPORTED where the pooling windows do not fit
+// the tiles (the caller then pools the unpooled output bits with bnn_maxpool_bits).
+int launch_conv_patch_pool_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
+                                 BnSignArgs bn, ConvArgs cv, void* stream) {
+    if (!aligned_to(B, 16) || ldb % 4 != 0) return BNN_ERR_UNSUPPORTED;
+    PatchGeom pg;
+    const bool big = ceil_div(M, 256) * ceil_div(N, 128) >= 512;
+    if (big && patch_geometry(cv, 256, pg) && pool_fits(cv, pg, 4))
+        return launch_patch<4, true, true>(in, B, ldb, nullptr, 0, M, N, K, bn, cv, pg, stream);
+    if (patch_geometry(cv, 128, pg) && pool_fits(cv, pg, 2))
+        return launch_patch<2, true, true>(in, B, ldb, nullptr, 0, M, N, K, bn, cv, pg, stream);
+    if (patch_geometry(cv, 256, pg) && pool_fits(cv, pg, 4))
+        return launch_patch<4, true, true>(in, B, ldb, nullptr, 0, M, N, K, bn, cv, pg, stream);
+    return BNN_ERR_UNSUPPORTED;
 }
 
 }  // namespace bnn

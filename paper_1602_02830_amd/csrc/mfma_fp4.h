@@ -163,14 +163,15 @@ __device__ inline float fold_column_term(int thr, int K, int pop_b2) {
 // v_permlane32_swap brings the halves of column block 0 to lanes 0-31 and those of block 1 to
 // lanes 32-63, so that, as in mfma_epilogue, lane l stores the word of column block l / 32.
 // pop_a / pop_af / pop_b / thr_s / flip_s as in mfma_epilogue.
+// mfma_output_words leaves, in words[i], the finished output word (flip and column validity
+// applied) of tile row wm*32*WM + i*32 + fr and column block fh of this wavefront's column pair;
+// mfma_epilogue_bits stores them.
 template <int WM, int WN>
-__device__ inline void mfma_epilogue_bits(v16f (&acc)[WM][WN], const int* pop_a, const float* pop_af,
-                                          const int* pop_b, const int* thr_s, const uint32_t* flip_s,
-                                          const float* colfix_s, const BnSignArgs& bn, int M, int N, int K,
-                                          int row0, int col0, int wm, int wn, int fr, int fh) {
+__device__ inline void mfma_output_words(v16f (&acc)[WM][WN], const int* pop_a, const float* pop_af,
+                                         const int* pop_b, const int* thr_s, const uint32_t* flip_s,
+                                         const float* colfix_s, int N, int K, int col0, int wm, int wn, int fr,
+                                         int fh, uint32_t (&words)[WM]) {
     static_assert(WN == 2, "the two column blocks are paired with the two lane halves");
-    const int64_t nw = (int64_t(N) + 31) >> 5;
-    const int64_t w = ((int64_t(col0) + wn * 32 * WN) >> 5) + fh;       // word column of this lane
     const uint32_t flip_word = flip_s[wn * WN + fh];                    // col0 is a multiple of 32
     const int cols_left = N - (col0 + wn * 32 * WN + fh * 32);
     const uint32_t live_word = cols_left >= 32 ? ~0u : cols_left <= 0 ? 0u : ((1u << cols_left) - 1u);
@@ -227,9 +228,23 @@ __device__ inline void mfma_epilogue_bits(v16f (&acc)[WM][WN], const int* pop_a,
         // Lanes 32-63 of part[0] <-> lanes 0-31 of part[1]: afterwards lane l holds, in the two
         // registers, the two halves of the word of column block l / 32.
         const auto sw = __builtin_amdgcn_permlane32_swap(part[0], part[1], false, false);
-        const uint32_t word = sw[0] | sw[1];
-        const int m = row0 + ml;
-        if (m < M && w < nw) bn.out[int64_t(m) * bn.ld_out + w] = (word ^ flip_word) & live_word;
+        words[i] = ((sw[0] | sw[1]) ^ flip_word) & live_word;
+    }
+}
+
+template <int WM, int WN>
+__device__ inline void mfma_epilogue_bits(v16f (&acc)[WM][WN], const int* pop_a, const float* pop_af,
+                                          const int* pop_b, const int* thr_s, const uint32_t* flip_s,
+                                          const float* colfix_s, const BnSignArgs& bn, int M, int N, int K,
+                                          int row0, int col0, int wm, int wn, int fr, int fh) {
+    uint32_t words[WM];
+    mfma_output_words<WM, WN>(acc, pop_a, pop_af, pop_b, thr_s, flip_s, colfix_s, N, K, col0, wm, wn, fr, fh, words);
+    const int64_t nw = (int64_t(N) + 31) >> 5;
+    const int64_t w = ((int64_t(col0) + wn * 32 * WN) >> 5) + fh;       // word column of this lane
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+        const int m = row0 + wm * 32 * WM + i * 32 + fr;
+        if (m < M && w < nw) bn.out[int64_t(m) * bn.ld_out + w] = words[i];
     }
 }
 

@@ -150,9 +150,23 @@ class BinaryConvLayer:
             self.Hp, self.Wp = (self.Ho - pool) // pool + 1, (self.Wo - pool) // pool + 1
             self.pooled = torch.empty((batch, self.Hp, self.Wp, B.words_per_row(self.Cout)), dtype=torch.int32,
                                       device=dev)
+        # Pooled, fused, implicit layers try the one-launch form first; the library refuses geometries whose
+        # pooling windows do not fit its tiles (before launching anything), and the layer then keeps to
+        # conv -> bnn_maxpool_bits.
+        self.pool_in_conv = bool(pool) and fused and implicit and self.Ho % pool == 0 and self.Wo % pool == 0
 
     def forward(self, x_bits: torch.Tensor) -> torch.Tensor:
         """x_bits: packed NHWC int32 [B][H][W][Cin/32].  Returns packed NHWC [B][Ho][Wo][ceil(Cout/32)]."""
+        if self.pool_in_conv:
+            try:
+                B.conv_pool_bn_sign_pack(x_bits, self.Cin, self.w_bits, self.thr, self.flip, self.kh, self.kw,
+                                         self.stride, self.pad, self.pool,
+                                         out=self.pooled.view(self.B * self.Hp * self.Wp, -1))
+                return self.pooled
+            except B.BnnError as e:
+                if e.status != 3:
+                    raise
+                self.pool_in_conv = False
         if self.implicit:
             if self.fused:
                 B.conv_bn_sign_pack(x_bits, self.Cin, self.w_bits, self.thr, self.flip, self.kh, self.kw,

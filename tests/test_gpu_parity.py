@@ -713,6 +713,57 @@ def test_maxpool_bits_matches_pooling_of_preactivations(shape):
     assert (words_to_host(pooled.reshape(-1, pooled.shape[-1])) == oracle.pack_bits(want)).all()
 
 
+@pytest.mark.parametrize("shape", [
+    # B, H, W, Cin, Cout
+    (3, 32, 32, 128, 130),      # row pairs in neighbouring accumulator blocks
+    (5, 16, 16, 256, 64),       # vertical neighbour 16 lanes away
+    (6, 8, 8, 128, 40),         # two images per tile
+    (3, 4, 4, 128, 33),
+    (70, 2, 2, 128, 20),        # 32 images per tile, the last tile partly empty
+    (2, 64, 64, 128, 40),       # 64-pixel rows: row pairs two blocks apart (256-pixel tiles)
+    (300, 32, 32, 128, 128),    # enough tiles for the 256-pixel form
+])
+def test_conv_pool_layer_in_one_launch(shape):
+    """conv -> 2x2 max pool of the pre-activations -> BatchNorm -> Sign in one launch against the oracle's
+    layer in that order, and against the two-call sequence (conv_bn_sign_pack, maxpool_bits)."""
+    B, H, W, Cin, Cout = shape
+    rng = np.random.default_rng(sum(shape))
+    x = synth.pm1(rng, (B, H, W, Cin))
+    Wt = synth.pm1(rng, (Cout, 3, 3, Cin))
+    bn = synth.bn_params(rng, Cout, 9 * Cin, adversarial=True)
+    xb = words_to_dev(_pack_nhwc(x).reshape(-1, Cin // 32)).view(B, H, W, Cin // 32)
+    wb = words_to_dev(oracle.pack_bits(Wt.reshape(Cout, -1)))
+    thr, flip = _fold_to_dev(bn, 9 * Cin)
+    got = bnn.conv_pool_bn_sign_pack(xb, Cin, wb, thr, flip)
+    bits = bnn.conv_bn_sign_pack(xb, Cin, wb, thr, flip)
+    two_calls = bnn.maxpool_bits(bits.view(B, H, W, -1), Cout, flip, 2, 2, 2)
+    assert torch.equal(got, two_calls.reshape(got.shape))
+    imgs = list(range(B)) if B <= 8 else [0, B // 2, B - 1]
+    for img in imgs:
+        _P, a_want = oracle.conv_pool_layer(x[img:img + 1], Wt, bn, pool=2, eps=EPS)
+        per = (H // 2) * (W // 2)
+        assert (words_to_host(got[img * per:(img + 1) * per]) == oracle.pack_bits(a_want.reshape(-1, Cout))).all(), img
+
+
+def test_conv_pool_layer_refuses_what_does_not_fit_its_tiles():
+    for (H, W, stride, pool) in ((6, 6, 1, 2), (32, 32, 2, 2), (32, 32, 1, 3), (16, 128, 1, 2)):
+        xb = torch.zeros((2, H, W, 4), dtype=torch.int32, device=DEV)
+        wb = torch.zeros((8, 36), dtype=torch.int32, device=DEV)
+        thr = torch.zeros(8, dtype=torch.int32, device=DEV)
+        flip = torch.zeros(1, dtype=torch.int32, device=DEV)
+        with pytest.raises(bnn.BnnError) as e:
+            bnn.conv_pool_bn_sign_pack(xb, 128, wb, thr, flip, 3, 3, stride, 1, pool)
+        assert e.value.status == 3, (H, W, stride, pool)
+    # the layer class falls back to the two-call sequence on such a geometry
+    x, Wt, bn = synth.config_conv(0, batch=2, size=6)
+    conv = bnn.BinaryConvLayer(torch.from_numpy(Wt.astype(np.float32)).to(DEV), bn, EPS, 2, 6, 6, fused=True,
+                               implicit=True, pool=2)
+    xb = words_to_dev(_pack_nhwc(x).reshape(-1, 4)).view(2, 6, 6, 4)
+    out = words_to_host(conv.forward(xb).reshape(2 * 9, -1))
+    _P, a_want = oracle.conv_pool_layer(x, Wt, bn, pool=2, eps=EPS)
+    assert (out == oracle.pack_bits(a_want.reshape(-1, 128))).all() and not conv.pool_in_conv
+
+
 def test_conv_pool_layers_full_batch_sampled_images():
     """conv -> max pool -> BatchNorm -> Sign at batch 256 with the implicit, fused layer + pooling on bits."""
     for layer in range(3):
