@@ -104,6 +104,14 @@ def test_argument_validation_of_the_fused_bitplane_and_conv_entry_points():
     assert lib.bnn_conv_xnor(p, 0, 4, 4, 128, p, 36, 4, 3, 3, 1, 1, p, 4, None) == 0
     assert lib.bnn_conv_bn_sign_pack(p, 1, 4, 4, 128, p, 36, 40, 3, 3, 1, 1, p, p, p, 1, None) == INVALID   # ld_out < ceil(Cout/32)
     assert lib.bnn_conv_bn_sign_pack(p, 1, 4, 4, 128, p, 36, 4, 3, 3, 1, 1, None, p, p, 1, None) == INVALID
+    # pooled layer in one launch: pool size, output leading dimension, what its tiles cannot hold
+    assert lib.bnn_conv_pool_bn_sign_pack(p, 1, 4, 4, 128, p, 36, 4, 3, 3, 1, 1, 0, p, p, p, 1, None) == INVALID
+    assert lib.bnn_conv_pool_bn_sign_pack(p, 1, 4, 4, 128, p, 36, 40, 3, 3, 1, 1, 2, p, p, p, 1, None) == INVALID
+    assert lib.bnn_conv_pool_bn_sign_pack(p, 1, 4, 4, 128, p, 36, 4, 3, 3, 1, 1, 2, None, p, p, 1, None) == INVALID
+    assert lib.bnn_conv_pool_bn_sign_pack(p, 1, 4, 4, 128, p, 36, 4, 3, 3, 1, 1, 3, p, p, p, 1, None) == UNSUPPORTED
+    assert lib.bnn_conv_pool_bn_sign_pack(p, 1, 6, 6, 128, p, 36, 4, 3, 3, 1, 1, 2, p, p, p, 1, None) == UNSUPPORTED
+    assert lib.bnn_conv_pool_bn_sign_pack(p, 1, 4, 4, 128, p, 36, 4, 3, 3, 2, 1, 2, p, p, p, 1, None) == UNSUPPORTED
+    assert lib.bnn_conv_pool_bn_sign_pack(p, 0, 4, 4, 128, p, 36, 4, 3, 3, 1, 1, 2, p, p, p, 1, None) == 0
     # pooling on bits: window larger than the map, zero stride, empty batch
     assert lib.bnn_maxpool_bits(p, 1, 2, 2, 32, 3, 3, 1, None, p, None) == INVALID
     assert lib.bnn_maxpool_bits(p, 1, 4, 4, 32, 2, 2, 0, None, p, None) == INVALID
