@@ -44,7 +44,11 @@ struct PatchGeom {
     int kq;            // quads of K per filter row: kh * kw * cqn
 };
 
-template <int WM, bool FUSED, bool POOL>
+// BRES: the filters' whole K extent (at most kResidentKTiles K-tiles of 4 quads) is staged once, next
+// to the patch, and the K loop runs without a barrier; otherwise B streams through two K-tile buffers.
+constexpr int kResidentKTiles = 5;
+
+template <int WM, bool FUSED, bool POOL, bool BRES>
 __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
     const uint32_t* __restrict__ in, const uint32_t* __restrict__ B, int64_t ldb, int32_t* __restrict__ C,
     int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n, BnSignArgs bn, ConvArgs cv, PatchGeom pg,
@@ -53,8 +57,8 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
     constexpr int PLANE_B = BN + 2;                     // 8-byte slots per B plane (2 pad slots)
     constexpr int ST_ROWS = 256 / 4;                    // filter rows per staging pass (4 threads per row)
     constexpr int LOADS_B = BN / ST_ROWS;
-    extern __shared__ uint2 patch[];                    // [cqn][2][slots], then int pix_pop[slots]
-    __shared__ uint2 lds_b[2][8 * PLANE_B];
+    extern __shared__ uint2 patch[];                    // [cqn][2][slots], int pix_pop[slots], resident B tiles
+    __shared__ uint2 lds_b_stream[BRES ? 1 : 2 * 8 * PLANE_B];
     __shared__ __attribute__((aligned(16))) int pop_a[BM];
     __shared__ __attribute__((aligned(16))) float pop_af[FUSED ? BM : 4];
     __shared__ __attribute__((aligned(16))) int pop_b[BN];
@@ -62,6 +66,7 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
     __shared__ uint32_t flip_s[FUSED ? BN / 32 : 1];
     __shared__ float colfix_s[FUSED ? BN : 1];
     int* pix_pop = reinterpret_cast<int*>(patch + size_t(2) * pg.cqn * pg.slots);
+    uint2* lds_b = BRES ? patch + size_t(2) * pg.cqn * pg.slots + (pg.slots + 1) / 2 : lds_b_stream;   // [buffer][8 planes]
 
     int tile_m, tile_n;
     tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
@@ -116,8 +121,8 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
         for (int l = 0; l < LOADS_B; ++l) {
             const uint4 v = zero_unless(live, rb[l]);
             cnt_b[l] += popc4(v);
-            lds_b[buf][(2 * st_q) * PLANE_B + st_r + l * ST_ROWS] = make_uint2(v.x, v.y);
-            lds_b[buf][(2 * st_q + 1) * PLANE_B + st_r + l * ST_ROWS] = make_uint2(v.z, v.w);
+            lds_b[(8 * buf + 2 * st_q) * PLANE_B + st_r + l * ST_ROWS] = make_uint2(v.x, v.y);
+            lds_b[(8 * buf + 2 * st_q + 1) * PLANE_B + st_r + l * ST_ROWS] = make_uint2(v.z, v.w);
         }
     };
 
@@ -125,9 +130,28 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
         if (tid < BN) thr_s[tid] = col0 + tid < N ? max(-K - 1, min(K + 1, bn.thr[col0 + tid])) : 0;
         if (tid < BN / 32) flip_s[tid] = col0 + 32 * tid < N ? bn.flip_bits[(col0 >> 5) + tid] : 0u;
     }
-    fetch_b(0);
-    stage_b(0, 0);
-    __syncthreads();                                    // patch, pixel popcounts and the first B tile are in LDS
+    if (BRES) {
+        // All K-tiles: every load is issued before the first is used.
+        uint4 all_b[kResidentKTiles][LOADS_B];
+#pragma unroll
+        for (int kt = 0; kt < kResidentKTiles; ++kt)
+            if (kt < n_ktiles) {
+                fetch_b(kt);
+#pragma unroll
+                for (int l = 0; l < LOADS_B; ++l) all_b[kt][l] = rb[l];
+            }
+#pragma unroll
+        for (int kt = 0; kt < kResidentKTiles; ++kt)
+            if (kt < n_ktiles) {
+#pragma unroll
+                for (int l = 0; l < LOADS_B; ++l) rb[l] = all_b[kt][l];
+                stage_b(kt, kt);
+            }
+    } else {
+        fetch_b(0);
+        stage_b(0, 0);
+    }
+    __syncthreads();                                    // patch, pixel popcounts and the first (or every) B tile are in LDS
 
     // Patch slot of output pixel r of the tile: group r / (rows * W), row and column inside it.
     auto slot_of = [&](int r) {
@@ -164,8 +188,8 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
     // (tap row, tap column, channel quad) of the next quad of K, stepped with carries.
     int ky = 0, kx = 0, cq = 0;
     for (int kt = 0; kt < n_ktiles; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < n_ktiles) fetch_b(kt + 1);
+        const int buf = BRES ? kt : kt & 1;
+        if (!BRES && kt + 1 < n_ktiles) fetch_b(kt + 1);
         const int quads_here = min(4, pg.kq - 4 * kt);
 #pragma unroll
         for (int qq = 0; qq < 4; ++qq) {
@@ -175,7 +199,7 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
 #pragma unroll
             for (int i = 0; i < WM; ++i) aw[i] = rd_a[i][a_off];
 #pragma unroll
-            for (int j = 0; j < WN; ++j) bw[j] = lds_b[buf][(2 * qq) * PLANE_B + rd_b + j * 32];
+            for (int j = 0; j < WN; ++j) bw[j] = lds_b[(8 * buf + 2 * qq) * PLANE_B + rd_b + j * 32];
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
                 v8i fa[WM], fb[WN];
@@ -204,13 +228,15 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
                 }
             }
         }
-        // Keep the staging of the next B tile (and the wait for its loads) behind the MFMA steps.
+        if (!BRES) {
+            // Keep the staging of the next B tile (and the wait for its loads) behind the MFMA steps.
 #pragma unroll
-        for (int i = 0; i < WM; ++i)
+            for (int i = 0; i < WM; ++i)
 #pragma unroll
-            for (int j = 0; j < WN; ++j) asm volatile("" : "+v"(acc[i][j]) : : "memory");
-        if (kt + 1 < n_ktiles) stage_b(kt + 1, buf ^ 1);
-        __syncthreads();
+                for (int j = 0; j < WN; ++j) asm volatile("" : "+v"(acc[i][j]) : : "memory");
+            if (kt + 1 < n_ktiles) stage_b(kt + 1, buf ^ 1);
+            __syncthreads();
+        }
     }
 
 #pragma unroll
@@ -300,11 +326,19 @@ static int launch_patch(const uint32_t* in, const uint32_t* B, int64_t ldb, int3
                         int64_t N, int64_t K, BnSignArgs bn, ConvArgs cv, PatchGeom pg, void* stream) {
     const int64_t tiles_m = ceil_div(M, 64 * WM), tiles_n = ceil_div(N, 128);
     if (tiles_m * tiles_n > kMaxDim) return BNN_ERR_UNSUPPORTED;
-    const size_t lds_bytes = size_t(pg.slots) * (size_t(cv.Cw) * 4 + 4);
+    const size_t patch_bytes = size_t(pg.slots) * size_t(cv.Cw) * 4 + size_t((pg.slots + 1) / 2) * 8;
+    const int n_ktiles = (pg.kq + 3) / 4;
+    const bool resident = n_ktiles <= kResidentKTiles;
+    const size_t lds_bytes = patch_bytes + (resident ? size_t(n_ktiles) * 8 * (128 + 2) * sizeof(uint2) : 0);
     const int n_images = int(M / (int64_t(cv.H) * cv.W));
-    hipLaunchKernelGGL((conv_patch_mfma_kernel<WM, FUSED, POOL>), dim3(unsigned(tiles_m * tiles_n)), dim3(256), lds_bytes,
-                       static_cast<hipStream_t>(stream), in, B, ldb, C, ldc, int(M), int(N), int(K), int(tiles_m),
-                       int(tiles_n), bn, cv, pg, n_images);
+    const dim3 grid(unsigned(tiles_m * tiles_n));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (resident)
+        hipLaunchKernelGGL((conv_patch_mfma_kernel<WM, FUSED, POOL, true>), grid, dim3(256), lds_bytes, s, in, B, ldb, C,
+                           ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn, cv, pg, n_images);
+    else
+        hipLaunchKernelGGL((conv_patch_mfma_kernel<WM, FUSED, POOL, false>), grid, dim3(256), lds_bytes, s, in, B, ldb, C,
+                           ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn, cv, pg, n_images);
     return check_launch();
 }
 
