@@ -65,6 +65,7 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
     __shared__ __attribute__((aligned(16))) int thr_s[FUSED ? BN : 1];
     __shared__ uint32_t flip_s[FUSED ? BN / 32 : 1];
     __shared__ float colfix_s[FUSED ? BN : 1];
+    __shared__ int coord_s[BM];
     int* pix_pop = reinterpret_cast<int*>(patch + size_t(2) * pg.cqn * pg.slots);
     uint2* lds_b = BRES ? patch + size_t(2) * pg.cqn * pg.slots + (pg.slots + 1) / 2 : lds_b_stream;   // [buffer][8 planes]
 
@@ -126,6 +127,14 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
         }
     };
 
+    // Output pixel r of the tile as (group, row in group, column), 10 bits each: the divisions are done
+    // once per pixel here, not once per use.
+    if (tid < BM) {
+        const int per_group = pg.rows * cv.W;
+        const int g = tid / per_group, t = tid - g * per_group;
+        const int yl = t / cv.W, x = t - yl * cv.W;
+        coord_s[tid] = (g << 20) | (yl << 10) | x;
+    }
     if (FUSED) {
         if (tid < BN) thr_s[tid] = col0 + tid < N ? max(-K - 1, min(K + 1, bn.thr[col0 + tid])) : 0;
         if (tid < BN / 32) flip_s[tid] = col0 + 32 * tid < N ? bn.flip_bits[(col0 >> 5) + tid] : 0u;
@@ -153,15 +162,12 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
     }
     __syncthreads();                                    // patch, pixel popcounts and the first (or every) B tile are in LDS
 
-    // Patch slot of output pixel r of the tile: group r / (rows * W), row and column inside it.
-    auto slot_of = [&](int r) {
-        const int per_group = pg.rows * cv.W;
-        const int g = r / per_group, t = r - g * per_group;
-        const int yl = t / cv.W, x = t - yl * cv.W;
-        return g * group_slots + yl * pg.pw + x;
-    };
     // Row popcounts: sum of the pixel popcounts under the kh x kw window (read before the epilogue,
     // which follows at least one more barrier).
+    auto slot_of = [&](int r) {
+        const int c = coord_s[r];
+        return (c >> 20) * group_slots + ((c >> 10) & 1023) * pg.pw + (c & 1023);
+    };
     if (tid < BM) {
         const int s0 = slot_of(tid);
         int sum = 0;
@@ -283,9 +289,9 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
                         l &= all[i2];
                     }
             }
-            const int m = row0 + wm * 32 * WM + i * 32 + fr;
-            const int b = m / hw, rem = m - b * hw;
-            const int y = rem / cv.W, x = rem - y * cv.W;
+            const int rl = wm * 32 * WM + i * 32 + fr, m = row0 + rl;
+            const int c = coord_s[rl];
+            const int b = b0 + (c >> 20), y = y0 + ((c >> 10) & 1023), x = c & 1023;
             const uint32_t pooled = (a & ~flip_word) | (l & flip_word);
             if (m < M && w < nw && !(y & 1) && !(x & 1))
                 bn.out[(int64_t(b) * hp + (y >> 1)) * wp * bn.ld_out + int64_t(x >> 1) * bn.ld_out + w] = pooled;
