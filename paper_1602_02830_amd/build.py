@@ -64,5 +64,18 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+C_ABI_EXAMPLE_SRC = os.path.join(ROOT, "tests", "c_abi", "hidden_layer.cpp")
+C_ABI_EXAMPLE = os.path.join(ROOT, "tests", "c_abi", "hidden_layer")
+
+
+def build_c_abi_example() -> str:
+    """Compiles the non-Python caller of the C ABI that the GPU tests run (tests/c_abi/hidden_layer.cpp)
+    and links it against the in-tree library (found again at run time through its rpath)."""
+    _run([HIPCC, f"--offload-arch={ARCH}", "-O2", "-std=c++17", f"-I{INCLUDE}", C_ABI_EXAMPLE_SRC, f"-L{PKG}",
+          "-lbnn_hip", f"-Wl,-rpath,{PKG}", "-Wl,-rpath,$ORIGIN/../../paper_1602_02830_amd", "-o", C_ABI_EXAMPLE])
+    return C_ABI_EXAMPLE
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_c_abi_example())

@@ -1011,3 +1011,16 @@ def test_gemm_i8_mfma_large_square_sampled():
     assert (C[rows] == oracle.matmul_pm1(A[rows], Bm)).all()
     H = torch.from_numpy(synth.hadamard(n)).to(DEV)
     assert torch.equal(bnn.gemm_i8_mfma(H, H), n * torch.eye(n, dtype=torch.int32, device=DEV))
+
+
+# ------------------------------------------------------------------ the C ABI from a non-Python caller
+
+def test_c_abi_from_a_plain_hip_program():
+    """tests/c_abi/hidden_layer.cpp (built by __graft_entry__.build()) links against libbnn_hip.so, allocates
+    with the HIP runtime and runs one hidden layer through include/bnn.h; it checks the results itself."""
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi", "hidden_layer")
+    assert os.path.exists(exe), "tests/c_abi/hidden_layer is not built: run __graft_entry__.build()"
+    proc = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert proc.returncode == 0 and "c_abi ok" in proc.stdout, proc.stdout
+
