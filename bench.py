@@ -120,6 +120,21 @@ def stream_only(args, bnn, torch, dev):
                       "avg_launch_ms": ms, "algorithmic_bytes": nbytes, "GBps": nbytes / ms / 1e6}), flush=True)
 
 
+def conv_only(args, bnn, torch, dev, synth, eps):
+    """One conv layer of the ConvNet workload (fused, no im2col matrix): one JSON line."""
+    layer = args.conv
+    ch, hw = synth.CONV_LAYERS[layer]
+    xc, Wt, bn = synth.config_conv(layer)
+    B = xc.shape[0]
+    wt = torch.from_numpy(Wt.astype(np.float32)).to(dev)
+    xb = bnn.pack_sign(torch.from_numpy(xc.reshape(-1, ch).astype(np.float32)).to(dev)).view(B, hw, hw, ch // 32)
+    conv = bnn.BinaryConvLayer(wt, bn, eps, B, hw, hw, fused=True, implicit=True)
+    ms, _ = time_launches(lambda: conv.forward(xb), args.steps, warmup=args.warmup)
+    ops = 2.0 * conv.M * conv.K * conv.Cout
+    print(json.dumps({"workload": f"conv_{ch}ch_{hw}x{hw}_batch{B}", "steps": args.steps, "warmup": args.warmup,
+                      "avg_launch_ms": ms, "binary_tops": ops / ms / 1e9, "images_per_s": B / ms * 1e3}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -144,6 +159,8 @@ def main():
     ap.add_argument("--stream", default=None, choices=["pack_sign", "bn_sign_pack"],
                     help="time only this streaming kernel on a --shape input (for profiler runs)")
     ap.add_argument("--shape", default="32768,8192", metavar="ROWS,COLS", help="input shape for --stream")
+    ap.add_argument("--conv", default=None, type=int, choices=[0, 1, 2],
+                    help="time only this fused conv layer of the ConvNet workload, batch 256 (for profiler runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -165,6 +182,9 @@ def main():
         return
     if args.stream:
         stream_only(args, bnn, torch, dev)
+        return
+    if args.conv is not None:
+        conv_only(args, bnn, torch, dev, synth, eps)
         return
 
     # ---------------- workload: MNIST-shaped MLP, batch 10000, synthetic -------------
