@@ -77,30 +77,6 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
     const int wm = wave >> 1, wn = wave & 1;
     const int fr = lane & 31, fh = lane >> 5;
 
-    // ---- patch: every slot once ------------------------------------------------------------
-    // The tile's first output pixel is (image b0, row y0, column 0); group g covers image rows
-    // y0 .. y0 + rows - 1 of image b0 (one group) or all rows of image b0 + g (several groups).
-    const int hw = cv.H * cv.W;
-    const int b0 = row0 / hw, y0 = (row0 - b0 * hw) / cv.W;
-    const int group_slots = pg.prows * pg.pw;
-    for (int s = tid; s < pg.slots; s += 256) {
-        const int g = s / group_slots, t = s - g * group_slots;
-        const int py = t / pg.pw, px = t - py * pg.pw;
-        const int b = b0 + g, y = y0 + py - cv.pad, x = px - cv.pad;
-        const bool inside = b < n_images && y >= 0 && y < cv.H && x >= 0 && x < cv.W;
-        const uint32_t pix = inside ? uint32_t((b * cv.H + y) * cv.W + x) : 0u;
-        const uint32_t* p = in + size_t(pix) * uint32_t(cv.Cw);
-        int pop = 0;
-        for (int cq = 0; cq < pg.cqn; ++cq) {
-            uint4 v = *reinterpret_cast<const uint4*>(p + 4 * cq);
-            if (!inside) v = make_uint4(~0u, ~0u, ~0u, ~0u);
-            patch[(2 * cq) * pg.slots + s] = make_uint2(v.x, v.y);
-            patch[(2 * cq + 1) * pg.slots + s] = make_uint2(v.z, v.w);
-            pop += popc4(v);
-        }
-        pix_pop[s] = pop;
-    }
-
     // ---- B staging: K-tiles of 4 quads, as planes [quad][half] ---------------------------------
     const int st_q = tid & 3, st_r = tid >> 2;
     const uint32_t* pb[LOADS_B];
@@ -139,9 +115,9 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
         if (tid < BN) thr_s[tid] = col0 + tid < N ? max(-K - 1, min(K + 1, bn.thr[col0 + tid])) : 0;
         if (tid < BN / 32) flip_s[tid] = col0 + 32 * tid < N ? bn.flip_bits[(col0 >> 5) + tid] : 0u;
     }
+    // The filter loads are issued first, so that they are in flight while the patch is addressed and loaded.
+    uint4 all_b[BRES ? kResidentKTiles : 1][LOADS_B];
     if (BRES) {
-        // All K-tiles: every load is issued before the first is used.
-        uint4 all_b[kResidentKTiles][LOADS_B];
 #pragma unroll
         for (int kt = 0; kt < kResidentKTiles; ++kt)
             if (kt < n_ktiles) {
@@ -149,6 +125,35 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
 #pragma unroll
                 for (int l = 0; l < LOADS_B; ++l) all_b[kt][l] = rb[l];
             }
+    } else {
+        fetch_b(0);
+    }
+
+    // ---- patch: every slot once ------------------------------------------------------------
+    // The tile's first output pixel is (image b0, row y0, column 0); group g covers image rows
+    // y0 .. y0 + rows - 1 of image b0 (one group) or all rows of image b0 + g (several groups).
+    const int hw = cv.H * cv.W;
+    const int b0 = row0 / hw, y0 = (row0 - b0 * hw) / cv.W;
+    const int group_slots = pg.prows * pg.pw;
+    for (int s = tid; s < pg.slots; s += 256) {
+        const int g = s / group_slots, t = s - g * group_slots;
+        const int py = t / pg.pw, px = t - py * pg.pw;
+        const int b = b0 + g, y = y0 + py - cv.pad, x = px - cv.pad;
+        const bool inside = b < n_images && y >= 0 && y < cv.H && x >= 0 && x < cv.W;
+        const uint32_t pix = inside ? uint32_t((b * cv.H + y) * cv.W + x) : 0u;
+        const uint32_t* p = in + size_t(pix) * uint32_t(cv.Cw);
+        int pop = 0;
+        for (int cq = 0; cq < pg.cqn; ++cq) {
+            uint4 v = *reinterpret_cast<const uint4*>(p + 4 * cq);
+            if (!inside) v = make_uint4(~0u, ~0u, ~0u, ~0u);
+            patch[(2 * cq) * pg.slots + s] = make_uint2(v.x, v.y);
+            patch[(2 * cq + 1) * pg.slots + s] = make_uint2(v.z, v.w);
+            pop += popc4(v);
+        }
+        pix_pop[s] = pop;
+    }
+
+    if (BRES) {
 #pragma unroll
         for (int kt = 0; kt < kResidentKTiles; ++kt)
             if (kt < n_ktiles) {
@@ -157,7 +162,6 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
                 stage_b(kt, kt);
             }
     } else {
-        fetch_b(0);
         stage_b(0, 0);
     }
     __syncthreads();                                    // patch, pixel popcounts and the first (or every) B tile are in LDS
