@@ -230,7 +230,10 @@ int bnn_conv_bn_sign_pack(const uint32_t *in, int64_t B, int64_t H, int64_t W, i
 
 /*
  * The pooled layer of the paper's ConvNets in one launch: convolution, pool x pool max pooling
- * (stride pool) of the pre-activations, BatchNorm, Sign (Sec. 2.2, 2.3; Alg. 4 for the last two).
+ * (stride pool) of the pre-activations, BatchNorm, Sign (Alg. 4 for the last two).  Sec. 2.2 only says
+ * that its ConvNet has the architecture of the BinaryConnect network it cites; that pooling sits between
+ * a convolution and its BatchNorm is this library's reading of that cited architecture, not a statement
+ * the paper prints.
  *   out [B*(Ho/pool)*(Wo/pool)][ld_out] packed bits, the packed NHWC input of the next layer;
  *   every other argument as in bnn_conv_bn_sign_pack.
  * Bit-identical to bnn_conv_bn_sign_pack followed by bnn_maxpool_bits (see there for why pooling
@@ -245,8 +248,9 @@ int bnn_conv_pool_bn_sign_pack(const uint32_t *in, int64_t B, int64_t H, int64_t
                                uint32_t *out, int64_t ld_out, void *stream);
 
 /*
- * Max pooling for binarized layers.  The paper's ConvNets pool the pre-activations between a
- * convolution and its BatchNorm + Sign; since Sign(BatchNorm(.)) is monotone per channel, the bit
+ * Max pooling for binarized layers.  In the architecture Sec. 2.2 refers to (the cited BinaryConnect
+ * ConvNet, as this library reads it) the pre-activations are pooled between a convolution and its
+ * BatchNorm + Sign; since Sign(BatchNorm(.)) is monotone per channel, the bit
  * of the pooled pre-activation is the OR of the window's bits where the channel's folded flip
  * bit is 0 and their AND where it is 1, so pooling runs on the packed output of the fused layer:
  *   out[b][py][px][c] = OR / AND over dy < ph, dx < pw of in[b][py*stride+dy][px*stride+dx][c]

@@ -213,9 +213,10 @@ void oracle_im2col(const int8_t *in, int64_t B, int64_t H, int64_t W,
             }
 }
 
-/* Max pooling of the integer pre-activations (the paper's ConvNets pool between the
- * convolution and its BatchNorm; Sec. 2.2 describes the architecture as that of
- * BinaryConnect, where every second convolution is followed by 2x2 max pooling):
+/* Max pooling of the integer pre-activations.  Sec. 2.2 only says its ConvNet has the
+ * architecture of the BinaryConnect network it cites; that every second convolution is
+ * followed by 2x2 max pooling, placed between the convolution and its BatchNorm, is this
+ * build's reading of that cited architecture (the paper prints neither):
  *   P[b][py][px][c] = max over (dy < ph, dx < pw) of S[b][py*stride+dy][px*stride+dx][c]
  * No padding; Hp = (H - ph)/stride + 1, Wp likewise. */
 void oracle_maxpool2d(const int32_t *S, int64_t B, int64_t H, int64_t W, int64_t C,

@@ -64,6 +64,16 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+CLOCK_PROBE_LIB = os.path.join(PKG, "libbnn_clock_probe.so")
+
+
+def build_clock_probe() -> str:
+    """Compiles the benchmark's clock probe (csrc/clock_probe.hip) into a library of its own: it is a
+    measurement aid that only bench.py loads, not part of the C ABI."""
+    _run([HIPCC, *HIP_FLAGS, "-shared", os.path.join(CSRC, "clock_probe.hip"), "-o", CLOCK_PROBE_LIB])
+    return CLOCK_PROBE_LIB
+
+
 C_ABI_EXAMPLE_SRC = os.path.join(ROOT, "tests", "c_abi", "hidden_layer.cpp")
 C_ABI_EXAMPLE = os.path.join(ROOT, "tests", "c_abi", "hidden_layer")
 
@@ -78,4 +88,5 @@ def build_c_abi_example() -> str:
 
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_clock_probe())
     print(build_c_abi_example())

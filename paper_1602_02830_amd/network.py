@@ -189,8 +189,11 @@ class BinaryConvLayer:
 
 
 class BinaryConvNet:
-    """The binary body of the paper's CIFAR-10 / SVHN ConvNet (Sec. 2.2, 2.3), from the first layer's
-    output bits to the class scores: 3x3 binary convolutions (fused with Sign(BatchNorm), max pooling on
+    """The binary body of the CIFAR-10 / SVHN ConvNet, from the first layer's output bits to the class
+    scores.  Sec. 2.2 only says the network has the architecture of the BinaryConnect ConvNet it cites;
+    the layer list used here (128C3-MP2-256C3-256C3-MP2-512C3-512C3-MP2-1024FC-1024FC-10 after the first
+    convolution) and the position of the pooling (before BatchNorm) are this build's reading of that
+    cited architecture.  Layers: 3x3 binary convolutions (fused with Sign(BatchNorm), max pooling on
     the output bits where the architecture pools), then binary dense layers.  Every layer's packed NHWC
     output is the next layer's input as it stands; the pooled bits of the last convolution, read row by
     row, are the (y, x, channel)-ordered input of the first dense layer.

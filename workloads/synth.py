@@ -6,7 +6,7 @@ path receive the arrays it returns.
 
 The inputs stand in, by shape only, for what the paper runs on: the 784-input,
 10-class, 10 000-image MNIST test set with a 3 x 4096 binary MLP (Sec. 2.1),
-32 x 32 images through 3 x 3 binary convolutions (Sec. 2.2, 2.3, 3.3) and the
+32 x 32 images (Sec. 2.2, 2.3) through 3 x 3 binary convolutions (Sec. 3.3) and the
 8192 x 8192 x 8192 binary matrix product of Sec. 4 / Fig. 3.  No item of any
 dataset is used or needed.
 
@@ -125,9 +125,10 @@ def config_conv(layer: int, batch: int = CONV_BATCH, channels: int | None = None
     return x, Wt, bn
 
 
-# The binary body of the paper's CIFAR-10 / SVHN ConvNet (Sec. 2.2, 2.3): after the first
-# convolution (which sees the real-valued image) come 128C3 - MP2 - 256C3 - 256C3 - MP2 - 512C3 -
-# 512C3 - MP2 - 1024FC - 1024FC - 10, all on +-1 activations.  (Cin, Cout, H = W, pooled)
+# The binary body of the CIFAR-10 / SVHN ConvNet.  Sec. 2.2 does not print the layer list: it says the
+# architecture is that of the BinaryConnect ConvNet it cites.  This build reads that cited architecture
+# as: after the first convolution (which sees the real-valued image) come 128C3 - MP2 - 256C3 - 256C3 -
+# MP2 - 512C3 - 512C3 - MP2 - 1024FC - 1024FC - 10, all on +-1 activations.  (Cin, Cout, H = W, pooled)
 CONVNET_CONVS = ((128, 128, 32, True), (128, 256, 16, False), (256, 256, 16, True),
                  (256, 512, 8, False), (512, 512, 8, True))
 CONVNET_FCS = (4 * 4 * 512, 1024, 1024, 10)
