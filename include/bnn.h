@@ -25,8 +25,9 @@
  *  - Every function returns a bnn_status.  On any status other than BNN_OK no
  *    kernel was launched and no output was written.  A dimension of 0 for
  *    rows/M/N/B is a valid empty problem: BNN_OK, nothing launched.
- *  - Limits: every dimension < 2^31; K <= 2^31 - 2 so that |dot| <= K and the
- *    threshold K + 1 fit in int32.
+ *  - Limits: every dimension < 2^31; K <= 2^31 - 32 for every product, so that
+ *    |dot| <= K, the threshold K + 1 and the word count (K + 31) / 32 stay inside
+ *    32-bit arithmetic (bnn_bn_fold alone accepts a range up to 2^31 - 2).
  */
 #ifndef BNN_H
 #define BNN_H
@@ -217,8 +218,8 @@ int bnn_conv_im2col_pack(const uint32_t *in, int64_t B, int64_t H, int64_t W,
  *   bnn_conv_bn_sign_pack:  out [B*Ho*Wo][ld_out] packed bits = (S >= thr[co]) XOR flip[co]
  *                           (= packed NHWC input of the next layer), thr/flip from bnn_bn_fold
  * Bit-identical to bnn_conv_im2col_pack followed by bnn_xnor_gemm (and bnn_bn_sign_pack).
- * Requires Cin % 128 == 0, `in` 16-byte aligned, kh*kw*Cin <= 2^24, H, W <= 32767 and an input of
- * fewer than 2^32 words; otherwise BNN_ERR_UNSUPPORTED (use the im2col path).
+ * Requires Cin % 128 == 0, `in` 16-byte aligned, kh*kw*Cin <= 2^24, H, W, pad, Ho, Wo <= 32767 and an
+ * input of fewer than 2^32 words; otherwise BNN_ERR_UNSUPPORTED (use the im2col path).
  */
 int bnn_conv_xnor(const uint32_t *in, int64_t B, int64_t H, int64_t W, int64_t Cin,
                   const uint32_t *Wb, int64_t ldw, int64_t Cout, int kh, int kw, int stride, int pad,
@@ -278,7 +279,9 @@ int bnn_gemm_i8_mfma(const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
 /* Expands packed rows to one int8 (+1 / -1) per element, the operand format of
  * bnn_gemm_i8_mfma: out[r][k] = bit k of in[r] ? +1 : -1 for k < K, and 0 for
  * K <= k < ld_out (so padded columns add nothing to a product).
- *   in [rows][ld_in] uint32, out [rows][ld_out] int8, ld_out >= K. */
+ *   in [rows][ld_in] uint32, out [rows][ld_out] int8, ld_out >= K.
+ * out is written four bytes at a time: it must be 4-byte aligned and ld_out a
+ * multiple of 4, else BNN_ERR_ALIGNMENT (bnn_gemm_i8_mfma wants 16 for both anyway). */
 int bnn_unpack_i8(const uint32_t *in, int64_t ld_in, int64_t rows, int64_t K,
                   int8_t *out, int64_t ld_out, void *stream);
 

@@ -15,7 +15,8 @@ namespace bnn {
 
 constexpr int kWave = 64;
 constexpr int64_t kMaxDim = (int64_t(1) << 31) - 1;
-constexpr int64_t kMaxK = (int64_t(1) << 31) - 2;
+// Largest K of a product: the kernels hold K and ceil(K / 32) = (K + 31) >> 5 in 32-bit integers.
+constexpr int64_t kMaxK = (int64_t(1) << 31) - 32;
 
 inline bool aligned_to(const void* p, size_t a) {
     return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0;

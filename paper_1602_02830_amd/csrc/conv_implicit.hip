@@ -38,6 +38,8 @@ static int conv_geometry(const uint32_t* in, int64_t B, int64_t H, int64_t W, in
     if (H + 2 * int64_t(pad) < kh || W + 2 * int64_t(pad) < kw) return BNN_ERR_INVALID_ARG;
     const int64_t Ho = (H + 2 * int64_t(pad) - kh) / stride + 1;
     const int64_t Wo = (W + 2 * int64_t(pad) - kw) / stride + 1;
+    // The tile loaders carry an output pixel as (oy << 16) | ox and form input coordinates in 32 bits.
+    if (pad > 32767 || Ho > 32767 || Wo > 32767) return BNN_ERR_UNSUPPORTED;
     K = int64_t(kh) * kw * Cin;
     M = B * Ho * Wo;
     if (K > kMaxK || M > kMaxDim - 1024) return BNN_ERR_INVALID_ARG;      // row indices run up to one tile past M

@@ -119,6 +119,13 @@ class BinaryConvLayer:
     im2col on packed NHWC bits -> XnorDotProduct -> Sign(BatchNorm) -> packed NHWC bits.
 
     weight_real: float32 device tensor [Cout][kh][kw][Cin], binarized by Eq. (1) on the device.
+    Any Cin is taken: a filter flattened as (ky, kx, ci) has exactly the bit order of the rows that
+    bnn_conv_im2col_pack writes, whether or not a tap fills whole words.
+
+    implicit=True asks for the layer without the im2col matrix (bnn_conv_xnor / bnn_conv_bn_sign_pack).
+    The library takes that form for Cin % 32 == 0 on same-size stride-1 layers and for Cin % 128 == 0
+    on any geometry; for everything else it answers "unsupported" before launching anything, and the
+    layer then keeps to bnn_conv_im2col_pack followed by the GEMM (self.implicit turns False).
     """
 
     def __init__(self, weight_real, bn, eps: float, batch: int, H: int, W: int, stride: int = 1, pad: int = 1,
@@ -134,16 +141,12 @@ class BinaryConvLayer:
         self.Wo = (W + 2 * pad - self.kw) // stride + 1
         self.K = self.kh * self.kw * self.Cin
         self.M = batch * self.Ho * self.Wo
-        if self.Cin % 32 == 0:
-            w2d = weight_real.reshape(self.Cout, self.K)
-        else:
-            raise ValueError("BinaryConvLayer packs weights per row; Cin must be a multiple of 32 here")
         self.w_bits = _packed_buffer(self.Cout, self.K, dev)
-        B.pack_sign(w2d, out=self.w_bits)
+        B.pack_sign(weight_real.reshape(self.Cout, self.K), out=self.w_bits)
         thr, flip = B.bn_fold(*bn, eps, self.K)
         self.thr = torch.from_numpy(thr).to(dev)
         self.flip = torch.from_numpy(flip.view(np.int32)).to(dev)
-        self.cols = None if implicit else _packed_buffer(self.M, self.K, dev)
+        self.cols = None if implicit else _packed_buffer(self.M, self.K, dev)     # the im2col matrix
         self.s = None if fused else torch.empty((self.M, self.Cout), dtype=torch.int32, device=dev)
         self.out_bits = torch.empty((self.M, B.words_per_row(self.Cout)), dtype=torch.int32, device=dev)
         if pool:
@@ -168,13 +171,20 @@ class BinaryConvLayer:
                     raise
                 self.pool_in_conv = False
         if self.implicit:
-            if self.fused:
-                B.conv_bn_sign_pack(x_bits, self.Cin, self.w_bits, self.thr, self.flip, self.kh, self.kw,
-                                    self.stride, self.pad, out=self.out_bits)
-            else:
-                B.conv_xnor(x_bits, self.Cin, self.w_bits, self.kh, self.kw, self.stride, self.pad, out=self.s)
-                B.bn_sign_pack(self.s, self.thr, self.flip, out=self.out_bits)
-        else:
+            try:
+                if self.fused:
+                    B.conv_bn_sign_pack(x_bits, self.Cin, self.w_bits, self.thr, self.flip, self.kh, self.kw,
+                                        self.stride, self.pad, out=self.out_bits)
+                else:
+                    B.conv_xnor(x_bits, self.Cin, self.w_bits, self.kh, self.kw, self.stride, self.pad, out=self.s)
+                    B.bn_sign_pack(self.s, self.thr, self.flip, out=self.out_bits)
+            except B.BnnError as e:
+                if e.status != 3:
+                    raise
+                # Refused before any launch (channel count or geometry): lower through the im2col matrix from now on.
+                self.implicit = False
+                self.cols = _packed_buffer(self.M, self.K, x_bits.device)
+        if not self.implicit:
             B.conv_im2col_pack(x_bits, self.Cin, self.kh, self.kw, self.stride, self.pad, out=self.cols)
             if self.fused:
                 B.xnor_gemm_bn_sign_pack(self.cols, self.w_bits, self.K, self.thr, self.flip, out=self.out_bits)

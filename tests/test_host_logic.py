@@ -16,6 +16,16 @@ from workloads import synth
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
+# tests/test_sanitizers.py runs the fold and size-helper tests of this file in a child process against a
+# build of the library's host-only sources (bn_fold.cpp, api.cpp) under AddressSanitizer and
+# UndefinedBehaviorSanitizer; BNN_HOST_LIB names that build, which exports only the host functions.
+_HOST_LIB = os.environ.get("BNN_HOST_LIB")
+if _HOST_LIB:
+    _lib = ctypes.CDLL(_HOST_LIB)
+    for _name in ("bnn_version", "bnn_status_string", "bnn_words_per_row", "bnn_bn_fold"):
+        getattr(_lib, _name).restype, getattr(_lib, _name).argtypes = binding._SIGNATURES[_name]
+    binding._lib = _lib
+
 
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "bnn.h")).read()
@@ -58,6 +68,7 @@ def test_argument_validation_happens_before_any_launch():
     assert lib.bnn_xnor_gemm(p, 1, p, 1, p, 4, 4, 4, 33, None) == INVALID      # lda < ceil(K/32)
     assert lib.bnn_xnor_gemm(p, 2, p, 2, p, 3, 4, 4, 33, None) == INVALID      # ldc < N
     assert lib.bnn_xnor_gemm(p, 2, p, 2, p, 4, 4, 4, 2 ** 31 - 1, None) == INVALID
+    assert lib.bnn_xnor_gemm(p, 2 ** 26, p, 2 ** 26, p, 4, 4, 4, 2 ** 31 - 31, None) == INVALID   # (K + 31) / 32 must fit 32 bits
     assert lib.bnn_xnor_gemm(None, 2, p, 2, p, 4, 4, 4, 33, None) == INVALID
     assert lib.bnn_xnor_gemm(p, 2, p, 2, p, 4, 0, 4, 33, None) == 0
     assert lib.bnn_xnor_gemm_kernel(p, 2, p, 2, p, 4, 4, 4, 33, 99, None) == INVALID
@@ -102,6 +113,10 @@ def test_argument_validation_of_the_fused_bitplane_and_conv_entry_points():
     assert lib.bnn_conv_xnor(p, 1, 1, 1, 128, p, 36, 4, 3, 3, 1, 0, p, 4, None) == INVALID        # no output pixel
     assert lib.bnn_conv_xnor(p, 1, 4, 4, 64, p, 18, 4, 3, 3, 1, 1, p, 4, None) == UNSUPPORTED     # Cin % 128 != 0
     assert lib.bnn_conv_xnor(p, 0, 4, 4, 128, p, 36, 4, 3, 3, 1, 1, p, 4, None) == 0
+    # output maps or paddings beyond the 15-bit coordinates of the tile loaders are refused, not mis-addressed
+    assert lib.bnn_conv_xnor(p, 1, 4, 4, 128, p, 36, 4, 3, 3, 1, 20000, p, 4, None) == UNSUPPORTED   # Ho = 40002
+    assert lib.bnn_conv_xnor(p, 1, 4, 4, 128, p, 36, 4, 3, 3, 1, 40000, p, 4, None) == UNSUPPORTED   # pad itself
+    assert lib.bnn_conv_bn_sign_pack(p, 1, 4, 4, 128, p, 36, 4, 3, 3, 1, 2 ** 30, p, p, p, 1, None) == UNSUPPORTED
     assert lib.bnn_conv_bn_sign_pack(p, 1, 4, 4, 128, p, 36, 40, 3, 3, 1, 1, p, p, p, 1, None) == INVALID   # ld_out < ceil(Cout/32)
     assert lib.bnn_conv_bn_sign_pack(p, 1, 4, 4, 128, p, 36, 4, 3, 3, 1, 1, None, p, p, 1, None) == INVALID
     # pooled layer in one launch: pool size, output leading dimension, what its tiles cannot hold
