@@ -382,27 +382,70 @@ def test_xnor_gemm_dense_layer_config(kernel):
     _gemm_case(A, Bm, GEMM_KERNELS[kernel])
 
 
+@pytest.mark.parametrize("adversarial", [False, True])
+def test_dense_layer_config_chained_as_specified(adversarial):
+    """The single binary dense layer as the workload states it: A 64 x 1024 and B 1024 x 1024 of +-1 from the
+    seed, packed on the device; int32 output 64 x 1024; then BatchNorm-then-Sign with the workload's own
+    per-channel parameters (and the copy with negative / zero gammas) folded to integer thresholds; output
+    packed.  Chained GEMM -> epilogue as two launches and as the fused launch, every element."""
+    A, Bm, bn = synth.config_dense(adversarial=adversarial)
+    S_want, a_want = oracle.dense_layer(A, Bm, bn, eps=EPS)
+    a_bits = bnn.pack_sign(torch.from_numpy(A.astype(np.float32)).to(DEV))
+    b_bits = bnn.pack_sign(torch.from_numpy(np.ascontiguousarray(Bm.T).astype(np.float32)).to(DEV))
+    assert (words_to_host(a_bits) == oracle.pack_bits(A)).all()
+    thr, flip = _fold_to_dev(bn, 1024)
+    S = bnn.xnor_gemm(a_bits, b_bits, 1024)
+    assert (S.cpu().numpy() == S_want).all()
+    out = bnn.bn_sign_pack(S, thr, flip)
+    assert (words_to_host(out) == oracle.pack_bits(a_want)).all()
+    fused = bnn.xnor_gemm_bn_sign_pack(a_bits, b_bits, 1024, thr, flip)
+    assert (words_to_host(fused) == oracle.pack_bits(a_want)).all()
+
+
+_LARGE_SQUARE = {}
+
+
+def _large_square_oracle():
+    """The 8192^3 workload and the oracle's full product (a few seconds on the host cores), computed once
+    for all the tests that check a kernel's 8192 x 8192 result on every element."""
+    if not _LARGE_SQUARE:
+        A, Bm = synth.config_gemm_square(synth.GEMM_LARGE)
+        _LARGE_SQUARE.update(A=A, Bm=Bm, C=oracle.matmul_pm1(A, Bm))
+    return _LARGE_SQUARE["A"], _LARGE_SQUARE["Bm"], _LARGE_SQUARE["C"]
+
+
 @pytest.mark.parametrize("kernel", ["auto", "tiled128", "mfma", "mfma128"])
-def test_xnor_gemm_large_square_hadamard_and_sampled_rows(kernel):
+def test_xnor_gemm_large_square_hadamard_and_every_element(kernel):
     """8192^3 in the launch configuration the benchmark times.  (i) Sylvester-Hadamard
     operands: the full 8192 x 8192 result must be 8192 * I (closed form, checked on
-    every element).  (ii) random +-1 operands: 256 sampled rows and a band of columns
-    against the oracle."""
+    every element).  (ii) random +-1 operands: every element against the oracle's
+    full product."""
     n = synth.GEMM_LARGE
     H = synth.hadamard(n)
     hb = words_to_dev(oracle.pack_bits(H))
     C = bnn.xnor_gemm(hb, hb, n, kernel=GEMM_KERNELS[kernel])
     assert torch.equal(C, n * torch.eye(n, dtype=torch.int32, device=DEV))
     del C
-    A, Bm = synth.config_gemm_square(n)
+    A, Bm, want = _large_square_oracle()
     da = words_to_dev(oracle.pack_bits(A))
     db = words_to_dev(oracle.pack_bits(np.ascontiguousarray(Bm.T)))
     C = bnn.xnor_gemm(da, db, n, kernel=GEMM_KERNELS[kernel]).cpu().numpy()
-    rows = np.random.default_rng(1).choice(n, 256, replace=False)
-    assert (C[rows] == oracle.matmul_pm1(A[rows], Bm)).all()
-    cols = np.arange(4000, 4128)
-    assert (C[:, cols] == oracle.matmul_pm1(A, np.ascontiguousarray(Bm[:, cols]))).all()
+    bad = np.argwhere(C != want)
+    assert bad.size == 0, f"first mismatch at {bad[0]}"
     assert (np.abs(C) <= n).all() and (C % 2 == 0).all()
+
+
+def test_fused_layer_large_square_every_element():
+    """bnn_xnor_gemm_bn_sign_pack at 8192^3 (the fused launch the benchmark also times): every output bit
+    against the oracle's float BatchNorm + Sign of its full product."""
+    n = synth.GEMM_LARGE
+    A, Bm, S = _large_square_oracle()
+    bn = synth.bn_params(synth.rng_for(4, 2), n, n, adversarial=True)
+    want = oracle.pack_bits(oracle.bn_sign(S, *bn, eps=EPS))
+    thr, flip = _fold_to_dev(bn, n)
+    got = bnn.xnor_gemm_bn_sign_pack(words_to_dev(oracle.pack_bits(A)),
+                                     words_to_dev(oracle.pack_bits(np.ascontiguousarray(Bm.T))), n, thr, flip)
+    assert (words_to_host(got) == want).all()
 
 
 def test_matrices_of_more_than_2_31_elements():
@@ -545,17 +588,18 @@ def test_fused_layer_with_thresholds_outside_the_result_range(kernel):
     assert (words_to_host(got) == oracle.pack_bits(want_pm1)).all()
 
 
-def test_fused_mlp_full_batch_sampled_rows():
-    x, weights, bns = synth.config_mlp(adversarial=True)
+@pytest.mark.parametrize("adversarial", [False, True])
+def test_fused_mlp_full_batch_every_row(adversarial):
+    """Batch 10000 through the fused layers, as the benchmark runs it (adversarial=False is the benchmark's
+    own workload): every row of every layer's packed activations and of the scores against the oracle."""
+    x, weights, bns = synth.config_mlp(adversarial=adversarial)
     wr = [torch.from_numpy(np.ascontiguousarray(w.T).astype(np.float32)).to(DEV) for w in weights]
     net = bnn.BinaryMLP(wr, bns, EPS, synth.MLP_BATCH, fused=True)
     scores = net.forward(torch.from_numpy(x).to(DEV)).cpu().numpy()
-    rows = np.sort(np.random.default_rng(4).choice(synth.MLP_BATCH, 400, replace=False))
-    rows[0], rows[-1] = 0, synth.MLP_BATCH - 1
-    tr = oracle.mlp_forward(x[rows], weights, bns, eps=EPS)
+    tr = oracle.mlp_forward(x, weights, bns, eps=EPS)
     for l in range(len(weights)):
-        assert (words_to_host(net.a_bits[l])[rows] == oracle.pack_bits(tr["a"][l])).all(), f"a^b_{l}"
-    assert (scores[rows] == tr["s"][-1]).all()
+        assert (words_to_host(net.a_bits[l]) == oracle.pack_bits(tr["a"][l])).all(), f"a^b_{l}"
+    assert (scores == tr["s"][-1]).all()
 
 
 # ------------------------------------------------------------------ conv_im2col_pack
@@ -604,21 +648,23 @@ def test_conv_layers_end_to_end_small_batch():
         assert (words_to_host(out.reshape(-1, out.shape[-1])) == oracle.pack_bits(a_want.reshape(-1, C))).all()
 
 
+@pytest.mark.parametrize("implicit", [False, True])
 @pytest.mark.parametrize("fused", [False, True])
-def test_conv_layers_full_batch_sampled_images(fused):
-    """Batch 256 as benchmarked; the oracle checks a sample of whole images (images are independent)."""
+def test_conv_layers_full_batch_every_image(fused, implicit):
+    """Batch 256 as benchmarked, through the im2col matrix and without it: every pre-activation and every
+    output bit of all 256 images against the oracle's direct convolution + float BatchNorm + Sign."""
     for layer in range(3):
         x, Wt, bn = synth.config_conv(layer, adversarial=fused)
         B, H, W, C = x.shape
-        conv = bnn.BinaryConvLayer(torch.from_numpy(Wt.astype(np.float32)).to(DEV), bn, EPS, B, H, W, fused=fused)
+        conv = bnn.BinaryConvLayer(torch.from_numpy(Wt.astype(np.float32)).to(DEV), bn, EPS, B, H, W, fused=fused,
+                                   implicit=implicit)
         xb = words_to_dev(_pack_nhwc(x).reshape(-1, C // 32)).view(B, H, W, C // 32)
-        out = words_to_host(conv.forward(xb).reshape(B, H * W, -1))
-        s = None if fused else conv.s.cpu().numpy().reshape(B, H, W, C)
-        for img in (0, 101, 255):
-            S_want, a_want = oracle.conv_layer(x[img:img + 1], Wt, bn, eps=EPS)
-            if not fused:
-                assert (s[img] == S_want[0]).all()
-            assert (out[img] == oracle.pack_bits(a_want.reshape(-1, C))).all()
+        out = words_to_host(conv.forward(xb).reshape(B * H * W, -1))
+        assert conv.implicit == implicit
+        S_want, a_want = oracle.conv_layer(x, Wt, bn, eps=EPS)
+        if not fused:
+            assert (conv.s.cpu().numpy().reshape(B, H, W, C) == S_want).all(), f"layer {layer}: pre-activations"
+        assert (out == oracle.pack_bits(a_want.reshape(-1, C))).all(), f"layer {layer}: output bits"
 
 
 @pytest.mark.parametrize("shape", [
@@ -764,18 +810,19 @@ def test_conv_pool_layer_refuses_what_does_not_fit_its_tiles():
     assert (out == oracle.pack_bits(a_want.reshape(-1, 128))).all() and not conv.pool_in_conv
 
 
-def test_conv_pool_layers_full_batch_sampled_images():
-    """conv -> max pool -> BatchNorm -> Sign at batch 256 with the implicit, fused layer + pooling on bits."""
+def test_conv_pool_layers_full_batch_every_image():
+    """conv -> max pool -> BatchNorm -> Sign at batch 256 with the implicit, fused layer and the pooling
+    inside the launch: every output bit of all 256 images."""
     for layer in range(3):
         x, Wt, bn = synth.config_conv(layer, adversarial=True)
         B, H, W, C = x.shape
         conv = bnn.BinaryConvLayer(torch.from_numpy(Wt.astype(np.float32)).to(DEV), bn, EPS, B, H, W, fused=True,
                                    implicit=True, pool=2)
         xb = words_to_dev(_pack_nhwc(x).reshape(-1, C // 32)).view(B, H, W, C // 32)
-        out = words_to_host(conv.forward(xb).reshape(B, (H // 2) * (W // 2), -1))
-        for img in (0, 77, 255):
-            _P, a_want = oracle.conv_pool_layer(x[img:img + 1], Wt, bn, pool=2, eps=EPS)
-            assert (out[img] == oracle.pack_bits(a_want.reshape(-1, C))).all()
+        out = words_to_host(conv.forward(xb).reshape(B * (H // 2) * (W // 2), -1))
+        assert conv.pool_in_conv
+        _P, a_want = oracle.conv_pool_layer(x, Wt, bn, pool=2, eps=EPS)
+        assert (out == oracle.pack_bits(a_want.reshape(-1, C))).all(), f"layer {layer}"
 
 
 def _convnet_oracle(x, convs, fcs, fc_bns):
@@ -819,13 +866,19 @@ def test_convnet_body_every_intermediate_small_batch():
     assert (scores == scores_want).all()
 
 
-def test_convnet_body_full_batch_sampled_images():
-    """Batch 256 as benchmarked; images are independent, so the oracle runs the chain on a sample."""
+def test_convnet_body_full_batch_every_image():
+    """Batch 256 as benchmarked: every layer's packed output and the scores of all 256 images against the
+    oracle's chain."""
     x, convs, fcs, fc_bns = synth.config_convnet()
-    _net, scores = _convnet_on_gpu(x, convs, fcs, fc_bns)
-    for img in (0, 131, 255):
-        _acts, want = _convnet_oracle(x[img:img + 1], convs, fcs, fc_bns)
-        assert (scores[img] == want[0]).all(), f"image {img}"
+    acts, scores_want = _convnet_oracle(x, convs, fcs, fc_bns)
+    net, scores = _convnet_on_gpu(x, convs, fcs, fc_bns)
+    for l, layer in enumerate(net.convs):
+        got = layer.pooled if layer.pool else layer.out_bits
+        C = acts[l].shape[-1]
+        assert (words_to_host(got.reshape(-1, C // 32)) == oracle.pack_bits(acts[l].reshape(-1, C))).all(), f"conv {l}"
+    for l, a in enumerate(net.a_bits):
+        assert (words_to_host(a) == oracle.pack_bits(acts[len(net.convs) + l])).all(), f"dense {l}"
+    assert (scores == scores_want).all()
 
 
 # ------------------------------------------------------------------ MLP chain
@@ -883,16 +936,15 @@ def test_mlp_forward_captured_in_a_hip_graph_replays_bit_exact():
         assert (net.s[-1].cpu().numpy() == oracle.mlp_forward(x0, weights, bns, eps=EPS)["s"][-1]).all()
 
 
-def test_mlp_full_batch_sampled_rows():
-    """Batch 10000 as benchmarked; samples (rows) are independent, so the oracle runs on 500 of them."""
+def test_mlp_full_batch_every_row():
+    """Batch 10000 with separate GEMM and BN+Sign launches: every int32 pre-activation and every packed
+    activation of all 10000 rows against the oracle."""
     x, weights, bns = synth.config_mlp()
     net = _mlp_on_gpu(x, weights, bns, synth.MLP_BATCH)
-    rows = np.sort(np.random.default_rng(2).choice(synth.MLP_BATCH, 500, replace=False))
-    rows[0], rows[-1] = 0, synth.MLP_BATCH - 1
-    tr = oracle.mlp_forward(x[rows], weights, bns, eps=EPS)
+    tr = oracle.mlp_forward(x, weights, bns, eps=EPS)
     for l in range(len(weights)):
-        assert (words_to_host(net.a_bits[l])[rows] == oracle.pack_bits(tr["a"][l])).all(), f"a^b_{l}"
-        assert (net.s[l].cpu().numpy()[rows] == tr["s"][l]).all(), f"s_{l}"
+        assert (words_to_host(net.a_bits[l]) == oracle.pack_bits(tr["a"][l])).all(), f"a^b_{l}"
+        assert (net.s[l].cpu().numpy() == tr["s"][l]).all(), f"s_{l}"
 
 
 # ------------------------------------------------------------------ first layer on 8-bit inputs
@@ -953,8 +1005,8 @@ def test_bitplane_gemm_ignores_pad_bits_of_the_planes():
 
 
 @pytest.mark.parametrize("fused", [False, True])
-def test_mlp_uint8_first_layer_full_batch_sampled_rows(fused):
-    """Alg. 4 as printed (8-bit inputs through bit planes), batch 10000, MNIST-shaped MLP."""
+def test_mlp_uint8_first_layer_full_batch_every_row(fused):
+    """Alg. 4 as printed (8-bit inputs through bit planes), batch 10000, MNIST-shaped MLP: every row."""
     _x, weights, bns = synth.config_mlp()
     x8 = synth.uint8_input(synth.rng_for(1, 1), (synth.MLP_BATCH, synth.MLP_SIZES[0]))
     bn0 = synth.bn_params(synth.rng_for(1, 30), synth.MLP_SIZES[1], 255 * synth.MLP_SIZES[0])
@@ -962,14 +1014,12 @@ def test_mlp_uint8_first_layer_full_batch_sampled_rows(fused):
     wr = [torch.from_numpy(np.ascontiguousarray(w.T).astype(np.float32)).to(DEV) for w in weights]
     net = bnn.BinaryMLP(wr, bns, EPS, synth.MLP_BATCH, fused=fused, input_uint8=True)
     scores = net.forward(torch.from_numpy(x8).to(DEV)).cpu().numpy()
-    rows = np.sort(np.random.default_rng(6).choice(synth.MLP_BATCH, 300, replace=False))
-    rows[0], rows[-1] = 0, synth.MLP_BATCH - 1
-    tr = oracle.mlp_forward_uint8(x8[rows], weights, bns, eps=EPS)
+    tr = oracle.mlp_forward_uint8(x8, weights, bns, eps=EPS)
     for l in range(1, len(weights)):
-        assert (words_to_host(net.a_bits[l])[rows] == oracle.pack_bits(tr["a"][l])).all(), f"a^b_{l}"
+        assert (words_to_host(net.a_bits[l]) == oracle.pack_bits(tr["a"][l])).all(), f"a^b_{l}"
     if not fused:
-        assert (net.s[0].cpu().numpy()[rows] == tr["s"][0]).all()
-    assert (scores[rows] == tr["s"][-1]).all()
+        assert (net.s[0].cpu().numpy() == tr["s"][0]).all()
+    assert (scores == tr["s"][-1]).all()
 
 
 # ------------------------------------------------------------------ int8 MFMA variant
@@ -1001,14 +1051,13 @@ def test_unpack_i8_then_mfma_equals_xnor_path():
     assert (bnn.gemm_i8_mfma(a8, b8).cpu().numpy() == oracle.matmul_pm1(A, Bm)).all()
 
 
-def test_gemm_i8_mfma_large_square_sampled():
+def test_gemm_i8_mfma_large_square_every_element():
     n = synth.GEMM_LARGE
-    A, Bm = synth.config_gemm_square(n)
+    A, Bm, want = _large_square_oracle()
     a = torch.from_numpy(A).to(DEV)
     b = torch.from_numpy(np.ascontiguousarray(Bm.T)).to(DEV)
     C = bnn.gemm_i8_mfma(a, b).cpu().numpy()
-    rows = np.random.default_rng(3).choice(n, 128, replace=False)
-    assert (C[rows] == oracle.matmul_pm1(A[rows], Bm)).all()
+    assert (C == want).all()
     H = torch.from_numpy(synth.hadamard(n)).to(DEV)
     assert torch.equal(bnn.gemm_i8_mfma(H, H), n * torch.eye(n, dtype=torch.int32, device=DEV))
 
