@@ -218,8 +218,12 @@ int bnn_conv_im2col_pack(const uint32_t *in, int64_t B, int64_t H, int64_t W,
  *   bnn_conv_bn_sign_pack:  out [B*Ho*Wo][ld_out] packed bits = (S >= thr[co]) XOR flip[co]
  *                           (= packed NHWC input of the next layer), thr/flip from bnn_bn_fold
  * Bit-identical to bnn_conv_im2col_pack followed by bnn_xnor_gemm (and bnn_bn_sign_pack).
- * Requires Cin % 128 == 0, `in` 16-byte aligned, kh*kw*Cin <= 2^24, H, W, pad, Ho, Wo <= 32767 and an
- * input of fewer than 2^32 words; otherwise BNN_ERR_UNSUPPORTED (use the im2col path).
+ * Requires kh*kw*Cin <= 2^24, H, W, pad, Ho, Wo <= 32767, an input of fewer than 2^32 words, and either
+ *   Cin % 128 == 0 with `in` 16-byte aligned (any kh, kw, stride, pad), or
+ *   Cin % 32 == 0 on a same-size stride-1 layer (kh = kw = 2*pad + 1) whose image rows fit the kernel's
+ *   128-pixel tiles (W divides 128; H a multiple of 128/W or the reverse), with kh*kw*Cin <= 2560 and
+ *   Wb 16-byte aligned, ldw % 4 == 0 (e.g. the 64-channel 3 x 3 layers of the half-width net of Sec. 2.3);
+ * otherwise BNN_ERR_UNSUPPORTED (use the im2col path).
  */
 int bnn_conv_xnor(const uint32_t *in, int64_t B, int64_t H, int64_t W, int64_t Cin,
                   const uint32_t *Wb, int64_t ldw, int64_t Cout, int kh, int kw, int stride, int pad,

@@ -46,9 +46,11 @@ static int conv_geometry(const uint32_t* in, int64_t B, int64_t H, int64_t W, in
     if (ldw < ceil_div(K, 32)) return BNN_ERR_INVALID_ARG;
     if (B > 0 && Cout > 0 && (!in || !Wb)) return BNN_ERR_INVALID_ARG;
     if (!aligned_to(in, 4) || !aligned_to(Wb, 4)) return BNN_ERR_ALIGNMENT;
-    // The tile loader moves 16-byte groups of 4 channel words and addresses the input with
-    // 32-bit word offsets.
-    if (Cin % 128 != 0 || !aligned_to(in, 16) || !mfma_path_supports(K)) return BNN_ERR_UNSUPPORTED;
+    // Whole channel words only.  With Cin % 128 == 0 the tile loaders move 16-byte groups of 4 channel
+    // words; other multiples of 32 are taken word by word, by the LDS-patch kernel alone (same-size
+    // stride-1 layers; launch_conv_mfma refuses the rest).  The input is addressed with 32-bit word offsets.
+    if (Cin % 32 != 0 || !mfma_path_supports(K)) return BNN_ERR_UNSUPPORTED;
+    if (Cin % 128 == 0 && !aligned_to(in, 16)) return BNN_ERR_UNSUPPORTED;
     if (B * H * W * (Cin / 32) > (int64_t(1) << 32) - 1) return BNN_ERR_UNSUPPORTED;
     cv.H = int(H); cv.W = int(W); cv.Cw = int(Cin / 32);
     cv.kh = kh; cv.kw = kw; cv.stride = stride; cv.pad = pad;

@@ -24,9 +24,17 @@
 // one wavefront's rows: the horizontal neighbour is the next lane, the vertical one W lanes away
 // (W < 32) or in the accumulator block W / 32 further on, and only the pooled words are stored.
 //
+// Channel counts that are multiples of 32 but not of 128 (WORDS = true; the 64-channel block of the
+// half-width SVHN net of Sec. 2.3): a tap is then not a whole number of 16-byte quads, so the patch is
+// kept as planes [channel word][slot] of single words, and the K-word that lane half h consumes at step
+// (quad q, s), word 4q + 2h + s of the receptive field, is looked up in a small LDS table that maps
+// a K-word to (channel word plane, tap offset).  Filter words beyond the receptive field's last word
+// are zeroed at staging.  Everything else is shared.
+//
 // Geometry this kernel takes (the launcher checks; everything else goes to the gathering kernels):
-// stride 1, Ho = H, Wo = W, Cin % 128 == 0, BM % W == 0 and, with R = BM / W, H % R == 0 or
-// R % H == 0; filters 16-byte aligned with ldb % 4 == 0; patch within kPatchMaxBytes of LDS.
+// stride 1, Ho = H, Wo = W, Cin % 32 == 0, BM % W == 0 and, with R = BM / W, H % R == 0 or
+// R % H == 0; filters 16-byte aligned with ldb % 4 == 0; patch within kPatchMaxBytes of LDS; with
+// Cin % 128 != 0 a receptive field of at most kResidentKTiles * 512 bits.
 #include "bnn_internal.h"
 #include "gemm_staging.h"
 #include "mfma_fp4.h"
@@ -40,15 +48,21 @@ struct PatchGeom {
     int rows;          // output rows per group
     int prows, pw;     // patch rows per group, patch row pitch (pixels)
     int slots;         // groups * prows * pw
-    int cqn;           // channel quads per pixel (Cw / 4)
-    int kq;            // quads of K per filter row: kh * kw * cqn
+    int cqn;           // channel quads per pixel (Cw / 4); unused when a tap is not a whole number of quads
+    int kq;            // quads of K per filter row: kh * kw * cqn, or ceil(kwords / 4)
+    int kwords;        // words of K per filter row: kh * kw * Cw
 };
+
+// Word offset of the K-word table behind the word-granular patch ([Cw][slots] words + slots pixel popcounts).
+__host__ __device__ inline size_t words_patch_koff_offset(int Cw, int slots) {
+    return (size_t(Cw + 1) * size_t(slots) + 1) & ~size_t(1);
+}
 
 // BRES: the filters' whole K extent (at most kResidentKTiles K-tiles of 4 quads) is staged once, next
 // to the patch, and the K loop runs without a barrier; otherwise B streams through two K-tile buffers.
 constexpr int kResidentKTiles = 5;
 
-template <int WM, bool FUSED, bool POOL, bool BRES>
+template <int WM, bool FUSED, bool POOL, bool BRES, bool WORDS>
 __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
     const uint32_t* __restrict__ in, const uint32_t* __restrict__ B, int64_t ldb, int32_t* __restrict__ C,
     int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n, BnSignArgs bn, ConvArgs cv, PatchGeom pg,
@@ -57,7 +71,9 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
     constexpr int PLANE_B = BN + 2;                     // 8-byte slots per B plane (2 pad slots)
     constexpr int ST_ROWS = 256 / 4;                    // filter rows per staging pass (4 threads per row)
     constexpr int LOADS_B = BN / ST_ROWS;
+    static_assert(!WORDS || BRES, "the word-granular patch is built for resident filters only");
     extern __shared__ uint2 patch[];                    // [cqn][2][slots], int pix_pop[slots], resident B tiles
+                                                        // WORDS: uint32 [Cw][slots], pix_pop, int koff[4*kq], B tiles
     __shared__ uint2 lds_b_stream[BRES ? 1 : 2 * 8 * PLANE_B];
     __shared__ __attribute__((aligned(16))) int pop_a[BM];
     __shared__ __attribute__((aligned(16))) float pop_af[FUSED ? BM : 4];
@@ -66,8 +82,15 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
     __shared__ uint32_t flip_s[FUSED ? BN / 32 : 1];
     __shared__ float colfix_s[FUSED ? BN : 1];
     __shared__ int coord_s[BM];
-    int* pix_pop = reinterpret_cast<int*>(patch + size_t(2) * pg.cqn * pg.slots);
-    uint2* lds_b = BRES ? patch + size_t(2) * pg.cqn * pg.slots + (pg.slots + 1) / 2 : lds_b_stream;   // [buffer][8 planes]
+    uint32_t* patchw = reinterpret_cast<uint32_t*>(patch);
+    int* pix_pop = WORDS ? reinterpret_cast<int*>(patchw + size_t(cv.Cw) * pg.slots)
+                         : reinterpret_cast<int*>(patch + size_t(2) * pg.cqn * pg.slots);
+    // WORDS: K-word -> plane and tap offset into patchw, read two at a time (hence the even word offset)
+    const size_t koff_at = words_patch_koff_offset(cv.Cw, pg.slots);
+    int* koff_s = reinterpret_cast<int*>(patchw) + koff_at;
+    uint2* lds_b = !BRES ? lds_b_stream                 // [buffer][8 planes]
+                   : WORDS ? patch + (koff_at + size_t(4) * pg.kq) / 2
+                           : patch + size_t(2) * pg.cqn * pg.slots + (pg.slots + 1) / 2;
 
     int tile_m, tile_n;
     tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
@@ -96,7 +119,13 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
         const bool live = 4 * kt + st_q < pg.kq;
 #pragma unroll
         for (int l = 0; l < LOADS_B; ++l) {
-            const uint4 v = zero_unless(live, rb[l]);
+            uint4 v = zero_unless(live, rb[l]);
+            if (WORDS) {                                // words of the quad beyond the receptive field's last one
+                const int left = pg.kwords - 4 * (4 * kt + st_q);
+                if (left < 4) v.w = 0u;
+                if (left < 3) v.z = 0u;
+                if (left < 2) v.y = 0u;
+            }
             cnt_b[l] += popc4(v);
             lds_b[(8 * buf + 2 * st_q) * PLANE_B + st_r + l * ST_ROWS] = make_uint2(v.x, v.y);
             lds_b[(8 * buf + 2 * st_q + 1) * PLANE_B + st_r + l * ST_ROWS] = make_uint2(v.z, v.w);
@@ -143,14 +172,35 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
         const uint32_t pix = inside ? uint32_t((b * cv.H + y) * cv.W + x) : 0u;
         const uint32_t* p = in + size_t(pix) * uint32_t(cv.Cw);
         int pop = 0;
-        for (int cq = 0; cq < pg.cqn; ++cq) {
-            uint4 v = *reinterpret_cast<const uint4*>(p + 4 * cq);
-            if (!inside) v = make_uint4(~0u, ~0u, ~0u, ~0u);
-            patch[(2 * cq) * pg.slots + s] = make_uint2(v.x, v.y);
-            patch[(2 * cq + 1) * pg.slots + s] = make_uint2(v.z, v.w);
-            pop += popc4(v);
+        if (WORDS) {
+            for (int cw = 0; cw < cv.Cw; ++cw) {
+                const uint32_t v = inside ? p[cw] : ~0u;
+                patchw[cw * pg.slots + s] = v;
+                pop += __popc(v);
+            }
+        } else {
+            for (int cq = 0; cq < pg.cqn; ++cq) {
+                uint4 v = *reinterpret_cast<const uint4*>(p + 4 * cq);
+                if (!inside) v = make_uint4(~0u, ~0u, ~0u, ~0u);
+                patch[(2 * cq) * pg.slots + s] = make_uint2(v.x, v.y);
+                patch[(2 * cq + 1) * pg.slots + s] = make_uint2(v.z, v.w);
+                pop += popc4(v);
+            }
         }
         pix_pop[s] = pop;
+    }
+    if (WORDS) {
+        // K-word kwi of a receptive field = channel word kwi % Cw of tap kwi / Cw; words past the field's
+        // end point at a valid cell (their filter words are zero).
+        for (int kwi = tid; kwi < 4 * pg.kq; kwi += 256) {
+            int off = 0;
+            if (kwi < pg.kwords) {
+                const int tap = kwi / cv.Cw, cw = kwi - tap * cv.Cw;
+                const int ty = tap / cv.kw, tx = tap - ty * cv.kw;
+                off = cw * pg.slots + ty * pg.pw + tx;
+            }
+            koff_s[kwi] = off;
+        }
     }
 
     if (BRES) {
@@ -183,8 +233,13 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
 
     // This lane's A operands: pixel wm*32*WM + i*32 + fr, words of lane half fh.
     const uint2* rd_a[WM];
+    const uint32_t* rd_aw[WM];                          // WORDS: the pixel's cell in plane 0
 #pragma unroll
-    for (int i = 0; i < WM; ++i) rd_a[i] = patch + fh * pg.slots + slot_of(wm * 32 * WM + i * 32 + fr);
+    for (int i = 0; i < WM; ++i) {
+        const int slot = slot_of(wm * 32 * WM + i * 32 + fr);
+        rd_a[i] = patch + fh * pg.slots + slot;
+        rd_aw[i] = patchw + slot;
+    }
     const int rd_b = fh * PLANE_B + wn * 32 * WN + fr;
 
     v16f acc[WM][WN];
@@ -204,10 +259,17 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
 #pragma unroll
         for (int qq = 0; qq < 4; ++qq) {
             if (qq >= quads_here) break;
-            const int a_off = (2 * cq) * pg.slots + ky * pg.pw + kx;
             uint2 aw[WM], bw[WN];
+            if (WORDS) {
+                // this lane half's two K-words of the quad: 4q + 2*fh and the next one
+                const int2 off = *reinterpret_cast<const int2*>(&koff_s[4 * (4 * kt + qq) + 2 * fh]);
 #pragma unroll
-            for (int i = 0; i < WM; ++i) aw[i] = rd_a[i][a_off];
+                for (int i = 0; i < WM; ++i) aw[i] = make_uint2(rd_aw[i][off.x], rd_aw[i][off.y]);
+            } else {
+                const int a_off = (2 * cq) * pg.slots + ky * pg.pw + kx;
+#pragma unroll
+                for (int i = 0; i < WM; ++i) aw[i] = rd_a[i][a_off];
+            }
 #pragma unroll
             for (int j = 0; j < WN; ++j) bw[j] = lds_b[(8 * buf + 2 * qq) * PLANE_B + rd_b + j * 32];
 #pragma unroll
@@ -230,7 +292,7 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
                                 fa[i], fb[j], acc[i][j], 4 /* A: fp4 */, 4 /* B: fp4 */, 0, 0, 0, 0);
                     }
             }
-            if (++cq == pg.cqn) {
+            if (!WORDS && ++cq == pg.cqn) {
                 cq = 0;
                 if (++kx == cv.kw) {
                     kx = 0;
@@ -312,7 +374,7 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
 static bool patch_geometry(const ConvArgs& cv, int BM, PatchGeom& pg) {
     if (cv.stride != 1 || cv.Ho != cv.H || cv.Wo != cv.W) return false;
     if (cv.kh != 2 * cv.pad + 1 || cv.kw != 2 * cv.pad + 1) return false;
-    if (cv.W > BM || BM % cv.W != 0 || cv.Cw % 4 != 0) return false;
+    if (cv.W > BM || BM % cv.W != 0) return false;
     const int R = BM / cv.W;
     if (cv.H % R == 0) {
         pg.groups = 1;
@@ -327,7 +389,9 @@ static bool patch_geometry(const ConvArgs& cv, int BM, PatchGeom& pg) {
     pg.pw = cv.W + 2 * cv.pad;
     pg.slots = pg.groups * pg.prows * pg.pw;
     pg.cqn = cv.Cw / 4;
-    pg.kq = cv.kh * cv.kw * pg.cqn;
+    pg.kwords = cv.kh * cv.kw * cv.Cw;
+    pg.kq = (pg.kwords + 3) / 4;
+    if (cv.Cw % 4 != 0 && (pg.kq + 3) / 4 > kResidentKTiles) return false;     // word-granular patch: resident filters only
     return int64_t(pg.slots) * (cv.Cw * 4 + 4) <= kPatchMaxBytes;
 }
 
@@ -336,19 +400,24 @@ static int launch_patch(const uint32_t* in, const uint32_t* B, int64_t ldb, int3
                         int64_t N, int64_t K, BnSignArgs bn, ConvArgs cv, PatchGeom pg, void* stream) {
     const int64_t tiles_m = ceil_div(M, 64 * WM), tiles_n = ceil_div(N, 128);
     if (tiles_m * tiles_n > kMaxDim) return BNN_ERR_UNSUPPORTED;
-    const size_t patch_bytes = size_t(pg.slots) * size_t(cv.Cw) * 4 + size_t((pg.slots + 1) / 2) * 8;
+    const bool words = cv.Cw % 4 != 0;                  // a tap is not a whole number of 16-byte quads
+    const size_t patch_bytes = words ? (words_patch_koff_offset(cv.Cw, pg.slots) + size_t(4) * pg.kq) * 4
+                                     : size_t(pg.slots) * size_t(cv.Cw) * 4 + size_t((pg.slots + 1) / 2) * 8;
     const int n_ktiles = (pg.kq + 3) / 4;
     const bool resident = n_ktiles <= kResidentKTiles;
     const size_t lds_bytes = patch_bytes + (resident ? size_t(n_ktiles) * 8 * (128 + 2) * sizeof(uint2) : 0);
     const int n_images = int(M / (int64_t(cv.H) * cv.W));
     const dim3 grid(unsigned(tiles_m * tiles_n));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (resident)
-        hipLaunchKernelGGL((conv_patch_mfma_kernel<WM, FUSED, POOL, true>), grid, dim3(256), lds_bytes, s, in, B, ldb, C,
-                           ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn, cv, pg, n_images);
+    if (words)                                          // patch_geometry has checked that the filters are resident
+        hipLaunchKernelGGL((conv_patch_mfma_kernel<WM, FUSED, POOL, true, true>), grid, dim3(256), lds_bytes, s, in, B,
+                           ldb, C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn, cv, pg, n_images);
+    else if (resident)
+        hipLaunchKernelGGL((conv_patch_mfma_kernel<WM, FUSED, POOL, true, false>), grid, dim3(256), lds_bytes, s, in, B,
+                           ldb, C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn, cv, pg, n_images);
     else
-        hipLaunchKernelGGL((conv_patch_mfma_kernel<WM, FUSED, POOL, false>), grid, dim3(256), lds_bytes, s, in, B, ldb, C,
-                           ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn, cv, pg, n_images);
+        hipLaunchKernelGGL((conv_patch_mfma_kernel<WM, FUSED, POOL, false, false>), grid, dim3(256), lds_bytes, s, in, B,
+                           ldb, C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn, cv, pg, n_images);
     return check_launch();
 }
 

@@ -448,6 +448,7 @@ int launch_conv_mfma(const uint32_t* in, const uint32_t* B, int64_t ldb, int32_t
                      int64_t N, int64_t K, ConvArgs cv, void* stream) {
     const int st = launch_conv_patch(in, B, ldb, C, ldc, M, N, K, cv, stream);
     if (st != BNN_ERR_UNSUPPORTED) return st;
+    if (cv.Cw % 4 != 0) return BNN_ERR_UNSUPPORTED;     // the gathering loaders move whole 16-byte channel quads
     if (conv_shortk_supports(B, ldb, K)) return launch_conv_mfma_shortk(in, B, ldb, C, ldc, M, N, K, cv, stream);
     if (conv_wants_small_tiles(M, N))
         return launch_mfma<2, false, false, true>(in, 0, B, ldb, C, ldc, M, N, K, BnSignArgs{}, cv, stream);
@@ -458,6 +459,7 @@ int launch_conv_mfma_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, i
                            BnSignArgs bn, ConvArgs cv, void* stream) {
     const int st = launch_conv_patch_fused(in, B, ldb, M, N, K, bn, cv, stream);
     if (st != BNN_ERR_UNSUPPORTED) return st;
+    if (cv.Cw % 4 != 0) return BNN_ERR_UNSUPPORTED;
     if (conv_shortk_supports(B, ldb, K)) return launch_conv_mfma_shortk_fused(in, B, ldb, M, N, K, bn, cv, stream);
     if (conv_wants_small_tiles(M, N))
         return launch_mfma<2, true, false, true>(in, 0, B, ldb, nullptr, 0, M, N, K, bn, cv, stream);

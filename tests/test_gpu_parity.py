@@ -689,6 +689,15 @@ def test_conv_layers_full_batch_every_image(fused, implicit):
     (2, 32, 32, 128, 70, 1, 1, 1, 0),       # 1 x 1 window, no halo
     (3, 6, 128, 128, 20, 3, 3, 1, 1),       # one image row per tile
     (9, 16, 16, 384, 200, 3, 3, 1, 1),      # 3 channel quads per pixel, K-tiles that straddle taps
+    # channel counts that are multiples of 32 but not of 128 (the half-width net's 64-channel block): the
+    # LDS-patch kernel with single-word planes
+    (6, 32, 32, 64, 64, 3, 3, 1, 1),        # 2 words per tap: 18 K-words, the last quad half empty
+    (5, 16, 16, 32, 40, 3, 3, 1, 1),        # 1 word per tap: a step spans two taps, 9 K-words (odd)
+    (3, 8, 8, 96, 130, 3, 3, 1, 1),         # 3 words per tap, two images per tile
+    (2, 16, 16, 160, 33, 3, 3, 1, 1),       # 5 words per tap: 45 K-words
+    (2, 4, 4, 64, 20, 5, 5, 1, 2),          # 5 x 5 window, 50 K-words, 8 images per tile of which 2 exist
+    (40, 32, 32, 64, 64, 3, 3, 1, 1),       # 320 tiles of 128 pixels
+    (520, 16, 16, 64, 128, 3, 3, 1, 1),     # 520 tiles of 256 pixels: the grid that takes the larger tile
 ])
 def test_implicit_conv_matches_direct_convolution(shape):
     """Implicit-GEMM conv (no im2col matrix) == the oracle's direct convolution; fused form ==
@@ -700,7 +709,7 @@ def test_implicit_conv_matches_direct_convolution(shape):
     bn = synth.bn_params(rng, Cout, kh * kw * Cin, adversarial=True)
     S = oracle.conv_direct(x, Wt, stride=stride, pad=pad)
     xb = words_to_dev(_pack_nhwc(x).reshape(-1, Cin // 32)).view(B, H, W, Cin // 32)
-    wb = words_to_dev(oracle.pack_bits(Wt.reshape(Cout, -1)))
+    wb = _aligned_words(oracle.pack_bits(Wt.reshape(Cout, -1)))     # junk behind filters that are not whole quads
     got = bnn.conv_xnor(xb, Cin, wb, kh, kw, stride, pad).cpu().numpy()
     assert (got.reshape(S.shape) == S).all()
     thr, flip = _fold_to_dev(bn, kh * kw * Cin)
@@ -734,12 +743,76 @@ def test_implicit_conv_randomized_geometries(seed):
         assert (bits == oracle.pack_bits(oracle.bn_sign(S.reshape(-1, Cout), *bn, eps=EPS))).all(), tag
 
 
-def test_implicit_conv_rejects_unsupported_channel_counts():
-    xb = torch.zeros((1, 4, 4, 1), dtype=torch.int32, device=DEV)
-    wb = torch.zeros((8, 9), dtype=torch.int32, device=DEV)
-    with pytest.raises(bnn.BnnError) as e:
-        bnn.conv_xnor(xb, 32, wb)
-    assert e.value.status == 3          # BNN_ERR_UNSUPPORTED: the im2col path handles this
+@pytest.mark.parametrize("seed", range(3))
+def test_implicit_conv_randomized_same_size_layers_with_any_whole_word_channel_count(seed):
+    """Seeded random same-size stride-1 layers whose rows tile 128 pixels, Cin any multiple of 32 up to 256
+    (single-word planes unless Cin % 128 == 0): int32 sums, fused bits and the pooled layer."""
+    rng = np.random.default_rng(4242 + seed)
+    for _case in range(10):
+        W = int(rng.choice([2, 4, 8, 16, 32, 64]))
+        rows_per_tile = 128 // W
+        H = int(rng.choice([h for h in (1, 2, 4, 6, 8, 12, 16, 32) if h % rows_per_tile == 0 or rows_per_tile % h == 0]))
+        k = int(rng.choice([1, 3])) if W >= 2 else 1
+        B, Cin, Cout = int(rng.integers(1, 6)), 32 * int(rng.integers(1, 9)), int(rng.integers(1, 200))
+        if k * k * Cin > 2560 and Cin % 128:
+            Cin = 64
+        tag = f"seed {seed} B={B} H={H} W={W} Cin={Cin} Cout={Cout} k={k}"
+        x = synth.pm1(rng, (B, H, W, Cin), rng.uniform(0.1, 0.9))
+        Wt = synth.pm1(rng, (Cout, k, k, Cin))
+        bn = synth.bn_params(rng, Cout, k * k * Cin, adversarial=True)
+        pad = k // 2
+        S = oracle.conv_direct(x, Wt, stride=1, pad=pad)
+        xb = words_to_dev(_pack_nhwc(x).reshape(-1, Cin // 32)).view(B, H, W, Cin // 32)
+        wb = _aligned_words(oracle.pack_bits(Wt.reshape(Cout, -1)))
+        got = bnn.conv_xnor(xb, Cin, wb, k, k, 1, pad).cpu().numpy()
+        assert (got.reshape(S.shape) == S).all(), tag
+        thr, flip = _fold_to_dev(bn, k * k * Cin)
+        bits = words_to_host(bnn.conv_bn_sign_pack(xb, Cin, wb, thr, flip, k, k, 1, pad))
+        assert (bits == oracle.pack_bits(oracle.bn_sign(S.reshape(-1, Cout), *bn, eps=EPS))).all(), tag
+        if H % 2 == 0 and W % 2 == 0 and W <= 32:
+            try:
+                pooled = bnn.conv_pool_bn_sign_pack(xb, Cin, wb, thr, flip, k, k, 1, pad)
+            except bnn.BnnError as e:
+                assert e.status == 3, tag            # a geometry whose pooling windows do not fit the tiles
+                continue
+            _P, a_want = oracle.conv_pool_layer(x, Wt, bn, pool=2, pad=pad, eps=EPS)
+            assert (words_to_host(pooled) == oracle.pack_bits(a_want.reshape(-1, Cout))).all(), tag + " pooled"
+
+
+def test_implicit_conv_rejects_what_only_the_im2col_path_takes():
+    """BNN_ERR_UNSUPPORTED before any launch: channel counts that are not whole words, and channel counts
+    that are not multiples of 128 on anything but a same-size stride-1 layer with a short receptive field."""
+    def refused(x_shape, Cin, Cout, kh, kw, stride, pad):
+        xb = torch.zeros(x_shape, dtype=torch.int32, device=DEV)
+        wb = torch.zeros((Cout, (kh * kw * Cin + 31) // 32 + 3 & ~3), dtype=torch.int32, device=DEV)
+        with pytest.raises(bnn.BnnError) as e:
+            bnn.conv_xnor(xb, Cin, wb, kh, kw, stride, pad)
+        return e.value.status == 3
+    assert refused((1, 4, 4, 2), 40, 8, 3, 3, 1, 1)            # Cin % 32 != 0
+    assert refused((1, 8, 8, 2), 64, 8, 3, 3, 2, 1)            # stride 2
+    assert refused((1, 8, 8, 2), 64, 8, 3, 3, 1, 0)            # output smaller than the input
+    assert refused((1, 5, 7, 2), 64, 8, 3, 3, 1, 1)            # image rows do not tile 128 pixels
+    assert refused((1, 8, 8, 11), 352, 8, 3, 3, 1, 1)          # 99 K-words: filters not resident
+
+
+def test_conv_layer_class_falls_back_to_im2col_for_other_channel_counts():
+    """BinaryConvLayer(implicit=True) on a layer the implicit form refuses (40 channels: taps that are not
+    whole words; 64 channels at stride 2) lowers through bnn_conv_im2col_pack instead, same result."""
+    for (B, H, W, Cin, Cout, stride) in [(2, 6, 6, 40, 33, 1), (3, 9, 9, 64, 20, 2)]:
+        rng = np.random.default_rng(B + Cin)
+        x = synth.pm1(rng, (B, H, W, Cin))
+        Wt = synth.pm1(rng, (Cout, 3, 3, Cin))
+        bn = synth.bn_params(rng, Cout, 9 * Cin, adversarial=True)
+        S_want, a_want = oracle.conv_layer(x, Wt, bn, stride=stride, eps=EPS)
+        for fused in (False, True):
+            conv = bnn.BinaryConvLayer(torch.from_numpy(Wt.astype(np.float32)).to(DEV), bn, EPS, B, H, W, stride=stride,
+                                       fused=fused, implicit=True)
+            xb = words_to_dev(_pack_nhwc(x).reshape(-1, (Cin + 31) // 32)).view(B, H, W, -1)
+            out = words_to_host(conv.forward(xb).reshape(-1, (Cout + 31) // 32))
+            assert not conv.implicit
+            if not fused:
+                assert (conv.s.cpu().numpy().reshape(S_want.shape) == S_want).all()
+            assert (out == oracle.pack_bits(a_want.reshape(-1, Cout))).all()
 
 
 @pytest.mark.parametrize("shape", [(2, 8, 8, 128, 2, 2), (3, 7, 9, 40, 2, 2), (1, 6, 6, 33, 3, 3), (2, 5, 5, 64, 2, 1)])

@@ -111,7 +111,9 @@ def test_argument_validation_of_the_fused_bitplane_and_conv_entry_points():
     assert lib.bnn_conv_xnor(p, 1, 4, 4, 128, p, 35, 4, 3, 3, 1, 1, p, 4, None) == INVALID        # ldw < 9 * Cin / 32
     assert lib.bnn_conv_xnor(p, 1, 4, 4, 128, p, 36, 4, 3, 3, 1, 1, p, 3, None) == INVALID        # lds < Cout
     assert lib.bnn_conv_xnor(p, 1, 1, 1, 128, p, 36, 4, 3, 3, 1, 0, p, 4, None) == INVALID        # no output pixel
-    assert lib.bnn_conv_xnor(p, 1, 4, 4, 64, p, 18, 4, 3, 3, 1, 1, p, 4, None) == UNSUPPORTED     # Cin % 128 != 0
+    assert lib.bnn_conv_xnor(p, 1, 4, 4, 48, p, 14, 4, 3, 3, 1, 1, p, 4, None) == UNSUPPORTED     # Cin % 32 != 0
+    assert lib.bnn_conv_xnor(p, 1, 4, 4, 64, p, 20, 4, 3, 3, 2, 1, p, 4, None) == UNSUPPORTED     # Cin % 128 != 0 at stride 2
+    assert lib.bnn_conv_xnor(p, 1, 4, 4, 64, p, 18, 4, 3, 3, 1, 1, p, 4, None) == UNSUPPORTED     # ... or with ldw % 4 != 0
     assert lib.bnn_conv_xnor(p, 0, 4, 4, 128, p, 36, 4, 3, 3, 1, 1, p, 4, None) == 0
     # output maps or paddings beyond the 15-bit coordinates of the tile loaders are refused, not mis-addressed
     assert lib.bnn_conv_xnor(p, 1, 4, 4, 128, p, 36, 4, 3, 3, 1, 20000, p, 4, None) == UNSUPPORTED   # Ho = 40002
