@@ -173,8 +173,10 @@ int bnn_xnor_gemm_bn_sign_pack_kernel(const uint32_t *A, int64_t lda, const uint
  * bnn_bitplane_gemm:  C[m][n] = sum_k x[m][k] * w[n][k],  x in [0,255] given as bit planes (layout
  *   above, Xp [M][ldx], ldx >= 8*ceil(K/32)), w in {-1,+1} given as packed rows B [N][ldb] as in
  *   bnn_xnor_gemm; C [M][ldc] int32.  Computed plane by plane on the matrix engine with the plane
- *   weight 2^(n-1) as block scale; exact while 255*K < 2^24, larger K gives BNN_ERR_UNSUPPORTED.
- *   Pad bits of the last K-word of either operand are ignored.
+ *   weight 2^(n-1) as block scale while 255*K < 2^24 (the exact range of its accumulation); larger
+ *   K is computed with and/popcount on the vector ALU (slow, exact).  255*K must fit int32
+ *   (255*K <= 2^31 - 32), else BNN_ERR_INVALID_ARG.  Pad bits of the last K-word of either operand
+ *   are ignored.
  *
  * bnn_bitplane_gemm_bn_sign_pack: the same product followed by Sign(BatchNorm(a_1, theta_1)) on
  *   folded thresholds (bnn_bn_fold with 255*K as the range argument), written as packed bits:
@@ -218,7 +220,9 @@ int bnn_conv_im2col_pack(const uint32_t *in, int64_t B, int64_t H, int64_t W,
  *   bnn_conv_bn_sign_pack:  out [B*Ho*Wo][ld_out] packed bits = (S >= thr[co]) XOR flip[co]
  *                           (= packed NHWC input of the next layer), thr/flip from bnn_bn_fold
  * Bit-identical to bnn_conv_im2col_pack followed by bnn_xnor_gemm (and bnn_bn_sign_pack).
- * Requires kh*kw*Cin <= 2^24, H, W, pad, Ho, Wo <= 32767, an input of fewer than 2^32 words, and either
+ * Receptive fields of more than 2^24 bits (beyond the matrix engine's exact range) take a slow, exact
+ * xor/popcount kernel for any geometry with Cin % 32 == 0.
+ * Requires H, W, pad, Ho, Wo <= 32767, an input of fewer than 2^32 words, and either
  *   Cin % 128 == 0 with `in` 16-byte aligned (any kh, kw, stride, pad), or
  *   Cin % 32 == 0 on a same-size stride-1 layer (kh = kw = 2*pad + 1) whose image rows fit the kernel's
  *   128-pixel tiles (W divides 128; H a multiple of 128/W or the reverse), with kh*kw*Cin <= 2560 and

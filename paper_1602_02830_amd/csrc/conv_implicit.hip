@@ -27,6 +27,9 @@ int launch_conv_mfma_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, i
                            BnSignArgs bn, ConvArgs cv, void* stream);
 int launch_conv_patch_pool_fused(const uint32_t* in, const uint32_t* B, int64_t ldb, int64_t M, int64_t N, int64_t K,
                                  BnSignArgs bn, ConvArgs cv, void* stream);
+// Vector-ALU form for receptive fields beyond the matrix engine's exact range (valu_fallbacks.hip).
+int launch_conv_xnor_valu(const uint32_t* in, const uint32_t* Wb, int64_t ldw, int32_t* S, int64_t lds, int64_t M,
+                          int64_t N, int64_t K, ConvArgs cv, bool fused, BnSignArgs bn, void* stream);
 
 // Validates a convolution and fills the geometry.  M = B*Ho*Wo, K = kh*kw*Cin.
 static int conv_geometry(const uint32_t* in, int64_t B, int64_t H, int64_t W, int64_t Cin, const uint32_t* Wb,
@@ -49,7 +52,7 @@ static int conv_geometry(const uint32_t* in, int64_t B, int64_t H, int64_t W, in
     // Whole channel words only.  With Cin % 128 == 0 the tile loaders move 16-byte groups of 4 channel
     // words; other multiples of 32 are taken word by word, by the LDS-patch kernel alone (same-size
     // stride-1 layers; launch_conv_mfma refuses the rest).  The input is addressed with 32-bit word offsets.
-    if (Cin % 32 != 0 || !mfma_path_supports(K)) return BNN_ERR_UNSUPPORTED;
+    if (Cin % 32 != 0) return BNN_ERR_UNSUPPORTED;
     if (Cin % 128 == 0 && !aligned_to(in, 16)) return BNN_ERR_UNSUPPORTED;
     if (B * H * W * (Cin / 32) > (int64_t(1) << 32) - 1) return BNN_ERR_UNSUPPORTED;
     cv.H = int(H); cv.W = int(W); cv.Cw = int(Cin / 32);
@@ -96,6 +99,7 @@ extern "C" int bnn_conv_xnor(const uint32_t* in, int64_t B, int64_t H, int64_t W
     if (M == 0 || Cout == 0) return BNN_OK;
     if (!S) return BNN_ERR_INVALID_ARG;
     if (!aligned_to(S, 4)) return BNN_ERR_ALIGNMENT;
+    if (!mfma_path_supports(K)) return launch_conv_xnor_valu(in, Wb, ldw, S, lds, M, Cout, K, cv, false, BnSignArgs{}, stream);
     return launch_conv_mfma(in, Wb, ldw, S, lds, M, Cout, K, cv, stream);
 }
 
@@ -112,6 +116,9 @@ extern "C" int bnn_conv_bn_sign_pack(const uint32_t* in, int64_t B, int64_t H, i
     if (M == 0 || Cout == 0) return BNN_OK;
     if (!thr || !flip_bits || !out) return BNN_ERR_INVALID_ARG;
     if (!aligned_to(thr, 4) || !aligned_to(flip_bits, 4) || !aligned_to(out, 4)) return BNN_ERR_ALIGNMENT;
+    if (!mfma_path_supports(K))
+        return launch_conv_xnor_valu(in, Wb, ldw, nullptr, 0, M, Cout, K, cv, true, BnSignArgs{thr, flip_bits, out, ld_out},
+                                     stream);
     return launch_conv_mfma_fused(in, Wb, ldw, M, Cout, K, BnSignArgs{thr, flip_bits, out, ld_out}, cv, stream);
 }
 
@@ -125,7 +132,7 @@ extern "C" int bnn_conv_pool_bn_sign_pack(const uint32_t* in, int64_t B, int64_t
     const int st = conv_geometry(in, B, H, W, Cin, Wb, ldw, Cout, kh, kw, stride, pad, cv, M, K);
     if (st != BNN_OK) return st;
     if (pool < 1 || ld_out < ceil_div(Cout, 32)) return BNN_ERR_INVALID_ARG;
-    if (pool != 2) return BNN_ERR_UNSUPPORTED;
+    if (pool != 2 || !mfma_path_supports(K)) return BNN_ERR_UNSUPPORTED;
     if (M == 0 || Cout == 0) return BNN_OK;
     if (!thr || !flip_bits || !out) return BNN_ERR_INVALID_ARG;
     if (!aligned_to(thr, 4) || !aligned_to(flip_bits, 4) || !aligned_to(out, 4)) return BNN_ERR_ALIGNMENT;

@@ -372,6 +372,9 @@ int launch_bitplane_gemm_mfma(const uint32_t* Xp, int64_t ldx, const uint32_t* B
                               int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream);
 int launch_bitplane_gemm_mfma_fused(const uint32_t* Xp, int64_t ldx, const uint32_t* B, int64_t ldb, int64_t M,
                                     int64_t N, int64_t K, BnSignArgs bn, void* stream);
+// Vector-ALU form for 255 * K beyond the matrix engine's exact range, defined in valu_fallbacks.hip.
+int launch_bitplane_gemm_valu(const uint32_t* Xp, int64_t ldx, const uint32_t* B, int64_t ldb, int32_t* C,
+                              int64_t ldc, int64_t M, int64_t N, int64_t K, bool fused, BnSignArgs bn, void* stream);
 
 template <int TM, int TN, int KT, bool FUSED>
 static void launch_tiled(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
@@ -537,7 +540,8 @@ static int bitplane_gemm_check(const uint32_t* Xp, int64_t ldx, const uint32_t* 
     if (ldx < 8 * kw || ldb < kw) return BNN_ERR_INVALID_ARG;
     if (M > 0 && N > 0 && K > 0 && (!Xp || !B)) return BNN_ERR_INVALID_ARG;
     if (!aligned_to(Xp, 4) || !aligned_to(B, 4)) return BNN_ERR_ALIGNMENT;
-    if (!mfma_planes_path_supports(K) || M > kMaxDim - 1024 || N > kMaxDim - 1024) return BNN_ERR_UNSUPPORTED;
+    if (255 * K > kMaxK) return BNN_ERR_INVALID_ARG;           // the sums must fit int32
+    if (M > kMaxDim - 1024 || N > kMaxDim - 1024) return BNN_ERR_UNSUPPORTED;
     return BNN_OK;
 }
 
@@ -552,6 +556,8 @@ extern "C" int bnn_bitplane_gemm(const uint32_t* Xp, int64_t ldx, const uint32_t
     if (M == 0 || N == 0) return BNN_OK;
     if (!C) return BNN_ERR_INVALID_ARG;
     if (!aligned_to(C, 4)) return BNN_ERR_ALIGNMENT;
+    if (!mfma_planes_path_supports(K))
+        return launch_bitplane_gemm_valu(Xp, ldx, B, ldb, C, ldc, M, N, K, false, BnSignArgs{}, stream);
     return launch_bitplane_gemm_mfma(Xp, ldx, B, ldb, C, ldc, M, N, K, stream);
 }
 
@@ -566,6 +572,9 @@ extern "C" int bnn_bitplane_gemm_bn_sign_pack(const uint32_t* Xp, int64_t ldx, c
     if (M == 0 || N == 0) return BNN_OK;
     if (!thr || !flip_bits || !out) return BNN_ERR_INVALID_ARG;
     if (!aligned_to(thr, 4) || !aligned_to(flip_bits, 4) || !aligned_to(out, 4)) return BNN_ERR_ALIGNMENT;
+    if (!mfma_planes_path_supports(K))
+        return launch_bitplane_gemm_valu(Xp, ldx, B, ldb, nullptr, 0, M, N, K, true,
+                                         BnSignArgs{thr, flip_bits, out, ld_out}, stream);
     return launch_bitplane_gemm_mfma_fused(Xp, ldx, B, ldb, M, N, K, BnSignArgs{thr, flip_bits, out, ld_out},
                                            stream);
 }

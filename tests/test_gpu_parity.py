@@ -348,10 +348,30 @@ def test_bitplane_gemm_at_the_exact_accumulation_limit():
     planes = bnn.pack_bitplanes(torch.from_numpy(X).to(DEV))
     wb = words_to_dev(oracle.pack_bits(np.ascontiguousarray(Wb.T)))
     assert (bnn.bitplane_gemm(planes, wb, K).cpu().numpy() == S).all()
-    with pytest.raises(bnn.BnnError) as e:
-        bnn.bitplane_gemm(torch.zeros((3, 8 * 2057), dtype=torch.int32, device=DEV),
-                          torch.zeros((2, 2057), dtype=torch.int32, device=DEV), 65824)
-    assert e.value.status == 3
+
+
+@pytest.mark.parametrize("K", [65794, 65824, 70001])
+def test_bitplane_gemm_past_the_matrix_engine_limit(K):
+    """One step past 255 * K < 2^24 (and a ragged K further out): the product leaves the matrix engine for the
+    and/popcount kernel; int32 sums and fused bits against the oracle, pad bits of both operands poisoned."""
+    rng = np.random.default_rng(K)
+    M, N = 5, 37
+    X = synth.uint8_input(rng, (M, K))
+    X[0, :] = 255
+    Wb = synth.pm1(rng, (K, N))
+    Wb[:, 0] = 1
+    S = oracle.first_layer_bitplanes(X, Wb)
+    assert S[0, 0] == 255 * K and S[0, 0] >= 1 << 24
+    planes = bnn.pack_bitplanes(torch.from_numpy(X).to(DEV))
+    w_words = poison_pad_bits(oracle.pack_bits(np.ascontiguousarray(Wb.T)), K)
+    if K % 32:
+        planes[:, -8:] |= torch.tensor(np.int32(np.uint32((0xFFFFFFFF << (K % 32)) & 0xFFFFFFFF).view(np.int32)), device=DEV)
+    wb = words_to_dev(w_words)
+    assert (bnn.bitplane_gemm(planes, wb, K).cpu().numpy() == S).all()
+    bn = synth.bn_params(rng, N, 255 * K, adversarial=True)
+    thr, flip = _fold_to_dev(bn, 255 * K)
+    got = bnn.bitplane_gemm_bn_sign_pack(planes, wb, K, thr, flip)
+    assert (words_to_host(got) == oracle.pack_bits(oracle.bn_sign(S, *bn, eps=EPS))).all()
 
 
 def test_xnor_gemm_ldc_and_canary():
@@ -741,6 +761,31 @@ def test_implicit_conv_randomized_geometries(seed):
         thr, flip = _fold_to_dev(bn, kh * kw * Cin)
         bits = words_to_host(bnn.conv_bn_sign_pack(xb, Cin, wb, thr, flip, kh, kw, stride, pad))
         assert (bits == oracle.pack_bits(oracle.bn_sign(S.reshape(-1, Cout), *bn, eps=EPS))).all(), tag
+
+
+@pytest.mark.parametrize("shape", [
+    # B, H, W, Cin, Cout, k, stride, pad: receptive fields of just over 2^24 bits
+    (1, 2, 2, (1 << 24) + 128, 3, 1, 1, 0),
+    (1, 3, 3, 1864192, 2, 3, 1, 1),
+    (1, 4, 3, 1864192 + 32, 5, 3, 2, 1),
+])
+def test_implicit_conv_past_the_matrix_engine_limit(shape):
+    """K = kh*kw*Cin > 2^24 is beyond the exact range of the matrix engine's accumulation: bnn_conv_xnor and
+    bnn_conv_bn_sign_pack take the xor/popcount kernel instead of refusing."""
+    B, H, W, Cin, Cout, k, stride, pad = shape
+    assert k * k * Cin > 1 << 24
+    rng = np.random.default_rng(Cin % 100003)
+    x = synth.pm1(rng, (B, H, W, Cin), 0.7)
+    Wt = synth.pm1(rng, (Cout, k, k, Cin))
+    bn = synth.bn_params(rng, Cout, k * k * Cin, adversarial=True)
+    S = oracle.conv_direct(x, Wt, stride=stride, pad=pad)
+    xb = words_to_dev(_pack_nhwc(x).reshape(-1, Cin // 32)).view(B, H, W, Cin // 32)
+    wb = words_to_dev(oracle.pack_bits(Wt.reshape(Cout, -1)))
+    got = bnn.conv_xnor(xb, Cin, wb, k, k, stride, pad).cpu().numpy()
+    assert (got.reshape(S.shape) == S).all()
+    thr, flip = _fold_to_dev(bn, k * k * Cin)
+    bits = words_to_host(bnn.conv_bn_sign_pack(xb, Cin, wb, thr, flip, k, k, stride, pad))
+    assert (bits == oracle.pack_bits(oracle.bn_sign(S.reshape(-1, Cout), *bn, eps=EPS))).all()
 
 
 @pytest.mark.parametrize("seed", range(3))

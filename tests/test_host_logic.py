@@ -104,7 +104,7 @@ def test_argument_validation_of_the_fused_bitplane_and_conv_entry_points():
     assert lib.bnn_bitplane_gemm(p, 15, p, 2, p, 4, 4, 4, 33, None) == INVALID                    # ldx < 8 * ceil(K/32)
     assert lib.bnn_bitplane_gemm(p, 16, p, 2, p, 3, 4, 4, 33, None) == INVALID                    # ldc < N
     assert lib.bnn_bitplane_gemm(p, 16, p, 2, p, 4, 0, 4, 33, None) == 0
-    assert lib.bnn_bitplane_gemm(p, 8 * 2 ** 12, p, 2 ** 12, p, 4, 4, 4, 2 ** 17, None) == UNSUPPORTED   # 255 K >= 2^24
+    assert lib.bnn_bitplane_gemm(p, 8 * 2 ** 19, p, 2 ** 19, p, 4, 4, 4, 2 ** 24, None) == INVALID       # 255 K beyond int32
     assert lib.bnn_bitplane_gemm_bn_sign_pack(p, 16, p, 2, 4, 4, 33, None, p, p, 1, None) == INVALID
     # implicit-GEMM convolution: geometry, leading dimensions, channel granularity
     assert lib.bnn_conv_xnor(p, 1, 4, 4, 128, p, 36, 4, 3, 3, 0, 1, p, 4, None) == INVALID        # stride 0
