@@ -35,5 +35,6 @@ from .binding import (  # noqa: F401
     KERNEL_MFMA,
     KERNEL_MFMA128,
     KERNEL_MFMA_SHORTK,
+    KERNEL_MFMA_PERSIST,
 )
 from .network import BinaryMLP, BinaryConvLayer, BinaryConvNet  # noqa: F401

@@ -349,7 +349,8 @@ __global__ __launch_bounds__(256) void xnor_gemm_ksplit_kernel(
 // host side
 // ----------------------------------------------------------------------------
 enum { KERNEL_AUTO = 0, KERNEL_NAIVE = 1, KERNEL_TILED128 = 2, KERNEL_KSPLIT = 3, KERNEL_TILED64 = 4,
-       KERNEL_MFMA = 5, KERNEL_MFMA128 = 6, KERNEL_MFMA_SHORTK = 7, KERNEL_LAST = KERNEL_MFMA_SHORTK };
+       KERNEL_MFMA = 5, KERNEL_MFMA128 = 6, KERNEL_MFMA_SHORTK = 7, KERNEL_MFMA_PERSIST = 8,
+       KERNEL_LAST = KERNEL_MFMA_PERSIST };
 
 // Matrix-engine variant, defined in xnor_gemm_mfma.hip.
 bool mfma_path_supports(int64_t K);
@@ -361,6 +362,24 @@ int launch_xnor_gemm_mfma128(const uint32_t* A, int64_t lda, const uint32_t* B, 
                              int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream);
 int launch_xnor_gemm_mfma128_fused(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M,
                                    int64_t N, int64_t K, BnSignArgs bn, void* stream);
+// Persistent form of the 256 x 128 matrix-engine kernel (xnor_gemm_mfma_persist.hip): BNN_ERR_UNSUPPORTED, with
+// nothing launched, for the products it does not take.
+int launch_xnor_gemm_mfma_persist(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
+                                  int64_t ldc, int64_t M, int64_t N, int64_t K, bool fused, BnSignArgs bn,
+                                  void* stream);
+int64_t mfma_persist_slots();
+// Whether the library's own choice of the 256 x 128 kernel should take the persistent form, from measurements
+// on MI355X.  With int32 output it always pays where it applies (the tile's 128 KB of stores drain under the
+// next tile's products: 8192^3 199 -> 191 us, 10000 x 4096 x 4096 78 -> 69 us).  With the fused epilogue a
+// workgroup per tile is the faster form when the tiles fill whole rounds of the chip's slots (successive
+// workgroups of a compute unit drift out of phase, which a fixed tile walk never does: 8192^3 167 vs 173 us),
+// and the persistent form when the last round is partial (10000 x 4096 x 4096: 57.5 -> 55.5 us).
+static bool prefers_persistent(int64_t M, int64_t N, bool fused) {
+    if (!fused) return true;
+    const int64_t slots = mfma_persist_slots();
+    const int64_t rem = (ceil_div(M, 256) * ceil_div(N, 128)) % slots;
+    return rem >= slots / 8 && rem <= slots - slots / 8;
+}
 // Short-K organisation of the matrix-engine kernel, defined in xnor_gemm_mfma_shortk.hip.
 bool mfma_shortk_supports(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t K);
 int launch_xnor_gemm_mfma_shortk(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
@@ -421,7 +440,8 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
                               void* stream) {
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return BNN_ERR_INVALID_ARG;
     if (kernel_id < KERNEL_AUTO || kernel_id > KERNEL_LAST) return BNN_ERR_INVALID_ARG;
-    if ((kernel_id == KERNEL_MFMA || kernel_id == KERNEL_MFMA128) && !mfma_path_supports(K))
+    if ((kernel_id == KERNEL_MFMA || kernel_id == KERNEL_MFMA128 || kernel_id == KERNEL_MFMA_PERSIST) &&
+        !mfma_path_supports(K))
         return BNN_ERR_UNSUPPORTED;
     if (kernel_id == KERNEL_MFMA_SHORTK && !mfma_shortk_supports(A, lda, B, ldb, K)) return BNN_ERR_UNSUPPORTED;
     const int64_t kw = ceil_div(K, 32);
@@ -436,8 +456,8 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int m = int(M), n = int(N), k = int(K);
 
-    if (kernel_id == KERNEL_AUTO)
-        kernel_id = choose_kernel(M, N, K, /*fused=*/false, mfma_shortk_supports(A, lda, B, ldb, K));
+    const bool automatic = kernel_id == KERNEL_AUTO;
+    if (automatic) kernel_id = choose_kernel(M, N, K, /*fused=*/false, mfma_shortk_supports(A, lda, B, ldb, K));
 
     switch (kernel_id) {
         case KERNEL_NAIVE: {
@@ -486,7 +506,14 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
             break;
         }
         case KERNEL_MFMA:
+            // the library's own choice walks several tiles per workgroup where that form applies
+            if (automatic && prefers_persistent(M, N, false)) {
+                const int st = launch_xnor_gemm_mfma_persist(A, lda, B, ldb, C, ldc, M, N, K, false, BnSignArgs{}, stream);
+                if (st != BNN_ERR_UNSUPPORTED) return st;
+            }
             return launch_xnor_gemm_mfma(A, lda, B, ldb, C, ldc, M, N, K, stream);
+        case KERNEL_MFMA_PERSIST:
+            return launch_xnor_gemm_mfma_persist(A, lda, B, ldb, C, ldc, M, N, K, false, BnSignArgs{}, stream);
         case KERNEL_MFMA128:
             return launch_xnor_gemm_mfma128(A, lda, B, ldb, C, ldc, M, N, K, stream);
         case KERNEL_MFMA_SHORTK:
@@ -503,9 +530,11 @@ static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const
                                            int kernel_id, void* stream) {
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return BNN_ERR_INVALID_ARG;
     if (kernel_id != KERNEL_AUTO && kernel_id != KERNEL_TILED128 && kernel_id != KERNEL_TILED64 &&
-        kernel_id != KERNEL_MFMA && kernel_id != KERNEL_MFMA128 && kernel_id != KERNEL_MFMA_SHORTK)
+        kernel_id != KERNEL_MFMA && kernel_id != KERNEL_MFMA128 && kernel_id != KERNEL_MFMA_SHORTK &&
+        kernel_id != KERNEL_MFMA_PERSIST)
         return BNN_ERR_INVALID_ARG;
-    if ((kernel_id == KERNEL_MFMA || kernel_id == KERNEL_MFMA128) && !mfma_path_supports(K))
+    if ((kernel_id == KERNEL_MFMA || kernel_id == KERNEL_MFMA128 || kernel_id == KERNEL_MFMA_PERSIST) &&
+        !mfma_path_supports(K))
         return BNN_ERR_UNSUPPORTED;
     if (kernel_id == KERNEL_MFMA_SHORTK && !mfma_shortk_supports(A, lda, B, ldb, K)) return BNN_ERR_UNSUPPORTED;
     const int64_t kw = ceil_div(K, 32);
@@ -520,9 +549,13 @@ static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const
         return BNN_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const BnSignArgs bn{thr, flip_bits, out, ld_out};
-    if (kernel_id == KERNEL_AUTO)
-        kernel_id = choose_kernel(M, N, K, /*fused=*/true, mfma_shortk_supports(A, lda, B, ldb, K));
+    const bool automatic = kernel_id == KERNEL_AUTO;
+    if (automatic) kernel_id = choose_kernel(M, N, K, /*fused=*/true, mfma_shortk_supports(A, lda, B, ldb, K));
     if (kernel_id == KERNEL_MFMA_SHORTK) return launch_xnor_gemm_mfma_shortk_fused(A, lda, B, ldb, M, N, K, bn, stream);
+    if (kernel_id == KERNEL_MFMA_PERSIST || (automatic && kernel_id == KERNEL_MFMA && prefers_persistent(M, N, true))) {
+        const int st = launch_xnor_gemm_mfma_persist(A, lda, B, ldb, nullptr, 0, M, N, K, true, bn, stream);
+        if (st != BNN_ERR_UNSUPPORTED || kernel_id == KERNEL_MFMA_PERSIST) return st;
+    }
     if (kernel_id == KERNEL_MFMA) return launch_xnor_gemm_mfma_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_MFMA128) return launch_xnor_gemm_mfma128_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_TILED128)

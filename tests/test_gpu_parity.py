@@ -24,6 +24,9 @@ GEMM_KERNELS = {
     "mfma": bnn.KERNEL_MFMA,
     "mfma128": bnn.KERNEL_MFMA128,
 }
+# Kernel id 8, the persistent form of "mfma", takes only large products (more 256 x 128 tiles than the chip
+# holds at once, K a multiple of 512, N a multiple of 128): it has tests of its own and takes part in the
+# 8192^3 and full-batch tests through "auto".
 # The short-K organisation of the matrix-engine kernel takes only 96 < K <= 1152 and operands that
 # allow 16-byte loads, so it has tests of its own instead of a place in the sweeps above.
 
@@ -171,9 +174,9 @@ def test_xnor_gemm_randomized_shapes_strides_alignments_and_kernels(seed):
     base offsets (so both the 16-byte and the word-wise loaders run), poisoned pad bits, every kernel id.
     A kernel either returns the exact product and the exact fused bits, or refuses with UNSUPPORTED."""
     rng = np.random.default_rng(4242 + seed)
-    ids = list(GEMM_KERNELS.values()) + [bnn.KERNEL_MFMA_SHORTK]
+    ids = list(GEMM_KERNELS.values()) + [bnn.KERNEL_MFMA_SHORTK, bnn.KERNEL_MFMA_PERSIST]
     fused_ids = {bnn.KERNEL_AUTO, bnn.KERNEL_TILED128, bnn.KERNEL_TILED64, bnn.KERNEL_MFMA, bnn.KERNEL_MFMA128,
-                 bnn.KERNEL_MFMA_SHORTK}
+                 bnn.KERNEL_MFMA_SHORTK, bnn.KERNEL_MFMA_PERSIST}
     for _case in range(20):
         M, N = (int(np.exp(rng.uniform(0, np.log(600)))) for _ in range(2))
         K = int(np.exp(rng.uniform(0, np.log(5000))))
@@ -420,6 +423,51 @@ def test_dense_layer_config_chained_as_specified(adversarial):
     assert (words_to_host(out) == oracle.pack_bits(a_want)).all()
     fused = bnn.xnor_gemm_bn_sign_pack(a_bits, b_bits, 1024, thr, flip)
     assert (words_to_host(fused) == oracle.pack_bits(a_want)).all()
+
+
+@pytest.mark.parametrize("M,N,K", [
+    (10241, 4096, 1024),     # 41 x 32 tiles on 512 slots; last row tile shifted by 255 rows; 2 K-tiles (the minimum)
+    (10000, 4096, 1536),     # odd number of K-tiles: the LDS buffer parity differs from tile to tile
+    (256 * 33, 2048, 2560),  # whole row tiles, 528 tiles: most workgroups walk one tile, 16 walk two
+    (9000, 8192, 1024),      # 36 x 64 tiles: up to five tiles per workgroup
+])
+def test_persistent_tile_walk_of_the_large_product_kernel(M, N, K):
+    """Products with more 256 x 128 tiles than the chip holds at once take the persistent form of the
+    matrix-engine kernel (a workgroup walks over several tiles, the next tile's first K-tile fetched
+    during the current tile's last): every int32 result and every fused output bit against the oracle."""
+    rng = np.random.default_rng(M + N + K)
+    A, Bm = synth.pm1(rng, (M, K), 0.6), synth.pm1(rng, (K, N))
+    bn = synth.bn_params(rng, N, K, adversarial=True)
+    S, a_next = oracle.dense_layer(A, Bm, bn, eps=EPS)
+    pa = words_to_dev(oracle.pack_bits(A))
+    pb = words_to_dev(oracle.pack_bits(np.ascontiguousarray(Bm.T)))
+    for kernel in (bnn.KERNEL_MFMA_PERSIST, bnn.KERNEL_AUTO):
+        got = bnn.xnor_gemm(pa, pb, K, kernel=kernel).cpu().numpy()
+        bad = np.argwhere(got != S)
+        assert bad.size == 0, f"kernel {kernel}: first mismatch at {bad[0]}"
+    thr, flip = _fold_to_dev(bn, K)
+    want = oracle.pack_bits(a_next)
+    for kernel in (bnn.KERNEL_MFMA_PERSIST, bnn.KERNEL_AUTO):
+        out = torch.full((M, N // 32), 0x55AA55AA, dtype=torch.int32, device=DEV)
+        bnn.xnor_gemm_bn_sign_pack(pa, pb, K, thr, flip, out=out, kernel=kernel)
+        assert (words_to_host(out) == want).all(), f"kernel {kernel}"
+
+
+def test_persistent_kernel_refuses_what_it_does_not_take():
+    """Kernel id 8 answers BNN_ERR_UNSUPPORTED, launching nothing, outside its shapes: K not a multiple of 512,
+    N not a multiple of 128, fewer tiles than resident slots, operands that do not allow 16-byte loads."""
+    def refused(M, N, K, ld_extra=0):
+        kw = (K + 31) // 32
+        a = torch.zeros((M, kw + ld_extra), dtype=torch.int32, device=DEV)[:, :kw]
+        b = torch.zeros((N, kw + ld_extra), dtype=torch.int32, device=DEV)[:, :kw]
+        with pytest.raises(bnn.BnnError) as e:
+            bnn.xnor_gemm(a, b, K, kernel=bnn.KERNEL_MFMA_PERSIST)
+        return e.value.status == 3
+    assert refused(10000, 4096, 4000)
+    assert refused(10000, 4096, 512)
+    assert refused(10000, 4000, 1024)
+    assert refused(4096, 4096, 1024)             # 16 x 32 = 512 tiles: no more than the slots
+    assert refused(10000, 4096, 1024, ld_extra=1)
 
 
 _LARGE_SQUARE = {}
