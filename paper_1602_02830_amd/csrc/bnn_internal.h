@@ -45,4 +45,31 @@ __device__ inline uint32_t or_reduce8(uint32_t v) {
     return v;
 }
 
+// Work split of the streaming kernels' fast path (rows that are whole numbers of 128-element units,
+// 16-byte aligned): a unit is 4 consecutive output words = 128 consecutive elements of one row, taken by
+// an aligned group of 8 lanes; a 256-thread workgroup takes 32 units per step - one 16 KB stretch of a
+// row (units_per_row % 32 == 0) or 32 / units_per_row whole rows (32 % units_per_row == 0) - and
+// `steps` such steps on consecutive rows, so a thread's columns never change.
+struct UnitSplit {
+    int units_per_row;     // cols / 128
+    int slices_per_row;    // workgroups side by side on one row (1 if a workgroup covers whole rows)
+    int rows_per_step;     // rows a workgroup covers per step (1 if a row needs several workgroups)
+    int steps;             // steps per workgroup
+};
+
+// False if the shape does not fit the split.
+inline bool unit_split(int64_t cols, int steps, UnitSplit& us) {
+    if (cols <= 0 || cols % 128 != 0 || cols / 128 > (int64_t(1) << 24)) return false;
+    const int upr = int(cols / 128);
+    if (upr % 32 == 0) {
+        us = UnitSplit{upr, upr / 32, 1, steps};
+        return true;
+    }
+    if (32 % upr == 0) {
+        us = UnitSplit{upr, 1, 32 / upr, steps};
+        return true;
+    }
+    return false;
+}
+
 }  // namespace bnn

@@ -7,7 +7,8 @@
 // nibbles together with three DPP permutes.  A wavefront therefore reads eight
 // 128-byte segments and writes eight words per step, and groups never straddle
 // a row, so rows whose length is not a multiple of 32 cost nothing extra apart
-// from their own partial last word.
+// from their own partial last word.  Rows that are whole numbers of 128 elements
+// take pack_sign_units_kernel (4 words per group, one 16-byte store).
 #include "bnn_internal.h"
 
 namespace bnn {
@@ -81,6 +82,35 @@ __global__ __launch_bounds__(kPackThreads) void pack_sign_kernel(
             if (q == 0 && row_of[u] >= 0) out[row_of[u] * ld_out + word_of[u]] = word;
         }
         advance(row0, w0, pass, kw);
+    }
+}
+
+// Fast path for rows that are whole numbers of 128-element units (see UnitSplit): a group of 8 lanes
+// takes 4 consecutive output words, each of its four 16-byte loads per lane covers 128 contiguous bytes
+// of the group, and lane 0 writes the four words with one 16-byte store, so a wavefront's store is one
+// full 128-byte line instead of four partial ones.
+__global__ __launch_bounds__(kPackThreads) void pack_sign_units_kernel(
+    const float* __restrict__ x, int64_t rows, int64_t ld_x, uint32_t* __restrict__ out, int64_t ld_out,
+    UnitSplit us) {
+    const int q = threadIdx.x & 7, gi = threadIdx.x >> 3;
+    const int64_t block_row = int64_t(blockIdx.x) / us.slices_per_row;
+    const int slice = int(int64_t(blockIdx.x) - block_row * us.slices_per_row);
+    const int unit = us.rows_per_step == 1 ? slice * 32 + gi : gi % us.units_per_row;
+    const int row_in_step = us.rows_per_step == 1 ? 0 : gi / us.units_per_row;
+    for (int i = 0; i < us.steps; ++i) {
+        const int64_t row = (block_row * us.steps + i) * us.rows_per_step + row_in_step;
+        if (row >= rows) break;
+        const float* p = x + row * ld_x + int64_t(unit) * 128 + q * 4;
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4*>(p + 32 * u);
+        uint32_t w[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t nib = ge_zero(v[u].x) | (ge_zero(v[u].y) << 1) | (ge_zero(v[u].z) << 2) | (ge_zero(v[u].w) << 3);
+            w[u] = or_reduce8(nib << (4 * q));
+        }
+        if (q == 0) *reinterpret_cast<uint4*>(out + row * ld_out + int64_t(unit) * 4) = make_uint4(w[0], w[1], w[2], w[3]);
     }
 }
 
@@ -169,9 +199,18 @@ extern "C" int bnn_pack_sign(const float* x, int64_t rows, int64_t cols, int64_t
     const int64_t max_blocks = int64_t(1) << 20;
     if (blocks > max_blocks) blocks = max_blocks;
     const bool vec = aligned_to(x, 16) && (ld_x % 4 == 0);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    UnitSplit us;
+    if (vec && aligned_to(out, 16) && ld_out % 4 == 0 && unit_split(cols, 1, us)) {
+        const int64_t unit_blocks = ceil_div(rows, int64_t(us.rows_per_step) * us.steps) * us.slices_per_row;
+        if (unit_blocks <= kMaxDim) {
+            hipLaunchKernelGGL(pack_sign_units_kernel, dim3(unsigned(unit_blocks)), dim3(kPackThreads), 0, s, x, rows, ld_x,
+                               out, ld_out, us);
+            return check_launch();
+        }
+    }
     const WordStep slice = word_step(groups_per_block, kw);
     const WordStep pass = word_step(blocks * groups_per_block * kPackUnroll, kw);
-    hipStream_t s = static_cast<hipStream_t>(stream);
     if (vec)
         hipLaunchKernelGGL(pack_sign_kernel<true>, dim3(unsigned(blocks)), dim3(kPackThreads), 0, s,
                            x, rows, cols, ld_x, out, ld_out, kw, n_words, slice, pass);

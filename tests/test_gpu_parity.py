@@ -85,6 +85,46 @@ def test_pack_sign_shapes(rows, cols):
     assert (got == want).all()
 
 
+# Rows that are whole numbers of 128 elements take the 4-words-per-group kernels of the Sign packer and of the
+# BatchNorm + Sign epilogue: several rows per workgroup (fewer than 32 units per row), several workgroups per
+# row, row counts that leave the last workgroup partly empty, strided inputs and outputs with guard words.
+UNIT_SHAPES = [(1, 128), (5, 128), (33, 256), (31, 512), (70, 1024), (7, 4096), (3, 8192), (129, 4096), (9, 12288),
+               (65, 384), (2, 128 * 33)]          # the last two fit neither split: the general kernels
+
+
+@pytest.mark.parametrize("rows,cols", UNIT_SHAPES)
+def test_pack_sign_rows_of_whole_128_element_units(rows, cols):
+    rng = np.random.default_rng(rows * 31 + cols)
+    x = synth.real_input(rng, (rows, cols + 8))
+    x[rng.random(x.shape) < 0.05] = 0.0
+    x[rng.random(x.shape) < 0.02] = -0.0
+    xd = torch.from_numpy(x).to(DEV)[:, 4:4 + cols]                 # 16-byte aligned rows, ld_x = cols + 8
+    nw = cols // 32
+    out = torch.full((rows + 2, nw + 4), 0x0BADBEEF, dtype=torch.int32, device=DEV)
+    bnn.pack_sign(xd, out=out[1:rows + 1, :nw])
+    host = words_to_host(out)
+    assert (host[1:rows + 1, :nw] == oracle.pack_bits(oracle.sign(x[:, 4:4 + cols]))).all()
+    host[1:rows + 1, :nw] = 0x0BADBEEF
+    assert (host == 0x0BADBEEF).all()
+
+
+@pytest.mark.parametrize("M,N", UNIT_SHAPES)
+def test_bn_sign_pack_rows_of_whole_128_channel_units(M, N):
+    rng = np.random.default_rng(M * 37 + N)
+    K = 600
+    bn = synth.bn_params(rng, N, K, adversarial=True)
+    S = np.clip(2 * np.rint(rng.normal(0, np.sqrt(K) / 2, (M, N + 8))) + (K % 2), -K, K).astype(np.int32)
+    Sd = torch.from_numpy(S).to(DEV)[:, 4:4 + N]
+    thr, flip = _fold_to_dev(bn, K)
+    nw = N // 32
+    out = torch.full((M + 2, nw + 4), 0x0BADBEEF, dtype=torch.int32, device=DEV)
+    bnn.bn_sign_pack(Sd, thr, flip, out=out[1:M + 1, :nw])
+    host = words_to_host(out)
+    assert (host[1:M + 1, :nw] == oracle.pack_bits(oracle.bn_sign(S[:, 4:4 + N], *bn, eps=EPS))).all()
+    host[1:M + 1, :nw] = 0x0BADBEEF
+    assert (host == 0x0BADBEEF).all()
+
+
 def test_pack_sign_unaligned_and_strided():
     rng = np.random.default_rng(77)
     rows, cols = 37, 203
