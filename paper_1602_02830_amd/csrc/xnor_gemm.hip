@@ -368,18 +368,8 @@ int launch_xnor_gemm_mfma_persist(const uint32_t* A, int64_t lda, const uint32_t
                                   int64_t ldc, int64_t M, int64_t N, int64_t K, bool fused, BnSignArgs bn,
                                   void* stream);
 int64_t mfma_persist_slots();
-// Whether the library's own choice of the 256 x 128 kernel should take the persistent form, from measurements
-// on MI355X.  With int32 output it always pays where it applies (the tile's 128 KB of stores drain under the
-// next tile's products: 8192^3 199 -> 191 us, 10000 x 4096 x 4096 78 -> 69 us).  With the fused epilogue a
-// workgroup per tile is the faster form when the tiles fill whole rounds of the chip's slots (successive
-// workgroups of a compute unit drift out of phase, which a fixed tile walk never does: 8192^3 167 vs 173 us),
-// and the persistent form when the last round is partial (10000 x 4096 x 4096: 57.5 -> 55.5 us).
-static bool prefers_persistent(int64_t M, int64_t N, bool fused) {
-    if (!fused) return true;
-    const int64_t slots = mfma_persist_slots();
-    const int64_t rem = (ceil_div(M, 256) * ceil_div(N, 128)) % slots;
-    return rem >= slots / 8 && rem <= slots - slots / 8;
-}
+bool mfma_persist_supports(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t ldc, int64_t M,
+                           int64_t N, int64_t K, bool fused);
 // Short-K organisation of the matrix-engine kernel, defined in xnor_gemm_mfma_shortk.hip.
 bool mfma_shortk_supports(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t K);
 int launch_xnor_gemm_mfma_shortk(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
@@ -420,11 +410,31 @@ static void launch_tiled(const uint32_t* A, int64_t lda, const uint32_t* B, int6
 // 16-byte loads (short_ok).  Tiny grids go to the
 // 64 x 64 XNOR tiles, which spread over more compute units; skinny outputs go to the K-split kernel;
 // K beyond the exact-fp32 range stays on the vector ALU.
-static int choose_kernel(int64_t M, int64_t N, int64_t K, bool fused, bool short_ok) {
+//
+// The 256 x 128 kernel in persistent form (persist_ok: the product is one it takes, which includes more
+// tiles than the chip's resident slots), kernel time in us, N = 4096, against the best other kernel:
+//   int32 output: its tile's 128 KB of stores drain under the next tile's products.  K = 4096: M = 5120
+//     37.8 vs 39.1, 9216 62.0 vs 69.4, 20000 134.5 vs 149.7; K = 2048: M = 6144 26.8 vs 30.9, 20000 85.9 vs 96.5,
+//     but 8192 (tiles = 2 whole rounds of slots) 42.4 vs 40.0; K = 1024: M = 6144 22.9 vs 24.1, 8192 38.4 vs 28.2.
+//   fused epilogue: a workgroup per tile is the faster form when the tiles fill whole rounds of slots
+//     (successive workgroups of a compute unit drift out of phase, which a fixed tile walk never does:
+//     8192^3 167 vs 173, M = 20000, K = 4096 110.9 vs 115.5) and the persistent form when the last round is
+//     partial (M = 10000, K = 4096 57.5 -> 55.5; M = 6144 36.6 -> 35.6); at 1.25 rounds (M = 5120) the 128 x 128
+//     tiles win (32.2 vs 35.1).
+static int choose_kernel(int64_t M, int64_t N, int64_t K, bool fused, bool short_ok, bool persist_ok) {
     if (!fused && (N <= 16 || M <= 4)) return KERNEL_KSPLIT;
     const int64_t tiles128 = ceil_div(M, 128) * ceil_div(N, 128);
+    const int64_t tiles256 = ceil_div(M, 256) * ceil_div(N, 128);
     if (mfma_path_supports(K)) {
-        if (K >= 4096 && ceil_div(M, 256) * ceil_div(N, 128) >= 1024) return KERNEL_MFMA;
+        if (persist_ok) {
+            const int64_t slots = mfma_persist_slots(), rem = tiles256 % slots;
+            const bool partial_round = rem >= slots / 8 && rem <= slots - slots / 8;
+            if (!fused && (K >= 4096 || (K >= 2048 && rem != 0) || partial_round)) return KERNEL_MFMA_PERSIST;
+            if (fused && K >= 2048 && partial_round && 2 * tiles256 >= 3 * slots) return KERNEL_MFMA_PERSIST;
+        }
+        if (K >= 4096 && tiles256 >= 1024) return KERNEL_MFMA;
+        // fused, K = 2048, N = 4096: M = 8192 27.4 vs 28.0 (128 x 128 tiles), 12288 39.4 vs 40.7, 20000 62.4 vs 65.5
+        if (fused && K >= 2048 && tiles256 >= 768) return KERNEL_MFMA;
         if (short_ok && tiles128 >= 768) return KERNEL_MFMA_SHORTK;
         // Small grids, measured against the 64 x 64 vector-ALU tiles (kernel time, fused / int32):
         // 64 x 1024 x 1024 5.4 vs 6.8 / 7.2 vs 5.8 us, 256 x 1024 x 8192 17.2 vs 26.3 / 18.7 vs 24.6 us,
@@ -456,8 +466,9 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int m = int(M), n = int(N), k = int(K);
 
-    const bool automatic = kernel_id == KERNEL_AUTO;
-    if (automatic) kernel_id = choose_kernel(M, N, K, /*fused=*/false, mfma_shortk_supports(A, lda, B, ldb, K));
+    if (kernel_id == KERNEL_AUTO)
+        kernel_id = choose_kernel(M, N, K, /*fused=*/false, mfma_shortk_supports(A, lda, B, ldb, K),
+                                  mfma_persist_supports(A, lda, B, ldb, ldc, M, N, K, false));
 
     switch (kernel_id) {
         case KERNEL_NAIVE: {
@@ -506,11 +517,6 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
             break;
         }
         case KERNEL_MFMA:
-            // the library's own choice walks several tiles per workgroup where that form applies
-            if (automatic && prefers_persistent(M, N, false)) {
-                const int st = launch_xnor_gemm_mfma_persist(A, lda, B, ldb, C, ldc, M, N, K, false, BnSignArgs{}, stream);
-                if (st != BNN_ERR_UNSUPPORTED) return st;
-            }
             return launch_xnor_gemm_mfma(A, lda, B, ldb, C, ldc, M, N, K, stream);
         case KERNEL_MFMA_PERSIST:
             return launch_xnor_gemm_mfma_persist(A, lda, B, ldb, C, ldc, M, N, K, false, BnSignArgs{}, stream);
@@ -549,13 +555,12 @@ static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const
         return BNN_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const BnSignArgs bn{thr, flip_bits, out, ld_out};
-    const bool automatic = kernel_id == KERNEL_AUTO;
-    if (automatic) kernel_id = choose_kernel(M, N, K, /*fused=*/true, mfma_shortk_supports(A, lda, B, ldb, K));
+    if (kernel_id == KERNEL_AUTO)
+        kernel_id = choose_kernel(M, N, K, /*fused=*/true, mfma_shortk_supports(A, lda, B, ldb, K),
+                                  mfma_persist_supports(A, lda, B, ldb, 0, M, N, K, true));
     if (kernel_id == KERNEL_MFMA_SHORTK) return launch_xnor_gemm_mfma_shortk_fused(A, lda, B, ldb, M, N, K, bn, stream);
-    if (kernel_id == KERNEL_MFMA_PERSIST || (automatic && kernel_id == KERNEL_MFMA && prefers_persistent(M, N, true))) {
-        const int st = launch_xnor_gemm_mfma_persist(A, lda, B, ldb, nullptr, 0, M, N, K, true, bn, stream);
-        if (st != BNN_ERR_UNSUPPORTED || kernel_id == KERNEL_MFMA_PERSIST) return st;
-    }
+    if (kernel_id == KERNEL_MFMA_PERSIST)
+        return launch_xnor_gemm_mfma_persist(A, lda, B, ldb, nullptr, 0, M, N, K, true, bn, stream);
     if (kernel_id == KERNEL_MFMA) return launch_xnor_gemm_mfma_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_MFMA128) return launch_xnor_gemm_mfma128_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_TILED128)

@@ -297,20 +297,27 @@ static int compute_units() {
 // Resident workgroup slots of the persistent kernel: two per compute unit, a whole number of dies.
 int64_t mfma_persist_slots() { return int64_t(2) * compute_units() / 8 * 8; }
 
-// BNN_ERR_UNSUPPORTED (nothing launched) unless the product is one the persistent kernel takes; the
-// caller then launches the general kernel.  fused: bn holds thresholds, flip words and the output.
+// Whether the product is one the persistent kernel takes (ldc: of the int32 output, ignored when fused).
+bool mfma_persist_supports(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t ldc, int64_t M,
+                           int64_t N, int64_t K, bool fused) {
+    constexpr int64_t kTileM = 256, kTileN = 128, kTileK = 32 * kMfmaKT, kMaxLd = int64_t(1) << 22;
+    if (K % kTileK != 0 || K < 2 * kTileK || K > kMfmaMaxAcc || N % kTileN != 0 || M < kTileM) return false;
+    if (!aligned_to(A, 16) || !aligned_to(B, 16) || lda % 4 != 0 || ldb % 4 != 0 || lda >= kMaxLd || ldb >= kMaxLd)
+        return false;
+    if (!fused && ldc >= (int64_t(1) << 28)) return false;       // 32-bit lane offsets in the int32 epilogue
+    const int64_t tiles = ceil_div(M, kTileM) * (N / kTileN);
+    const int64_t slots = mfma_persist_slots();
+    return slots >= 8 && tiles > slots && tiles <= kMaxDim;
+}
+
+// BNN_ERR_UNSUPPORTED (nothing launched) unless the product is one the persistent kernel takes.
+// fused: bn holds thresholds, flip words and the output.
 int launch_xnor_gemm_mfma_persist(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
                                   int64_t ldc, int64_t M, int64_t N, int64_t K, bool fused, BnSignArgs bn,
                                   void* stream) {
-    constexpr int64_t kTileM = 256, kTileN = 128, kTileK = 32 * kMfmaKT, kMaxLd = int64_t(1) << 22;
-    if (K % kTileK != 0 || K < 2 * kTileK || K > kMfmaMaxAcc || N % kTileN != 0 || M < kTileM)
-        return BNN_ERR_UNSUPPORTED;
-    if (!aligned_to(A, 16) || !aligned_to(B, 16) || lda % 4 != 0 || ldb % 4 != 0 || lda >= kMaxLd || ldb >= kMaxLd)
-        return BNN_ERR_UNSUPPORTED;
-    if (!fused && ldc >= (int64_t(1) << 28)) return BNN_ERR_UNSUPPORTED;       // 32-bit lane offsets in the int32 epilogue
-    const int64_t tiles_m = ceil_div(M, kTileM), tiles_n = N / kTileN;
+    if (!mfma_persist_supports(A, lda, B, ldb, ldc, M, N, K, fused)) return BNN_ERR_UNSUPPORTED;
+    const int64_t tiles_m = ceil_div(M, 256), tiles_n = N / 128;
     const int64_t slots = mfma_persist_slots();
-    if (slots < 8 || tiles_m * tiles_n <= slots || tiles_m * tiles_n > kMaxDim) return BNN_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (fused)
         hipLaunchKernelGGL(xnor_gemm_mfma_persist_kernel<true>, dim3(unsigned(slots)), dim3(256), 0, s, A, lda, B, ldb,
