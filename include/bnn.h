@@ -96,13 +96,13 @@ int bnn_xnor_gemm(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb
  * 7 = the same arithmetic organised for short K (a workgroup keeps its 128
  * columns of B in LDS and walks over several 128-row tiles of A; needs
  * 96 < K <= 1152, A and B 16-byte aligned, lda and ldb multiples of 4, else
- * BNN_ERR_UNSUPPORTED), 8 = kernel 5 in persistent form (one workgroup per
+ * BNN_ERR_UNSUPPORTED), 8 = kernel 5 as a tile walk (one workgroup per
  * resident slot walks over several 256x128 tiles, fetching the next tile's
  * first operands under the current tile's last products; needs more tiles
  * than slots, K a multiple of 512 with 1024 <= K <= 2^24, N a multiple of
  * 128, M >= 256, A and B 16-byte aligned, lda and ldb multiples of 4 below
- * 2^22, else BNN_ERR_UNSUPPORTED; what 0 picks for such products).
- * Unknown ids give BNN_ERR_INVALID_ARG. */
+ * 2^22, else BNN_ERR_UNSUPPORTED; what 0 picks when the last round of tiles
+ * would fill only part of the chip).  Unknown ids give BNN_ERR_INVALID_ARG. */
 int bnn_xnor_gemm_kernel(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb,
                          int32_t *C, int64_t ldc, int64_t M, int64_t N, int64_t K,
                          int kernel_id, void *stream);

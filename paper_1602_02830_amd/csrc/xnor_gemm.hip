@@ -362,14 +362,15 @@ int launch_xnor_gemm_mfma128(const uint32_t* A, int64_t lda, const uint32_t* B, 
                              int64_t ldc, int64_t M, int64_t N, int64_t K, void* stream);
 int launch_xnor_gemm_mfma128_fused(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M,
                                    int64_t N, int64_t K, BnSignArgs bn, void* stream);
-// Persistent form of the 256 x 128 matrix-engine kernel (xnor_gemm_mfma_persist.hip): BNN_ERR_UNSUPPORTED, with
-// nothing launched, for the products it does not take.
+// Whole-tile form of the 256 x 128 matrix-engine kernel (xnor_gemm_mfma_persist.hip), launched as a tile walk
+// (walk: one workgroup per resident slot) or with one workgroup per tile: BNN_ERR_UNSUPPORTED, with nothing
+// launched, for the products it does not take.
 int launch_xnor_gemm_mfma_persist(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
-                                  int64_t ldc, int64_t M, int64_t N, int64_t K, bool fused, BnSignArgs bn,
+                                  int64_t ldc, int64_t M, int64_t N, int64_t K, bool fused, bool walk, BnSignArgs bn,
                                   void* stream);
 int64_t mfma_persist_slots();
 bool mfma_persist_supports(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t ldc, int64_t M,
-                           int64_t N, int64_t K, bool fused);
+                           int64_t N, int64_t K, bool fused, bool walk);
 // Short-K organisation of the matrix-engine kernel, defined in xnor_gemm_mfma_shortk.hip.
 bool mfma_shortk_supports(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t K);
 int launch_xnor_gemm_mfma_shortk(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
@@ -411,27 +412,29 @@ static void launch_tiled(const uint32_t* A, int64_t lda, const uint32_t* B, int6
 // 64 x 64 XNOR tiles, which spread over more compute units; skinny outputs go to the K-split kernel;
 // K beyond the exact-fp32 range stays on the vector ALU.
 //
-// The 256 x 128 kernel in persistent form (persist_ok: the product is one it takes, which includes more
-// tiles than the chip's resident slots), kernel time in us, N = 4096, against the best other kernel:
-//   int32 output: its tile's 128 KB of stores drain under the next tile's products.  K = 4096: M = 5120
-//     37.8 vs 39.1, 9216 62.0 vs 69.4, 20000 134.5 vs 149.7; K = 2048: M = 6144 26.8 vs 30.9, 20000 85.9 vs 96.5,
-//     but 8192 (tiles = 2 whole rounds of slots) 42.4 vs 40.0; K = 1024: M = 6144 22.9 vs 24.1, 8192 38.4 vs 28.2.
-//   fused epilogue: a workgroup per tile is the faster form when the tiles fill whole rounds of slots
-//     (successive workgroups of a compute unit drift out of phase, which a fixed tile walk never does:
-//     8192^3 167 vs 173, M = 20000, K = 4096 110.9 vs 115.5) and the persistent form when the last round is
-//     partial (M = 10000, K = 4096 57.5 -> 55.5; M = 6144 36.6 -> 35.6); at 1.25 rounds (M = 5120) the 128 x 128
-//     tiles win (32.2 vs 35.1).
-static int choose_kernel(int64_t M, int64_t N, int64_t K, bool fused, bool short_ok, bool persist_ok) {
+// The 256 x 128 kernel as a tile walk (kernel 8; walk_ok: the product is one it takes, which includes
+// more tiles than the chip's resident slots) against one workgroup per tile, kernel time in us, N = 4096:
+// the walk wins where the last round of tiles is partial (every compute unit gets the same share of it:
+// fused M = 10000, K = 4096 57.5 -> 55.5, M = 6144 36.6 -> 35.6; int32 M = 9216, K = 2048 41.3 -> 39.1) and
+// loses where the tiles fill whole rounds or run for many rounds (the hardware hands a tile to whichever
+// slot frees up first: fused 8192^3 167 vs 173, int32 M = 32768, K = 4096 209 vs 214); at 1.25 rounds with
+// the fused epilogue the 128 x 128 tiles win (M = 5120, K = 4096: 32.2 vs 35.1).
+// With int32 output the 256 x 128 kernel (in its whole-tile form where the product allows it) also takes
+// shorter K and smaller grids than with the fused epilogue, its 128 KB of stores per tile being the larger
+// part of a tile's life: K = 2048, M = 12288 55.0 vs 59.8 (128 x 128 tiles), but M = 8192 42.5 vs 40.0.
+// (whole_ok: the product is one the whole-tile form takes.)
+static int choose_kernel(int64_t M, int64_t N, int64_t K, bool fused, bool short_ok, bool whole_ok, bool walk_ok) {
     if (!fused && (N <= 16 || M <= 4)) return KERNEL_KSPLIT;
     const int64_t tiles128 = ceil_div(M, 128) * ceil_div(N, 128);
     const int64_t tiles256 = ceil_div(M, 256) * ceil_div(N, 128);
     if (mfma_path_supports(K)) {
-        if (persist_ok) {
+        if (walk_ok) {
             const int64_t slots = mfma_persist_slots(), rem = tiles256 % slots;
             const bool partial_round = rem >= slots / 8 && rem <= slots - slots / 8;
-            if (!fused && (K >= 4096 || (K >= 2048 && rem != 0) || partial_round)) return KERNEL_MFMA_PERSIST;
+            if (!fused && partial_round) return KERNEL_MFMA_PERSIST;
             if (fused && K >= 2048 && partial_round && 2 * tiles256 >= 3 * slots) return KERNEL_MFMA_PERSIST;
         }
+        if (!fused && whole_ok && K * tiles256 >= int64_t(4096) * 768) return KERNEL_MFMA;
         if (K >= 4096 && tiles256 >= 1024) return KERNEL_MFMA;
         // fused, K = 2048, N = 4096: M = 8192 27.4 vs 28.0 (128 x 128 tiles), 12288 39.4 vs 40.7, 20000 62.4 vs 65.5
         if (fused && K >= 2048 && tiles256 >= 768) return KERNEL_MFMA;
@@ -468,7 +471,8 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
 
     if (kernel_id == KERNEL_AUTO)
         kernel_id = choose_kernel(M, N, K, /*fused=*/false, mfma_shortk_supports(A, lda, B, ldb, K),
-                                  mfma_persist_supports(A, lda, B, ldb, ldc, M, N, K, false));
+                                  mfma_persist_supports(A, lda, B, ldb, ldc, M, N, K, false, false),
+                                  mfma_persist_supports(A, lda, B, ldb, ldc, M, N, K, false, true));
 
     switch (kernel_id) {
         case KERNEL_NAIVE: {
@@ -516,10 +520,14 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
             }
             break;
         }
-        case KERNEL_MFMA:
+        case KERNEL_MFMA: {
+            // Whole-tile products take the form whose int32 stores go to scalar row bases, one workgroup per tile.
+            const int st = launch_xnor_gemm_mfma_persist(A, lda, B, ldb, C, ldc, M, N, K, false, false, BnSignArgs{}, stream);
+            if (st != BNN_ERR_UNSUPPORTED) return st;
             return launch_xnor_gemm_mfma(A, lda, B, ldb, C, ldc, M, N, K, stream);
+        }
         case KERNEL_MFMA_PERSIST:
-            return launch_xnor_gemm_mfma_persist(A, lda, B, ldb, C, ldc, M, N, K, false, BnSignArgs{}, stream);
+            return launch_xnor_gemm_mfma_persist(A, lda, B, ldb, C, ldc, M, N, K, false, true, BnSignArgs{}, stream);
         case KERNEL_MFMA128:
             return launch_xnor_gemm_mfma128(A, lda, B, ldb, C, ldc, M, N, K, stream);
         case KERNEL_MFMA_SHORTK:
@@ -557,10 +565,11 @@ static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const
     const BnSignArgs bn{thr, flip_bits, out, ld_out};
     if (kernel_id == KERNEL_AUTO)
         kernel_id = choose_kernel(M, N, K, /*fused=*/true, mfma_shortk_supports(A, lda, B, ldb, K),
-                                  mfma_persist_supports(A, lda, B, ldb, 0, M, N, K, true));
+                                  mfma_persist_supports(A, lda, B, ldb, 0, M, N, K, true, false),
+                                  mfma_persist_supports(A, lda, B, ldb, 0, M, N, K, true, true));
     if (kernel_id == KERNEL_MFMA_SHORTK) return launch_xnor_gemm_mfma_shortk_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_MFMA_PERSIST)
-        return launch_xnor_gemm_mfma_persist(A, lda, B, ldb, nullptr, 0, M, N, K, true, bn, stream);
+        return launch_xnor_gemm_mfma_persist(A, lda, B, ldb, nullptr, 0, M, N, K, true, true, bn, stream);
     if (kernel_id == KERNEL_MFMA) return launch_xnor_gemm_mfma_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_MFMA128) return launch_xnor_gemm_mfma128_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_TILED128)

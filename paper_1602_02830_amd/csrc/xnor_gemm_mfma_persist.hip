@@ -1,26 +1,29 @@
-// Persistent form of the bits-in, matrix-engine-inside kernel for the large products of Alg. 4
+// Whole-tile form of the bits-in, matrix-engine-inside kernel for the large products of Alg. 4
 // (a_k = XnorDotProduct(a^b_{k-1}, W^b_k), Sec. 4 Eq. (5); with FUSED also a^b_k = Sign(BatchNorm(a_k))).
 //
 // Arithmetic, operand widening, LDS layout and epilogues are those of xnor_gemm_mfma.hip (256 x 128
-// tiles, 2 x 2 wavefronts of 4 x 2 accumulator blocks).  What differs is the life of a workgroup: the
-// grid is one workgroup per resident slot of the chip (two per compute unit), and a workgroup walks
-// over the output tiles blockIdx.x, blockIdx.x + gridDim.x, ... (the stride is a multiple of the
-// number of dies, so a workgroup's tiles keep to one die's L2 panel).  During the last K-tile of an
-// output tile the first K-tile of the next one is fetched, and it is staged before the epilogue
-// runs: a tile no longer starts with an exposed global load, no workgroup is launched per tile, and
-// the epilogue's stores drain under the next tile's K loop.
-//
-// It takes only the shapes where that pays and nothing has to be checked per element (the launcher
-// refuses the rest, which stay with xnor_gemm_mfma.hip):
+// tiles, 2 x 2 wavefronts of 4 x 2 accumulator blocks).  It takes only products where nothing has to be
+// checked per element (the launcher refuses the rest, which stay with xnor_gemm_mfma.hip):
 //   - K a multiple of 512 (whole K-tiles: no masking, no partial loads), 1024 <= K <= 2^24;
 //   - N a multiple of 128 (whole column tiles), M >= 256; the last row tile is SHIFTED up to end at
 //     row M instead of being padded, so every tile row exists (rows shared with the previous tile
 //     are computed twice and written twice with the same values);
-//   - operands that allow 16-byte loads, leading dimensions below 2^22 words;
-//   - more tiles than resident slots.
-// With whole tiles a staging thread's loads are `uniform tile address + constant 32-bit lane
-// offset`: the per-lane 64-bit row pointers of the general kernel (12 registers, recomputed per
-// tile) are gone, which is what lets the tile loop fit the register budget of two wavefronts per SIMD.
+//   - operands that allow 16-byte loads, leading dimensions below 2^22 words.
+// With whole tiles every global address is `wavefront-uniform tile address + constant 32-bit lane offset`:
+// the per-lane 64-bit row pointers of the general kernel (12 registers, recomputed per tile) and the
+// 64-bit address per int32 store are gone.  The int32 epilogue is where that shows: 128 stores per
+// lane at scalar bases (8192^3 199 -> 190 us with one workgroup per tile).
+//
+// A workgroup walks over the output tiles blockIdx.x, blockIdx.x + gridDim.x, ... (the stride is kept a
+// multiple of the number of dies, so a workgroup's tiles keep to one die's L2 panel); during the last
+// K-tile of an output tile the first K-tile of the next one is fetched, and it is staged before the
+// epilogue runs.  Two launch shapes:
+//   - one workgroup per tile (grid = tiles, no walk): the hardware hands tiles to whichever slot frees
+//     up first, which balances a long run of tiles better than any fixed assignment (32768 x 4096 x 4096
+//     int32: 209 us vs 214 us walked);
+//   - one workgroup per resident slot (two per compute unit) walking over the tiles: the better form when
+//     the last round of tiles is partial, because every compute unit then gets the same share of it
+//     (10000 x 4096 x 4096 fused: 57.5 -> 55.5 us; 9216 x 4096 x 2048 int32: 41.3 -> 39.1 us).
 #include "bnn_internal.h"
 #include "gemm_staging.h"
 #include "mfma_fp4.h"
@@ -297,9 +300,10 @@ static int compute_units() {
 // Resident workgroup slots of the persistent kernel: two per compute unit, a whole number of dies.
 int64_t mfma_persist_slots() { return int64_t(2) * compute_units() / 8 * 8; }
 
-// Whether the product is one the persistent kernel takes (ldc: of the int32 output, ignored when fused).
+// Whether the product is one this kernel takes (ldc: of the int32 output, ignored when fused); walk: as a
+// tile walk of one workgroup per resident slot, which needs more tiles than slots.
 bool mfma_persist_supports(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t ldc, int64_t M,
-                           int64_t N, int64_t K, bool fused) {
+                           int64_t N, int64_t K, bool fused, bool walk) {
     constexpr int64_t kTileM = 256, kTileN = 128, kTileK = 32 * kMfmaKT, kMaxLd = int64_t(1) << 22;
     if (K % kTileK != 0 || K < 2 * kTileK || K > kMfmaMaxAcc || N % kTileN != 0 || M < kTileM) return false;
     if (!aligned_to(A, 16) || !aligned_to(B, 16) || lda % 4 != 0 || ldb % 4 != 0 || lda >= kMaxLd || ldb >= kMaxLd)
@@ -307,17 +311,18 @@ bool mfma_persist_supports(const uint32_t* A, int64_t lda, const uint32_t* B, in
     if (!fused && ldc >= (int64_t(1) << 28)) return false;       // 32-bit lane offsets in the int32 epilogue
     const int64_t tiles = ceil_div(M, kTileM) * (N / kTileN);
     const int64_t slots = mfma_persist_slots();
-    return slots >= 8 && tiles > slots && tiles <= kMaxDim;
+    return tiles <= kMaxDim && (!walk || (slots >= 8 && tiles > slots));
 }
 
-// BNN_ERR_UNSUPPORTED (nothing launched) unless the product is one the persistent kernel takes.
-// fused: bn holds thresholds, flip words and the output.
+// BNN_ERR_UNSUPPORTED (nothing launched) unless the product is one this kernel takes.
+// fused: bn holds thresholds, flip words and the output.  walk: one workgroup per resident slot walking
+// over the tiles, else one workgroup per tile.
 int launch_xnor_gemm_mfma_persist(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
-                                  int64_t ldc, int64_t M, int64_t N, int64_t K, bool fused, BnSignArgs bn,
+                                  int64_t ldc, int64_t M, int64_t N, int64_t K, bool fused, bool walk, BnSignArgs bn,
                                   void* stream) {
-    if (!mfma_persist_supports(A, lda, B, ldb, ldc, M, N, K, fused)) return BNN_ERR_UNSUPPORTED;
+    if (!mfma_persist_supports(A, lda, B, ldb, ldc, M, N, K, fused, walk)) return BNN_ERR_UNSUPPORTED;
     const int64_t tiles_m = ceil_div(M, 256), tiles_n = N / 128;
-    const int64_t slots = mfma_persist_slots();
+    const int64_t slots = walk ? mfma_persist_slots() : tiles_m * tiles_n;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (fused)
         hipLaunchKernelGGL(xnor_gemm_mfma_persist_kernel<true>, dim3(unsigned(slots)), dim3(256), 0, s, A, lda, B, ldb,
