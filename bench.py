@@ -104,6 +104,50 @@ def time_launches(fn, iters, warmup=2, batches=10):
             "launches_per_batch": iters}
 
 
+class HipEvent:
+    """A HIP event created without the system-scope release that a default event record carries
+    (hipEventDisableSystemFence): timing events inside the timed region then cost the step less.  Recorded
+    on the raw stream handle torch launches on.  record()/elapsed_time() mirror torch.cuda.Event."""
+    _hip = None
+    DISABLE_SYSTEM_FENCE = 0x20000000
+
+    def __init__(self):
+        import ctypes
+        if HipEvent._hip is None:
+            hip = ctypes.CDLL("libamdhip64.so")
+            hip.hipEventCreateWithFlags.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint]
+            hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+            hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+            hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+            hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+            HipEvent._hip = hip
+        self._ct = ctypes
+        self.handle = ctypes.c_void_p()
+        rc = HipEvent._hip.hipEventCreateWithFlags(ctypes.byref(self.handle), HipEvent.DISABLE_SYSTEM_FENCE)
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreateWithFlags failed: {rc}")
+
+    def record(self):
+        import torch
+        rc = HipEvent._hip.hipEventRecord(self.handle, self._ct.c_void_p(torch.cuda.current_stream().cuda_stream))
+        if rc != 0:
+            raise RuntimeError(f"hipEventRecord failed: {rc}")
+
+    def elapsed_time(self, end):
+        ms = self._ct.c_float()
+        HipEvent._hip.hipEventSynchronize(end.handle)
+        rc = HipEvent._hip.hipEventElapsedTime(self._ct.byref(ms), self.handle, end.handle)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return float(ms.value)
+
+    def __del__(self):
+        try:
+            HipEvent._hip.hipEventDestroy(self.handle)
+        except Exception:
+            pass
+
+
 _clock_probe = None
 
 
@@ -251,6 +295,11 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=10000, help="images the CPU oracle is timed on")
     ap.add_argument("--cpu-gemm-rows", type=int, default=8192,
                     help="rows of the 8192^3 product the CPU oracle is timed on (and every element of which is compared)")
+    ap.add_argument("--event-pairs", type=int, default=None,
+                    help="timed steps on which the dominant kernel's launches are bracketed by events "
+                         "(default: max(10, steps / 10), at most every step)")
+    ap.add_argument("--torch-events", action="store_true",
+                    help="bracket with torch.cuda.Event (default flags) instead of HIP events without the system fence")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic, for scaling profiler byte counters)")
     ap.add_argument("--gemm", default=None, metavar="M,N,K",
@@ -309,16 +358,18 @@ def main():
     # them (only the second one when a BN+Sign launch sits in between); on the other steps nothing is
     # recorded, because each event record drains the queue and costs the step several microseconds.
     dominant_layers = [1, 2] if fused else [2]
-    n_pairs = min(args.steps, max(10, args.steps // 10))
-    event_steps = set(int(round(v)) for v in np.linspace(0, args.steps - 1, n_pairs))
-    pairs = []
+    n_pairs = min(args.steps, args.event_pairs if args.event_pairs is not None else max(10, args.steps // 10))
+    event_steps = set(int(round(v)) for v in np.linspace(0, args.steps - 1, n_pairs)) if n_pairs else set()
+    # The events are created before the timed region; inside it they are only recorded.
+    make_event = (lambda: torch.cuda.Event(enable_timing=True)) if args.torch_events else HipEvent
+    pairs = [{"start": make_event(), "end": make_event()} for _ in range(len(event_steps))]
+    next_pair = 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         if i in event_steps:
-            ev = {}
-            net.forward(xd, span_events=(dominant_layers[0], dominant_layers[-1], ev))
-            pairs.append(ev)
+            net.forward(xd, span_events=(dominant_layers[0], dominant_layers[-1], pairs[next_pair]))
+            next_pair += 1
         else:
             net.forward(xd)
     torch.cuda.synchronize()

@@ -81,8 +81,8 @@ class BinaryMLP:
         """x: float32 device tensor [batch][K_0].  Returns the int32 scores [batch][N_last].
 
         span_events: optional (first_layer, last_layer, dict); one event is recorded on the current
-        stream before the GEMM launch of first_layer and one right after that of last_layer,
-        stored as dict["start"], dict["end"].
+        stream before the GEMM launch of first_layer and one right after that of last_layer:
+        dict["start"], dict["end"] (created here unless the caller put events there already).
         """
         if self.input_uint8:
             B.pack_bitplanes(x, out=self.a_bits[0])
@@ -91,7 +91,8 @@ class BinaryMLP:
         n_layers = len(self.w_bits)
         for l in range(n_layers):
             if span_events is not None and l == span_events[0]:
-                span_events[2]["start"] = torch.cuda.Event(enable_timing=True)
+                if "start" not in span_events[2]:
+                    span_events[2]["start"] = torch.cuda.Event(enable_timing=True)
                 span_events[2]["start"].record()
             hidden = l + 1 < n_layers
             if self.input_uint8 and l == 0:
@@ -107,7 +108,8 @@ class BinaryMLP:
                 B.xnor_gemm(self.a_bits[l], self.w_bits[l], self.K[l], out=self.s[l],
                             kernel=self.kernel if hidden else B.KERNEL_AUTO)
             if span_events is not None and l == span_events[1]:
-                span_events[2]["end"] = torch.cuda.Event(enable_timing=True)
+                if "end" not in span_events[2]:
+                    span_events[2]["end"] = torch.cuda.Event(enable_timing=True)
                 span_events[2]["end"].record()
             if hidden and not self.fused:
                 B.bn_sign_pack(self.s[l], self.thr[l], self.flip[l], out=self.a_bits[l + 1])

@@ -1142,6 +1142,41 @@ def test_mlp_forward_captured_in_a_hip_graph_replays_bit_exact():
         assert (net.s[-1].cpu().numpy() == oracle.mlp_forward(x0, weights, bns, eps=EPS)["s"][-1]).all()
 
 
+def test_tile_walk_kernel_captured_in_a_hip_graph_replays_bit_exact():
+    """The tile walk of the large-product kernel keeps no state between launches (no counters, no scratch
+    memory): captured in a HIP graph, every replay on new inputs, with eager launches of the same kernel in
+    between, gives the oracle's bits."""
+    M, N, K = 10000, 4096, 1024
+    rng = np.random.default_rng(31)
+    Bm = synth.pm1(rng, (K, N))
+    bn = synth.bn_params(rng, N, K, adversarial=True)
+    pb = words_to_dev(oracle.pack_bits(np.ascontiguousarray(Bm.T)))
+    thr, flip = _fold_to_dev(bn, K)
+    a_static = torch.zeros((M, K // 32), dtype=torch.int32, device=DEV)
+    out = torch.zeros((M, N // 32), dtype=torch.int32, device=DEV)
+    launch = lambda: bnn.xnor_gemm_bn_sign_pack(a_static, pb, K, thr, flip, out=out, kernel=bnn.KERNEL_MFMA_PERSIST)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        launch()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        launch()
+    for replay in range(3):
+        A = synth.pm1(rng, (M, K), 0.3 + 0.2 * replay)
+        want = oracle.pack_bits(oracle.dense_layer(A, Bm, bn, eps=EPS)[1])
+        a_static.copy_(words_to_dev(oracle.pack_bits(A)))
+        out.fill_(0x3C3C3C3C)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert (words_to_host(out) == want).all(), f"replay {replay}"
+        out.fill_(0)
+        launch()                                     # eager, between the replays
+        torch.cuda.synchronize()
+        assert (words_to_host(out) == want).all(), f"eager launch after replay {replay}"
+
+
 def test_mlp_full_batch_every_row():
     """Batch 10000 with separate GEMM and BN+Sign launches: every int32 pre-activation and every packed
     activation of all 10000 rows against the oracle."""

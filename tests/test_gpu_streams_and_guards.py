@@ -81,6 +81,21 @@ def _cases():
                           lambda o, kid=kid: bnn.xnor_gemm_bn_sign_pack(pa, pb, K, thr, flip, out=o, kernel=kid),
                           oracle.pack_bits(a_next).view(np.int32)))
 
+    # the whole-tile 256 x 128 kernel as a tile walk (kernel id 8) needs more tiles than the chip holds at once
+    Mw, Nw, Kw = 10241, 4096, 1024
+    Aw, Bw = synth.pm1(rng, (Mw, Kw)), synth.pm1(rng, (Kw, Nw))
+    bnw = synth.bn_params(rng, Nw, Kw, adversarial=True)
+    Sw, aw_next = oracle.dense_layer(Aw, Bw, bnw, eps=EPS)
+    paw, pbw = _dev_words(oracle.pack_bits(Aw)), _dev_words(oracle.pack_bits(np.ascontiguousarray(Bw.T)))
+    thrw, flipw = _fold(bnw, Kw)
+    cases.append(("xnor_gemm[mfma_walk]", lambda: Guarded(Mw, Nw),
+                  lambda o: bnn.xnor_gemm(paw, pbw, Kw, out=o, kernel=bnn.KERNEL_MFMA_PERSIST), Sw))
+    cases.append(("xnor_gemm[mfma_whole_tiles]", lambda: Guarded(Mw, Nw),
+                  lambda o: bnn.xnor_gemm(paw, pbw, Kw, out=o, kernel=bnn.KERNEL_MFMA), Sw))
+    cases.append(("xnor_gemm_bn_sign_pack[mfma_walk]", lambda: Guarded(Mw, Nw // 32),
+                  lambda o: bnn.xnor_gemm_bn_sign_pack(paw, pbw, Kw, thrw, flipw, out=o, kernel=bnn.KERNEL_MFMA_PERSIST),
+                  oracle.pack_bits(aw_next).view(np.int32)))
+
     # bnn_bn_sign_pack
     Sd = torch.from_numpy(S).to(DEV)
     cases.append(("bn_sign_pack", lambda: Guarded(M, (N + 31) // 32), lambda o: bnn.bn_sign_pack(Sd, thr, flip, out=o),
@@ -158,6 +173,7 @@ def cases():
 CASE_NAMES = ["pack_sign"] + \
     [f"xnor_gemm[{k}]" for k in ("auto", "naive", "tiled128", "ksplit", "tiled64", "mfma", "mfma128", "mfma_shortk")] + \
     [f"xnor_gemm_bn_sign_pack[{k}]" for k in ("auto", "tiled128", "tiled64", "mfma", "mfma128", "mfma_shortk")] + \
+    ["xnor_gemm[mfma_walk]", "xnor_gemm[mfma_whole_tiles]", "xnor_gemm_bn_sign_pack[mfma_walk]"] + \
     ["bn_sign_pack", "pack_bitplanes", "bitplane_gemm", "bitplane_gemm_bn_sign_pack", "conv_im2col_pack", "conv_xnor",
      "conv_bn_sign_pack", "conv_pool_bn_sign_pack", "maxpool_bits", "gemm_i8_mfma"]
 
