@@ -5,10 +5,24 @@ One step = one forward pass of the fully binarized MNIST-shaped MLP
 (784 -> 4096 -> 4096 -> 4096 -> 10, batch 10000) through the library:
 Sign+pack of the real input, four XNOR-popcount GEMMs, three BatchNorm+Sign
 epilogues.  Inputs, weights and thresholds are resident in HBM before the timed
-region; the value is images/s.  The same run also reports, outside the timed
-region, the 8192^3 binary GEMM (XNOR kernel and int8-MFMA variant) in binary
-TOP/s (2*M*N*K per second), the streaming kernels in GB/s, the conv layers,
-and the CPU oracle timed on the host cores on a bounded sample.
+region; the value is images/s over exactly --steps steps between two device
+synchronisations.
+
+Protocol: --warmup steps, then steps keep running until the step time has
+settled (at least 50 ms, two 10-step windows within 2 %), so that a short run
+measures the same clocks as a long one.  The dominant kernel is timed inside
+the timed region by at least 10 pre-created pairs of HIP events (created
+without the system-scope fence, so that recording them costs the step nothing)
+spread over the steps; the roofline uses the median pair.  A one-wavefront
+probe reads the shader clock while that kernel runs, for the fraction at the
+clock the box actually held.  Outside the timed region the same run reports
+the 8192^3 binary GEMM (matrix-engine and vector-ALU kernels, int8-MFMA
+variant) in binary TOP/s (2*M*N*K per second), the streaming kernels in GB/s,
+the conv layers, and the CPU oracle timed on the host cores: the whole batch
+of the step, and the 8192^3 product with every element compared.
+
+Single workloads: --gemm M,N,K [--fused] [--kernel ...], --stream NAME,
+--conv LAYER (back-to-back launches, 10 batches of --steps, median batch).
 
 Prints exactly one JSON line on stdout; progress goes to stderr.
 """
@@ -35,17 +49,15 @@ PEAK_BINARY_TOPS = PEAK_LANE_OPS / 2 * 64 / 1e12          # ~1258.3
 PEAK_HBM_GBS = 8000.0
 PEAK_I8_MFMA_TOPS = 5000.0                                # dense int8, 2*M*N*K counting
 PEAK_FP4_MFMA_TFLOPS = 10100.0                            # dense fp4/fp6 MFMA, 2*M*N*K counting
-# HBM bytes per launch of the dominant kernel (fetched + written), from the FETCH_SIZE / WRITE_SIZE counter
-# runs summarised in profiles/xnor_gemm_mfma_mlp_batch10000.txt and profiles/xnor_gemm_tiled128_mlp_batch10000.txt.
 WARM_SECONDS = 0.05
 # HBM bytes per launch of the dominant kernel (fetched + written): rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this script, scaled by the same counters over a plain 1 GiB copy.  They cannot be read from inside the run, so the
 # figure is carried here together with the file that holds the counter run it comes from.
 PROFILED_TRAFFIC = {
-    ("mfma", True): (23.1e6 + 5.2e6, "profiles/xnor_gemm_mfma_mlp_batch10000.txt"),
+    ("mfma", True): (23.15e6 + 5.24e6, "profiles/xnor_gemm_mfma_mlp_batch10000.txt"),
     ("valu", False): (32.9e6 + 166.4e6, "profiles/xnor_gemm_tiled128_mlp_batch10000.txt"),
-    "xnor_gemm_8192_mfma": (None, "profiles/xnor_gemm_8192_mfma_vs_valu.txt"),
-    "xnor_gemm_8192_valu": (None, "profiles/xnor_gemm_8192_mfma_vs_valu.txt"),
+    "xnor_gemm_8192_mfma": (58.2e6 + 268.8e6, "profiles/xnor_gemm_8192_mfma_vs_valu.txt"),
+    "xnor_gemm_8192_valu": (82.4e6 + 272.6e6, "profiles/xnor_gemm_8192_mfma_vs_valu.txt"),
 }
 NOMINAL_CLOCK_HZ = 2.4e9
 
@@ -358,7 +370,7 @@ def main():
     # them (only the second one when a BN+Sign launch sits in between); on the other steps nothing is
     # recorded, because each event record drains the queue and costs the step several microseconds.
     dominant_layers = [1, 2] if fused else [2]
-    n_pairs = min(args.steps, args.event_pairs if args.event_pairs is not None else max(10, args.steps // 10))
+    n_pairs = max(1, min(args.steps, args.event_pairs if args.event_pairs is not None else max(10, args.steps // 10)))
     event_steps = set(int(round(v)) for v in np.linspace(0, args.steps - 1, n_pairs)) if n_pairs else set()
     # The events are created before the timed region; inside it they are only recorded.
     make_event = (lambda: torch.cuda.Event(enable_timing=True)) if args.torch_events else HipEvent
@@ -490,7 +502,7 @@ def main():
     other = {
         "xnor_gemm_8192_mfma": gemm_roofline(
             "xnor_gemm_8192_mfma", "mfma", t_auto, ops, clk_auto,
-            {"kernel": "bnn_xnor_gemm 8192^3, int32 out, library's choice = xnor_gemm_mfma_kernel<4,2>",
+            {"kernel": "bnn_xnor_gemm 8192^3, int32 out, library's choice = xnor_gemm_mfma_persist_kernel<false> launched one workgroup per 256x128 tile",
              "binary_tops": ops / t_auto["median"] / 1e9,
              "vs_integer_valu_ceiling": ops / t_auto["median"] / 1e9 / PEAK_BINARY_TOPS}),
         "xnor_gemm_8192_valu": gemm_roofline(

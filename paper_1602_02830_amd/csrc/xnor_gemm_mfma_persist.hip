@@ -59,7 +59,7 @@ __device__ inline void persist_epilogue_int32(const v16f (&acc)[WM][WN], const i
                                               int32_t* __restrict__ C, int64_t ldc, int K, int row0, int col0, int wm,
                                               int wn, int fr, int fh) {
     static_assert(WN == 2, "two column blocks of 32 int32 = 128 bytes apart");
-    const uint32_t lane_off = (uint32_t(4 * fh) * uint32_t(ldc) + uint32_t(fr)) * 4u;      // ldc < 2^28
+    const uint32_t lane_off = (uint32_t(4 * fh) * uint32_t(ldc) + uint32_t(fr)) * 4u;      // ldc < 2^27
     int base_n[WN];
 #pragma unroll
     for (int j = 0; j < WN; ++j) base_n[j] = K - pop_b[wn * 32 * WN + j * 32 + fr];
@@ -308,7 +308,7 @@ bool mfma_persist_supports(const uint32_t* A, int64_t lda, const uint32_t* B, in
     if (K % kTileK != 0 || K < 2 * kTileK || K > kMfmaMaxAcc || N % kTileN != 0 || M < kTileM) return false;
     if (!aligned_to(A, 16) || !aligned_to(B, 16) || lda % 4 != 0 || ldb % 4 != 0 || lda >= kMaxLd || ldb >= kMaxLd)
         return false;
-    if (!fused && ldc >= (int64_t(1) << 28)) return false;       // 32-bit lane offsets in the int32 epilogue
+    if (!fused && ldc >= (int64_t(1) << 27)) return false;       // 32-bit lane byte offsets (16 * ldc + 124) in the int32 epilogue
     const int64_t tiles = ceil_div(M, kTileM) * (N / kTileN);
     const int64_t slots = mfma_persist_slots();
     return tiles <= kMaxDim && (!walk || (slots >= 8 && tiles > slots));
