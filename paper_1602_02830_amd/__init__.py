@@ -36,5 +36,6 @@ from .binding import (  # noqa: F401
     KERNEL_MFMA128,
     KERNEL_MFMA_SHORTK,
     KERNEL_MFMA_PERSIST,
+    KERNEL_MFMA_BIG,
 )
 from .network import BinaryMLP, BinaryConvLayer, BinaryConvNet  # noqa: F401

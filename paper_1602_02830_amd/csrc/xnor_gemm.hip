@@ -350,7 +350,7 @@ __global__ __launch_bounds__(256) void xnor_gemm_ksplit_kernel(
 // ----------------------------------------------------------------------------
 enum { KERNEL_AUTO = 0, KERNEL_NAIVE = 1, KERNEL_TILED128 = 2, KERNEL_KSPLIT = 3, KERNEL_TILED64 = 4,
        KERNEL_MFMA = 5, KERNEL_MFMA128 = 6, KERNEL_MFMA_SHORTK = 7, KERNEL_MFMA_PERSIST = 8,
-       KERNEL_LAST = KERNEL_MFMA_PERSIST };
+       KERNEL_MFMA_BIG = 9, KERNEL_LAST = KERNEL_MFMA_BIG };
 
 // Matrix-engine variant, defined in xnor_gemm_mfma.hip.
 bool mfma_path_supports(int64_t K);
@@ -371,6 +371,13 @@ int launch_xnor_gemm_mfma_persist(const uint32_t* A, int64_t lda, const uint32_t
 int64_t mfma_persist_slots();
 bool mfma_persist_supports(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t ldc, int64_t M,
                            int64_t N, int64_t K, bool fused, bool walk);
+// 256 x 256-tile form of the fused product for one wavefront per SIMD (xnor_gemm_mfma_big.hip), one workgroup
+// per compute unit: BNN_ERR_UNSUPPORTED, with nothing launched, for the products it does not take.
+int launch_xnor_gemm_mfma_big(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M, int64_t N,
+                              int64_t K, BnSignArgs bn, void* stream);
+bool mfma_big_supports(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M, int64_t N,
+                       int64_t K, const BnSignArgs& bn);
+bool mfma_big_prefers(int64_t M, int64_t N);
 // Short-K organisation of the matrix-engine kernel, defined in xnor_gemm_mfma_shortk.hip.
 bool mfma_shortk_supports(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t K);
 int launch_xnor_gemm_mfma_shortk(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
@@ -423,8 +430,17 @@ static void launch_tiled(const uint32_t* A, int64_t lda, const uint32_t* B, int6
 // shorter K and smaller grids than with the fused epilogue, its 128 KB of stores per tile being the larger
 // part of a tile's life: K = 2048, M = 12288 55.0 vs 59.8 (128 x 128 tiles), but M = 8192 42.5 vs 40.0.
 // (whole_ok: the product is one the whole-tile form takes.)
-static int choose_kernel(int64_t M, int64_t N, int64_t K, bool fused, bool short_ok, bool whole_ok, bool walk_ok) {
+//
+// The 256 x 256-tile kernel for one wavefront per SIMD (kernel 9, fused products only; big_ok: the product is
+// one it takes) against the choices above, 121 shapes with N = 1024 .. 8192, K = 2048 .. 8192, M = 4096 .. 65536:
+// 10 - 20 % faster wherever a compute unit's row strip has 512 rows or more, or exactly 256
+// (10000 x 4096 x 4096 55.7 -> 51.5 us, 8192^3 167 -> 151, 16384 x 4096 x 4096 88.6 -> 77, 65536 x 1024 x 8192
+// 169 -> 147); with 257 .. 511 rows a strip is one tile and a bit, and the second start-up costs what the
+// kernel gains (20000 x 1024 x 2048 19.3 vs 21.0, 10000 x 2048 x 4096 32.8 vs 33.1).
+static int choose_kernel(int64_t M, int64_t N, int64_t K, bool fused, bool short_ok, bool whole_ok, bool walk_ok,
+                         bool big_ok) {
     if (!fused && (N <= 16 || M <= 4)) return KERNEL_KSPLIT;
+    if (fused && big_ok && mfma_big_prefers(M, N)) return KERNEL_MFMA_BIG;
     const int64_t tiles128 = ceil_div(M, 128) * ceil_div(N, 128);
     const int64_t tiles256 = ceil_div(M, 256) * ceil_div(N, 128);
     if (mfma_path_supports(K)) {
@@ -453,7 +469,8 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
                               void* stream) {
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return BNN_ERR_INVALID_ARG;
     if (kernel_id < KERNEL_AUTO || kernel_id > KERNEL_LAST) return BNN_ERR_INVALID_ARG;
-    if ((kernel_id == KERNEL_MFMA || kernel_id == KERNEL_MFMA128 || kernel_id == KERNEL_MFMA_PERSIST) &&
+    if ((kernel_id == KERNEL_MFMA || kernel_id == KERNEL_MFMA128 || kernel_id == KERNEL_MFMA_PERSIST ||
+         kernel_id == KERNEL_MFMA_BIG) &&
         !mfma_path_supports(K))
         return BNN_ERR_UNSUPPORTED;
     if (kernel_id == KERNEL_MFMA_SHORTK && !mfma_shortk_supports(A, lda, B, ldb, K)) return BNN_ERR_UNSUPPORTED;
@@ -472,7 +489,7 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
     if (kernel_id == KERNEL_AUTO)
         kernel_id = choose_kernel(M, N, K, /*fused=*/false, mfma_shortk_supports(A, lda, B, ldb, K),
                                   mfma_persist_supports(A, lda, B, ldb, ldc, M, N, K, false, false),
-                                  mfma_persist_supports(A, lda, B, ldb, ldc, M, N, K, false, true));
+                                  mfma_persist_supports(A, lda, B, ldb, ldc, M, N, K, false, true), false);
 
     switch (kernel_id) {
         case KERNEL_NAIVE: {
@@ -528,6 +545,8 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
         }
         case KERNEL_MFMA_PERSIST:
             return launch_xnor_gemm_mfma_persist(A, lda, B, ldb, C, ldc, M, N, K, false, true, BnSignArgs{}, stream);
+        case KERNEL_MFMA_BIG:
+            return BNN_ERR_UNSUPPORTED;          // a kernel of the fused product only
         case KERNEL_MFMA128:
             return launch_xnor_gemm_mfma128(A, lda, B, ldb, C, ldc, M, N, K, stream);
         case KERNEL_MFMA_SHORTK:
@@ -545,9 +564,10 @@ static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return BNN_ERR_INVALID_ARG;
     if (kernel_id != KERNEL_AUTO && kernel_id != KERNEL_TILED128 && kernel_id != KERNEL_TILED64 &&
         kernel_id != KERNEL_MFMA && kernel_id != KERNEL_MFMA128 && kernel_id != KERNEL_MFMA_SHORTK &&
-        kernel_id != KERNEL_MFMA_PERSIST)
+        kernel_id != KERNEL_MFMA_PERSIST && kernel_id != KERNEL_MFMA_BIG)
         return BNN_ERR_INVALID_ARG;
-    if ((kernel_id == KERNEL_MFMA || kernel_id == KERNEL_MFMA128 || kernel_id == KERNEL_MFMA_PERSIST) &&
+    if ((kernel_id == KERNEL_MFMA || kernel_id == KERNEL_MFMA128 || kernel_id == KERNEL_MFMA_PERSIST ||
+         kernel_id == KERNEL_MFMA_BIG) &&
         !mfma_path_supports(K))
         return BNN_ERR_UNSUPPORTED;
     if (kernel_id == KERNEL_MFMA_SHORTK && !mfma_shortk_supports(A, lda, B, ldb, K)) return BNN_ERR_UNSUPPORTED;
@@ -566,10 +586,12 @@ static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const
     if (kernel_id == KERNEL_AUTO)
         kernel_id = choose_kernel(M, N, K, /*fused=*/true, mfma_shortk_supports(A, lda, B, ldb, K),
                                   mfma_persist_supports(A, lda, B, ldb, 0, M, N, K, true, false),
-                                  mfma_persist_supports(A, lda, B, ldb, 0, M, N, K, true, true));
+                                  mfma_persist_supports(A, lda, B, ldb, 0, M, N, K, true, true),
+                                  mfma_big_supports(A, lda, B, ldb, M, N, K, bn));
     if (kernel_id == KERNEL_MFMA_SHORTK) return launch_xnor_gemm_mfma_shortk_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_MFMA_PERSIST)
         return launch_xnor_gemm_mfma_persist(A, lda, B, ldb, nullptr, 0, M, N, K, true, true, bn, stream);
+    if (kernel_id == KERNEL_MFMA_BIG) return launch_xnor_gemm_mfma_big(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_MFMA) return launch_xnor_gemm_mfma_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_MFMA128) return launch_xnor_gemm_mfma128_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_TILED128)

@@ -510,6 +510,67 @@ def test_persistent_kernel_refuses_what_it_does_not_take():
     assert refused(10000, 4096, 1024, ld_extra=1)
 
 
+@pytest.mark.parametrize("M,N,K,ld_extra", [
+    (10000, 4096, 4096, 0),    # the MLP's hidden layer: 16 strips of 625 rows = two 256-row tiles and a 128-row tile
+    (10007, 4096, 2048, 4),    # strips of 625 and 626 rows; padded operand rows
+    (13001, 2048, 2048, 0),    # 32 strips of 406 / 407 rows: one tile and a second one shifted up over it
+    (12000, 2048, 2560, 8),    # 375 rows: one tile and a 128-row tile; 5 K-tiles
+    (65536, 256, 2048, 0),     # one column tile, 256 strips of exactly one tile; 4 K-tiles (the minimum)
+    (8192, 8192, 3072, 0),     # 8 strips of four whole tiles
+])
+def test_one_wavefront_per_simd_kernel_of_the_fused_layer(M, N, K, ld_extra):
+    """The 256 x 256-tile kernel of the fused hidden layer (one workgroup per compute unit, row strips of
+    256-row tiles plus a 128-row tile, K-tile stream running on across a workgroup's tiles): every output
+    bit against the oracle, as the explicit kernel and as the library's own choice, with adversarial
+    thresholds, pad words between the rows and an output buffer whose pad words must stay untouched."""
+    rng = np.random.default_rng(M + 3 * N + K)
+    A, Bm = synth.pm1(rng, (M, K), 0.55), synth.pm1(rng, (K, N), 0.45)
+    bn = synth.bn_params(rng, N, K, adversarial=True)
+    _, a_next = oracle.dense_layer(A, Bm, bn, eps=EPS)
+    want = oracle.pack_bits(a_next)
+    kw, nw = K // 32, N // 32
+    pa = torch.full((M, kw + ld_extra), 0x5A5A5A5A, dtype=torch.int32, device=DEV)
+    pb = torch.full((N, kw + ld_extra), 0x5A5A5A5A, dtype=torch.int32, device=DEV)
+    pa[:, :kw] = words_to_dev(oracle.pack_bits(A))
+    pb[:, :kw] = words_to_dev(oracle.pack_bits(np.ascontiguousarray(Bm.T)))
+    thr, flip = _fold_to_dev(bn, K)
+    for kernel in (bnn.KERNEL_MFMA_BIG, bnn.KERNEL_AUTO):
+        out = torch.full((M, nw + 2), 0x55AA55AA, dtype=torch.int32, device=DEV)
+        bnn.xnor_gemm_bn_sign_pack(pa[:, :kw], pb[:, :kw], K, thr, flip, out=out[:, :nw], kernel=kernel)
+        got = out.cpu().numpy().view(np.uint32)
+        bad = np.argwhere(got[:, :nw] != want)
+        assert bad.size == 0, f"kernel {kernel}: first mismatch at {bad[0]}"
+        assert (got[:, nw:] == 0x55AA55AA).all(), f"kernel {kernel}: pad words of the output written"
+
+
+def test_one_wavefront_per_simd_kernel_refuses_what_it_does_not_take():
+    """Kernel id 9 answers BNN_ERR_UNSUPPORTED, launching nothing, outside its shapes: the int32 product,
+    K not a multiple of 512 or below 2048, N not a multiple of 256 or with a tile count that does not divide
+    the compute units, strips of fewer than 256 rows, operands that do not allow 16-byte loads, output rows
+    that do not allow 8-byte stores."""
+    def refused(M, N, K, ld_extra=0, out_extra=0, int32=False):
+        kw = (K + 31) // 32
+        a = torch.zeros((M, kw + ld_extra), dtype=torch.int32, device=DEV)[:, :kw]
+        b = torch.zeros((N, kw + ld_extra), dtype=torch.int32, device=DEV)[:, :kw]
+        thr = torch.zeros(N, dtype=torch.int32, device=DEV)
+        flip = torch.zeros((N + 31) // 32, dtype=torch.int32, device=DEV)
+        out = torch.zeros((M, (N + 31) // 32 + out_extra), dtype=torch.int32, device=DEV)[:, :(N + 31) // 32]
+        with pytest.raises(bnn.BnnError) as e:
+            if int32:
+                bnn.xnor_gemm(a, b, K, kernel=bnn.KERNEL_MFMA_BIG)
+            else:
+                bnn.xnor_gemm_bn_sign_pack(a, b, K, thr, flip, out=out, kernel=bnn.KERNEL_MFMA_BIG)
+        return e.value.status == 3
+    assert refused(10000, 4096, 4096, int32=True)
+    assert refused(10000, 4096, 4000)
+    assert refused(10000, 4096, 1536)
+    assert refused(10000, 4000, 4096)
+    assert refused(10000, 768, 4096)             # 3 column tiles do not divide 256 compute units
+    assert refused(4000, 4096, 4096)             # 16 strips of 250 rows
+    assert refused(10000, 4096, 4096, ld_extra=1)
+    assert refused(10000, 4096, 4096, out_extra=1)
+
+
 _LARGE_SQUARE = {}
 
 
@@ -1142,11 +1203,12 @@ def test_mlp_forward_captured_in_a_hip_graph_replays_bit_exact():
         assert (net.s[-1].cpu().numpy() == oracle.mlp_forward(x0, weights, bns, eps=EPS)["s"][-1]).all()
 
 
-def test_tile_walk_kernel_captured_in_a_hip_graph_replays_bit_exact():
-    """The tile walk of the large-product kernel keeps no state between launches (no counters, no scratch
-    memory): captured in a HIP graph, every replay on new inputs, with eager launches of the same kernel in
-    between, gives the oracle's bits."""
-    M, N, K = 10000, 4096, 1024
+@pytest.mark.parametrize("kernel,K", [(bnn.KERNEL_MFMA_PERSIST, 1024), (bnn.KERNEL_MFMA_BIG, 2048)])
+def test_tile_walk_kernel_captured_in_a_hip_graph_replays_bit_exact(kernel, K):
+    """The kernels in which a workgroup takes several output tiles keep no state between launches (no
+    counters, no scratch memory): captured in a HIP graph, every replay on new inputs, with eager launches
+    of the same kernel in between, gives the oracle's bits."""
+    M, N = 10000, 4096
     rng = np.random.default_rng(31)
     Bm = synth.pm1(rng, (K, N))
     bn = synth.bn_params(rng, N, K, adversarial=True)
@@ -1154,7 +1216,7 @@ def test_tile_walk_kernel_captured_in_a_hip_graph_replays_bit_exact():
     thr, flip = _fold_to_dev(bn, K)
     a_static = torch.zeros((M, K // 32), dtype=torch.int32, device=DEV)
     out = torch.zeros((M, N // 32), dtype=torch.int32, device=DEV)
-    launch = lambda: bnn.xnor_gemm_bn_sign_pack(a_static, pb, K, thr, flip, out=out, kernel=bnn.KERNEL_MFMA_PERSIST)
+    launch = lambda: bnn.xnor_gemm_bn_sign_pack(a_static, pb, K, thr, flip, out=out, kernel=kernel)
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):

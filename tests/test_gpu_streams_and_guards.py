@@ -96,6 +96,17 @@ def _cases():
                   lambda o: bnn.xnor_gemm_bn_sign_pack(paw, pbw, Kw, thrw, flipw, out=o, kernel=bnn.KERNEL_MFMA_PERSIST),
                   oracle.pack_bits(aw_next).view(np.int32)))
 
+    # the 256 x 256-tile kernel of the fused layer (kernel id 9): strips of two tiles and a 128-row tile
+    Mg, Ng, Kg = 5000, 2048, 2048
+    Ag, Bg = synth.pm1(rng, (Mg, Kg)), synth.pm1(rng, (Kg, Ng))
+    bng = synth.bn_params(rng, Ng, Kg, adversarial=True)
+    _, ag_next = oracle.dense_layer(Ag, Bg, bng, eps=EPS)
+    pag, pbg = _dev_words(oracle.pack_bits(Ag)), _dev_words(oracle.pack_bits(np.ascontiguousarray(Bg.T)))
+    thrg, flipg = _fold(bng, Kg)
+    cases.append(("xnor_gemm_bn_sign_pack[mfma_big]", lambda: Guarded(Mg, Ng // 32, pad_cols=2),   # rows of 8-byte stores
+                  lambda o: bnn.xnor_gemm_bn_sign_pack(pag, pbg, Kg, thrg, flipg, out=o, kernel=bnn.KERNEL_MFMA_BIG),
+                  oracle.pack_bits(ag_next).view(np.int32)))
+
     # bnn_bn_sign_pack
     Sd = torch.from_numpy(S).to(DEV)
     cases.append(("bn_sign_pack", lambda: Guarded(M, (N + 31) // 32), lambda o: bnn.bn_sign_pack(Sd, thr, flip, out=o),
