@@ -102,7 +102,8 @@ int bnn_xnor_gemm(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb
  * than slots, K a multiple of 512 with 1024 <= K <= 2^24, N a multiple of
  * 128, M >= 256, A and B 16-byte aligned, lda and ldb multiples of 4 below
  * 2^22, else BNN_ERR_UNSUPPORTED; what 0 picks when the last round of tiles
- * would fill only part of the chip).  Unknown ids give BNN_ERR_INVALID_ARG. */
+ * would fill only part of the chip), 9 = a kernel of the fused product
+ * only (BNN_ERR_UNSUPPORTED here).  Unknown ids give BNN_ERR_INVALID_ARG. */
 int bnn_xnor_gemm_kernel(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb,
                          int32_t *C, int64_t ldc, int64_t M, int64_t N, int64_t K,
                          int kernel_id, void *stream);
@@ -160,7 +161,14 @@ int bnn_xnor_gemm_bn_sign_pack(const uint32_t *A, int64_t lda, const uint32_t *B
                                void *stream);
 
 /* Same contract with the kernel chosen by the caller: 0 = automatic, 2, 4, 5, 6, 7, 8 as
- * in bnn_xnor_gemm_kernel (the other kernels have no fused form). */
+ * in bnn_xnor_gemm_kernel (the other kernels have no fused form), 9 = the arithmetic of
+ * kernel 5 on 256x256 tiles with one wavefront per SIMD and one workgroup per compute
+ * unit, which takes a strip of rows of one 256-column tile as 256-row tiles and at most
+ * one 128-row tile (needs K a multiple of 512 with 2048 <= K <= 2^19, N a multiple of
+ * 256 whose tile count N/256 divides the compute units, M / (compute units / (N/256))
+ * >= 256, A and B 16-byte aligned, lda and ldb multiples of 4 below 2^22, out 8-byte
+ * aligned, ld_out even, else BNN_ERR_UNSUPPORTED; what 0 picks for such products when
+ * a strip has at least 512 rows or exactly 256). */
 int bnn_xnor_gemm_bn_sign_pack_kernel(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb,
                                       int64_t M, int64_t N, int64_t K, const int32_t *thr,
                                       const uint32_t *flip_bits, uint32_t *out, int64_t ld_out,

@@ -422,19 +422,19 @@ __device__ inline void run_row_tiles(const uint32_t* __restrict__ A, int64_t lda
 
 }  // namespace big
 
-// Workgroup b of the grid of tiles_n * strips: the hardware places consecutive workgroups on the 8 dies in
-// turn, so die d gets the logical ids [d * per, (d + 1) * per), which are whole strips (or parts of one
-// strip) times consecutive column tiles: the workgroups of a die share few rows of A.
+// Workgroup b of the grid of tiles_n * strips.  The hardware places consecutive workgroups on the 8 dies
+// (each with its own L2) in turn, so die d runs the workgroups b = d, d + 8, ...; they are given a compact
+// block of die_strips strips times die_cols column tiles, chosen by the launcher so that the rows of A and
+// B a die reads are as few as possible and its B tiles stay in its L2 over the strip's row tiles.
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void xnor_gemm_mfma_big_kernel(
     const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B, int64_t ldb, int M, int K,
-    int tiles_n, int strips, BnSignArgs bn) {
+    int tiles_n, int strips, int die_strips, int die_cols, BnSignArgs bn) {
     using namespace big;
     __shared__ Shared sh;
-    const int per = int(gridDim.x) / 8;
-    int logical = blockIdx.x;
-    if (int(blockIdx.x) < per * 8) logical = (int(blockIdx.x) % 8) * per + int(blockIdx.x) / 8;
-    const int strip = __builtin_amdgcn_readfirstlane(logical / tiles_n);
-    const int col0 = __builtin_amdgcn_readfirstlane((logical - strip * tiles_n) * BN);
+    const int die = int(blockIdx.x) % 8, idx = int(blockIdx.x) / 8;     // idx < die_strips * die_cols
+    const int dies_n = tiles_n / die_cols;
+    const int strip = __builtin_amdgcn_readfirstlane((die / dies_n) * die_strips + idx / die_cols);
+    const int col0 = __builtin_amdgcn_readfirstlane(((die % dies_n) * die_cols + idx % die_cols) * BN);
     // Rows [r_begin, r_end) of the strip (at least 256).
     const int r_begin = int(int64_t(strip) * M / strips), r_end = int(int64_t(strip + 1) * M / strips);
     const int rows = r_end - r_begin;
@@ -502,9 +502,26 @@ bool mfma_big_supports(const uint32_t* A, int64_t lda, const uint32_t* B, int64_
 int launch_xnor_gemm_mfma_big(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M, int64_t N,
                               int64_t K, BnSignArgs bn, void* stream) {
     if (!mfma_big_supports(A, lda, B, ldb, M, N, K, bn)) return BNN_ERR_UNSUPPORTED;
-    const int64_t strips = mfma_big_strips(M, N), tiles_n = N / 256;
+    const int64_t strips = mfma_big_strips(M, N), tiles_n = N / 256, per_die = strips * tiles_n / 8;
+    // A die's block of die_strips x die_cols workgroups: the rows of A and B it reads per K-tile, B counted
+    // once per row tile of a strip if a die's B tiles do not fit in half of its 4 MB L2.
+    const int64_t rows = ceil_div(M, strips), row_tiles = ceil_div(rows, 256);
+    int64_t best_s = 0, best_cost = 0;
+    for (int64_t ds = 1; ds <= strips && ds <= per_die; ++ds) {
+        if (per_die % ds != 0 || strips % ds != 0) continue;
+        const int64_t dc = per_die / ds;
+        if (dc > tiles_n || tiles_n % dc != 0) continue;
+        const bool b_resident = dc * 256 * (K / 8) <= (int64_t(2) << 20);
+        const int64_t cost = ds * rows + dc * 256 * (b_resident ? 1 : row_tiles);
+        if (best_s == 0 || cost < best_cost) {
+            best_s = ds;
+            best_cost = cost;
+        }
+    }
+    if (best_s == 0) return BNN_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(xnor_gemm_mfma_big_kernel, dim3(unsigned(strips * tiles_n)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), A, lda, B, ldb, int(M), int(K), int(tiles_n), int(strips), bn);
+                       static_cast<hipStream_t>(stream), A, lda, B, ldb, int(M), int(K), int(tiles_n), int(strips),
+                       int(best_s), int(per_die / best_s), bn);
     return check_launch();
 }
 
