@@ -543,6 +543,42 @@ def test_one_wavefront_per_simd_kernel_of_the_fused_layer(M, N, K, ld_extra):
         assert (got[:, nw:] == 0x55AA55AA).all(), f"kernel {kernel}: pad words of the output written"
 
 
+def test_one_wavefront_per_simd_kernel_at_its_largest_k():
+    """K = 2^19 is the largest K whose threshold the fused epilogue folds exactly into fp32 sums, and the
+    largest the 256 x 256-tile kernel takes: 1024 K-tiles per output tile, sums up to 2^19 and thresholds at,
+    just above and just below attained values.  The oracle computes sampled rows x sampled columns
+    (the operands are drawn as packed words; 640 MB on the device); one K-tile more is refused."""
+    M, N, K = 2048, 8192, 1 << 19
+    kw = K // 32
+    rng = np.random.default_rng(19)
+    aw = rng.integers(0, 1 << 32, (M, kw + 16), dtype=np.uint64).astype(np.uint32)
+    bw = rng.integers(0, 1 << 32, (N, kw + 16), dtype=np.uint64).astype(np.uint32)
+    aw[5, :kw] = 0xFFFFFFFF                                  # a row and a column of all +1: the sum K itself
+    bw[7, :kw] = 0xFFFFFFFF
+    rows = np.array([0, 5, 255, 256, 1000, 1023, 1024, 2047])
+    cols = np.concatenate([np.arange(0, 40), [7, 255, 256, 4095, 4096, 8191]])
+    S = oracle.matmul_pm1(oracle.unpack_bits(aw[rows, :kw], K), np.ascontiguousarray(oracle.unpack_bits(bw[cols, :kw], K).T))
+    assert S[1, 40] == K
+    thr = np.zeros(N, dtype=np.int32)
+    thr[cols[:10]] = S[0, :10]
+    thr[cols[10:20]] = S[2, 10:20] + 1
+    thr[cols[20:30]] = S[3, 20:30] - 1
+    thr[cols[30:40]] = [K, K + 1, -K, -K - 1, 0, 1, -1, 2, -2, 3]
+    thr[7] = K
+    flip = rng.integers(0, 2, N).astype(bool)
+    want = (S >= thr[cols][None, :]) != flip[cols][None, :]
+    flip_words = oracle.pack_bits(np.where(flip, 1, -1).astype(np.int8)[None, :])[0]
+    pa, pb = words_to_dev(aw), words_to_dev(bw)
+    thr_d, flip_d = torch.from_numpy(thr).to(DEV), words_to_dev(flip_words[None, :])[0]
+    out = bnn.xnor_gemm_bn_sign_pack(pa[:, :kw], pb[:, :kw], K, thr_d, flip_d, kernel=bnn.KERNEL_MFMA_BIG)
+    got = oracle.unpack_bits(words_to_host(out)[rows], N)[:, cols] > 0
+    bad = np.argwhere(got != want)
+    assert bad.size == 0, f"first mismatch at sampled (row, column) {bad[0]}"
+    with pytest.raises(bnn.BnnError) as e:
+        bnn.xnor_gemm_bn_sign_pack(pa[:, :kw + 16], pb[:, :kw + 16], K + 512, thr_d, flip_d, kernel=bnn.KERNEL_MFMA_BIG)
+    assert e.value.status == 3
+
+
 def test_one_wavefront_per_simd_kernel_refuses_what_it_does_not_take():
     """Kernel id 9 answers BNN_ERR_UNSUPPORTED, launching nothing, outside its shapes: the int32 product,
     K not a multiple of 512 or below 2048, N not a multiple of 256 or with a tile count that does not divide
