@@ -96,6 +96,13 @@ def test_argument_validation_of_the_fused_bitplane_and_conv_entry_points():
     assert lib.bnn_xnor_gemm_bn_sign_pack(p, 2, p, 2, 0, 4, 33, p, p, p, 1, None) == 0
     assert lib.bnn_xnor_gemm_bn_sign_pack_kernel(p, 2, p, 2, 4, 4, 33, p, p, p, 1, 3, None) == INVALID   # no fused K-split
     assert lib.bnn_xnor_gemm_bn_sign_pack_kernel(p, 2, p, 2, 4, 4, 33, p, p, p, 1, 99, None) == INVALID
+    # kernel 9 (256 x 256 tiles, fused product only) refuses, launching nothing: the int32 product; K not a
+    # multiple of 512; N / 256 = 3 column tiles, which do not divide the compute units; strips under 256 rows
+    assert lib.bnn_xnor_gemm_kernel(p, 128, p, 128, p, 4096, 10000, 4096, 4096, 9, None) == UNSUPPORTED
+    assert lib.bnn_xnor_gemm_bn_sign_pack_kernel(p, 128, p, 128, 10000, 4096, 4000, p, p, p, 128, 9, None) == UNSUPPORTED
+    assert lib.bnn_xnor_gemm_bn_sign_pack_kernel(p, 128, p, 128, 10000, 768, 4096, p, p, p, 24, 9, None) == UNSUPPORTED
+    assert lib.bnn_xnor_gemm_bn_sign_pack_kernel(p, 128, p, 128, 4000, 4096, 4096, p, p, p, 128, 9, None) == UNSUPPORTED
+    assert lib.bnn_xnor_gemm_bn_sign_pack_kernel(p, 128, p, 128, 10000, 4096, 4096, p, p, p, 129, 9, None) == UNSUPPORTED  # ld_out odd
     # 8-bit first layer: a row holds 8 words per K-word
     assert lib.bnn_pack_bitplanes(p, -1, 4, 4, p, 8, None) == INVALID
     assert lib.bnn_pack_bitplanes(p, 2, 40, 40, p, 15, None) == INVALID                           # ld_out < 8 * ceil(cols/32)
