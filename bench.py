@@ -24,7 +24,9 @@ of the step, and the 8192^3 product with every element compared.
 Single workloads: --gemm M,N,K [--fused] [--kernel ...], --stream NAME,
 --conv LAYER (back-to-back launches, 10 batches of --steps, median batch).
 
-Prints exactly one JSON line on stdout; progress goes to stderr.
+Prints exactly one JSON line on stdout; progress goes to stderr.  With
+--results FILE every workload's figures are also appended to FILE, one JSON
+line each, as soon as they are measured.
 """
 from __future__ import annotations
 
@@ -302,6 +304,10 @@ def main():
     ap.add_argument("--valu", action="store_true",
                     help="force the vector-ALU XNOR-popcount GEMM kernel in the hidden layers "
                          "(default: the library's choice, the bits-in / MFMA-inside kernel at these sizes)")
+    ap.add_argument("--results", default=None, metavar="FILE",
+                    help="append one JSON line per workload to FILE as soon as it is measured (the MLP step, the 8192^3 "
+                         "product, the streaming kernels, the dense layer, the ragged sweep, the conv layers, the "
+                         "ConvNet body), so that a run cut short keeps what it has; stdout stays the one line")
     ap.add_argument("--skip-extras", action="store_true",
                     help="only the timed MLP region, the 8192^3 product and the CPU baselines")
     ap.add_argument("--cpu-sample", type=int, default=10000, help="images the CPU oracle is timed on")
@@ -430,6 +436,13 @@ def main():
                    "warmup_by_time_ms": warm_s * 1e3, "warmup_steps_run": args.warmup + warm_steps,
                    "clocks_settled": settled},
     }
+    def emit(workload, payload):
+        """One line per workload in the --results file: workload, seed of its inputs, measurements."""
+        if args.results:
+            with open(args.results, "a") as f:
+                f.write(json.dumps({"workload": workload, "data": "synthetic (workloads/synth.py, fixed seeds)",
+                                    "n_gpus": 1, **payload}) + "\n")
+
     kname = ("xnor_gemm_tiled_kernel<8,8,16>" if args.valu else
              "xnor_gemm_mfma_big_kernel (256x256 tiles, one wavefront per SIMD)" if fused else
              "xnor_gemm_mfma_persist_kernel<false> (256x128 tiles, tile walk)") + \
@@ -472,6 +485,8 @@ def main():
         "scores_equal_gpu": parity,
     }
     log(f"oracle: {n_cpu} images in {c1 - c0:.2f} s on {oracle.num_threads()} threads; scores equal GPU: {parity}")
+    emit(result["config"]["workload"], {k: result[k] for k in ("metric", "value", "unit", "steps", "warmup", "ms_per_step",
+                                                               "dtype", "roofline", "cpu_baseline")})
     if not parity:
         raise RuntimeError("GPU scores differ from the oracle")
     del tr, net, a1, w1, thr1, flip1, out1
@@ -524,6 +539,7 @@ def main():
             f"{v['frac']:.1%} of its peak; clock {v.get('measured_clock_ghz', float('nan')):.3f} GHz -> "
             f"{v.get('frac_at_measured_clock', float('nan')):.1%}")
     log(f"oracle: {n_rows} rows of 8192^3 in {g1 - g0:.2f} s; equal GPU: {gemm_parity}; VALU == MFMA result: {equal}")
+    emit("xnor_gemm_8192x8192x8192", {"kernels": other, "cpu_baseline": result["cpu_baseline"]["other_workloads"]["xnor_gemm_8192"]})
     if not (gemm_parity and equal):
         raise RuntimeError("8192^3: GPU results differ from the oracle or from each other")
 
@@ -548,6 +564,7 @@ def main():
                                                  "frac_of_fp4_mfma_peak": ops / t["median"] / 1e9 / PEAK_FP4_MFMA_TFLOPS}
         log(f"xnor_gemm_bn_sign_pack 8192^3: {t['median']:.3f} ms = {ops / t['median'] / 1e9:.1f} TOP/s")
         del thr8, flip8, out8
+        emit("xnor_gemm_8192_variants", {k: extras[k] for k in ("gemm_i8_mfma_8192", "xnor_gemm_bn_sign_pack_8192")})
     del c, a_bits, b_bits, A8, Bm8
 
     if not args.skip_extras:
@@ -570,6 +587,7 @@ def main():
                                              "frac_of_hbm_peak": bytes_ / ms / 1e6 / PEAK_HBM_GBS}
         log(f"bn_sign_pack 32768x8192: {ms:.3f} ms = {bytes_ / ms / 1e6:.0f} GB/s")
         del x_s, c_s, bits_s
+        emit("streaming_kernels_32768x8192", {k: extras[k] for k in ("pack_sign_32768x8192", "bn_sign_pack_32768x8192")})
 
         # The small dense layer (64 x 1024 x 1024) and the ragged sweep: launch-latency bound, time only.
         A0, Bm0, bn0 = synth.config_dense()
@@ -588,6 +606,7 @@ def main():
                                                     "note": "launch-latency bound; includes the host-side launch cost"}
         log(f"dense layer 64x1024x1024 (fused GEMM + BN + Sign): {t['median'] * 1e3:.1f} us per launch "
             f"(oracle {(o1 - o0) / 3 * 1e6:.0f} us)")
+        emit("dense_64x1024x1024", extras["dense_64x1024x1024_fused_layer"])
         cases, host_cases = [], []
         for idx, (Mr, Nr, Kr, _p) in enumerate(synth.ragged_cases()):
             Ar, Br = synth.config_ragged(idx)
@@ -608,6 +627,7 @@ def main():
         log(f"ragged sweep, {len(cases)} GEMMs: {t['median']:.3f} ms in total ({t['median'] * 1e3 / len(cases):.1f} us "
             f"per case); oracle {(o1 - o0) * 1e3:.0f} ms")
         del cases, host_cases
+        emit("ragged_sweep_336_cases", extras["ragged_sweep_336_cases"])
 
         conv = {}
         for layer, (ch, hw) in enumerate(synth.CONV_LAYERS):
@@ -633,6 +653,7 @@ def main():
                 f"{B / ms_imp * 1e3:,.0f} images/s); im2col + fused GEMM {ms_low:.3f} ms (im2col {ms_i:.3f}); equal: {same}")
             del imp, low, xb
         extras["conv_layers_batch256"] = conv
+        emit("conv_layers_batch256", conv)
 
         # The binary body of the paper's CIFAR-10 ConvNet (the architecture Sec. 2.2 refers to): five 3x3
         # convolutions with three poolings and three dense layers, batch 256, from the first layer's output
@@ -655,6 +676,7 @@ def main():
         log(f"ConvNet body (128C3-MP2-256C3-256C3-MP2-512C3-512C3-MP2-1024FC-1024FC-10) batch {Bn}: {ms_net:.3f} ms "
             f"({Bn / ms_net * 1e3:,.0f} images/s, {ops_net / ms_net / 1e9:.0f} TOP/s)")
         del net, xnb
+        emit("convnet_body_batch256", extras["convnet_body_batch256"])
         result["extras"] = extras
 
     print(json.dumps(result), flush=True)
