@@ -103,7 +103,14 @@ int bnn_xnor_gemm(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb
  * 128, M >= 256, A and B 16-byte aligned, lda and ldb multiples of 4 below
  * 2^22, else BNN_ERR_UNSUPPORTED; what 0 picks when the last round of tiles
  * would fill only part of the chip), 9 = a kernel of the fused product
- * only (BNN_ERR_UNSUPPORTED here).  Unknown ids give BNN_ERR_INVALID_ARG. */
+ * only (BNN_ERR_UNSUPPORTED here), 10 = the arithmetic of kernel 5 on 32x32
+ * output tiles with K split over the four wavefronts of a workgroup and the
+ * operands read from memory straight into the MFMA's registers (for small
+ * outputs with a long K, such as fully connected layers at batch 256; needs
+ * K a positive multiple of 128 up to 2^24, A and B 16-byte aligned, lda and
+ * ldb multiples of 4, else BNN_ERR_UNSUPPORTED; what 0 picks, from K = 512
+ * on, for outputs of at most 256 such tiles, at most 512 with K >= 2048 or
+ * at most 1024 with K >= 4096).  Unknown ids give BNN_ERR_INVALID_ARG. */
 int bnn_xnor_gemm_kernel(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb,
                          int32_t *C, int64_t ldc, int64_t M, int64_t N, int64_t K,
                          int kernel_id, void *stream);
@@ -168,7 +175,7 @@ int bnn_xnor_gemm_bn_sign_pack(const uint32_t *A, int64_t lda, const uint32_t *B
  * 256 whose tile count N/256 divides the compute units, M / (compute units / (N/256))
  * >= 256, A and B 16-byte aligned, lda and ldb multiples of 4 below 2^22, out 8-byte
  * aligned, ld_out even, else BNN_ERR_UNSUPPORTED; what 0 picks for such products when
- * a strip has at least 512 rows or exactly 256). */
+ * a strip has at least 512 rows or exactly 256), 10 as in bnn_xnor_gemm_kernel. */
 int bnn_xnor_gemm_bn_sign_pack_kernel(const uint32_t *A, int64_t lda, const uint32_t *B, int64_t ldb,
                                       int64_t M, int64_t N, int64_t K, const int32_t *thr,
                                       const uint32_t *flip_bits, uint32_t *out, int64_t ld_out,

@@ -37,5 +37,6 @@ from .binding import (  # noqa: F401
     KERNEL_MFMA_SHORTK,
     KERNEL_MFMA_PERSIST,
     KERNEL_MFMA_BIG,
+    KERNEL_MFMA_SPLITK,
 )
 from .network import BinaryMLP, BinaryConvLayer, BinaryConvNet  # noqa: F401

@@ -17,7 +17,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "libbnn_hip.so")
 
 (KERNEL_AUTO, KERNEL_NAIVE, KERNEL_TILED128, KERNEL_KSPLIT, KERNEL_TILED64, KERNEL_MFMA, KERNEL_MFMA128,
- KERNEL_MFMA_SHORTK, KERNEL_MFMA_PERSIST, KERNEL_MFMA_BIG) = range(10)
+ KERNEL_MFMA_SHORTK, KERNEL_MFMA_PERSIST, KERNEL_MFMA_BIG, KERNEL_MFMA_SPLITK) = range(11)
 
 _i64 = ctypes.c_int64
 _int = ctypes.c_int

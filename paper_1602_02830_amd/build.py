@@ -20,7 +20,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 ARCH = "gfx950"
 
 HIP_SOURCES = ["pack_sign.hip", "xnor_gemm.hip", "xnor_gemm_mfma.hip", "xnor_gemm_mfma_shortk.hip",
-               "xnor_gemm_mfma_persist.hip", "xnor_gemm_mfma_big.hip",
+               "xnor_gemm_mfma_persist.hip", "xnor_gemm_mfma_big.hip", "xnor_gemm_mfma_splitk.hip",
                "bn_sign_pack.hip", "im2col_pack.hip", "conv_implicit.hip", "conv_patch.hip", "gemm_i8_mfma.hip",
                "valu_fallbacks.hip"]
 HOST_SOURCES = ["bn_fold.cpp", "api.cpp"]

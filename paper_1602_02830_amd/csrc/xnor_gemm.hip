@@ -350,7 +350,7 @@ __global__ __launch_bounds__(256) void xnor_gemm_ksplit_kernel(
 // ----------------------------------------------------------------------------
 enum { KERNEL_AUTO = 0, KERNEL_NAIVE = 1, KERNEL_TILED128 = 2, KERNEL_KSPLIT = 3, KERNEL_TILED64 = 4,
        KERNEL_MFMA = 5, KERNEL_MFMA128 = 6, KERNEL_MFMA_SHORTK = 7, KERNEL_MFMA_PERSIST = 8,
-       KERNEL_MFMA_BIG = 9, KERNEL_LAST = KERNEL_MFMA_BIG };
+       KERNEL_MFMA_BIG = 9, KERNEL_MFMA_SPLITK = 10, KERNEL_LAST = KERNEL_MFMA_SPLITK };
 
 // Matrix-engine variant, defined in xnor_gemm_mfma.hip.
 bool mfma_path_supports(int64_t K);
@@ -378,6 +378,13 @@ int launch_xnor_gemm_mfma_big(const uint32_t* A, int64_t lda, const uint32_t* B,
 bool mfma_big_supports(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M, int64_t N,
                        int64_t K, const BnSignArgs& bn);
 bool mfma_big_prefers(int64_t M, int64_t N);
+// 32 x 32 output tiles with K split over the wavefronts of a workgroup (xnor_gemm_mfma_splitk.hip), for small
+// outputs with a long K: BNN_ERR_UNSUPPORTED, with nothing launched, for the products it does not take.
+bool mfma_splitk_supports(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t M, int64_t N,
+                          int64_t K);
+int launch_xnor_gemm_mfma_splitk(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
+                                 int64_t ldc, int64_t M, int64_t N, int64_t K, bool fused, const BnSignArgs& bn,
+                                 void* stream);
 // Short-K organisation of the matrix-engine kernel, defined in xnor_gemm_mfma_shortk.hip.
 bool mfma_shortk_supports(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int64_t K);
 int launch_xnor_gemm_mfma_shortk(const uint32_t* A, int64_t lda, const uint32_t* B, int64_t ldb, int32_t* C,
@@ -438,8 +445,18 @@ static void launch_tiled(const uint32_t* A, int64_t lda, const uint32_t* B, int6
 // 169 -> 147); with 257 .. 511 rows a strip is one tile and a bit, and the second start-up costs what the
 // kernel gains (20000 x 1024 x 2048 19.3 vs 21.0, 10000 x 2048 x 4096 32.8 vs 33.1).
 static int choose_kernel(int64_t M, int64_t N, int64_t K, bool fused, bool short_ok, bool whole_ok, bool walk_ok,
-                         bool big_ok) {
+                         bool big_ok, bool splitk_ok) {
     if (!fused && (N <= 16 || M <= 4)) return KERNEL_KSPLIT;
+    // Small outputs: 32 x 32 tiles with K split inside the workgroup, while the tiles are few enough for the
+    // workgroup dispatch rate.  Launches replayed from a graph, fused, against the choice below:
+    // 256 x 1024 (256 tiles) K = 512 3.3 vs 3.6 us, 1024 3.7 vs 4.2, 8192 5.3 vs 12.9, 16384 8.1 vs 23.0;
+    // 512 x 1024 (512 tiles) K = 1024 4.7 vs 4.2, 2048 4.7 vs 5.5, 8192 7.1 vs 12.9;
+    // 1024 x 1024 (1024 tiles) K = 2048 6.7 vs 5.5, 4096 6.8 vs 8.0, 16384 19.3 vs 23.2.  The int32 form alike.
+    if (splitk_ok) {
+        const int64_t tiles32 = ceil_div(M, 32) * ceil_div(N, 32);
+        if (tiles32 <= 256 || (tiles32 <= 512 && K >= 2048) || (tiles32 <= 1024 && K >= 4096))
+            return KERNEL_MFMA_SPLITK;
+    }
     if (fused && big_ok && mfma_big_prefers(M, N)) return KERNEL_MFMA_BIG;
     const int64_t tiles128 = ceil_div(M, 128) * ceil_div(N, 128);
     const int64_t tiles256 = ceil_div(M, 256) * ceil_div(N, 128);
@@ -489,7 +506,8 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
     if (kernel_id == KERNEL_AUTO)
         kernel_id = choose_kernel(M, N, K, /*fused=*/false, mfma_shortk_supports(A, lda, B, ldb, K),
                                   mfma_persist_supports(A, lda, B, ldb, ldc, M, N, K, false, false),
-                                  mfma_persist_supports(A, lda, B, ldb, ldc, M, N, K, false, true), false);
+                                  mfma_persist_supports(A, lda, B, ldb, ldc, M, N, K, false, true), false,
+                                  K >= 512 && mfma_splitk_supports(A, lda, B, ldb, M, N, K));
 
     switch (kernel_id) {
         case KERNEL_NAIVE: {
@@ -547,6 +565,8 @@ static int xnor_gemm_dispatch(const uint32_t* A, int64_t lda, const uint32_t* B,
             return launch_xnor_gemm_mfma_persist(A, lda, B, ldb, C, ldc, M, N, K, false, true, BnSignArgs{}, stream);
         case KERNEL_MFMA_BIG:
             return BNN_ERR_UNSUPPORTED;          // a kernel of the fused product only
+        case KERNEL_MFMA_SPLITK:
+            return launch_xnor_gemm_mfma_splitk(A, lda, B, ldb, C, ldc, M, N, K, false, BnSignArgs{}, stream);
         case KERNEL_MFMA128:
             return launch_xnor_gemm_mfma128(A, lda, B, ldb, C, ldc, M, N, K, stream);
         case KERNEL_MFMA_SHORTK:
@@ -564,7 +584,7 @@ static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const
     if (M < 0 || N < 0 || K < 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return BNN_ERR_INVALID_ARG;
     if (kernel_id != KERNEL_AUTO && kernel_id != KERNEL_TILED128 && kernel_id != KERNEL_TILED64 &&
         kernel_id != KERNEL_MFMA && kernel_id != KERNEL_MFMA128 && kernel_id != KERNEL_MFMA_SHORTK &&
-        kernel_id != KERNEL_MFMA_PERSIST && kernel_id != KERNEL_MFMA_BIG)
+        kernel_id != KERNEL_MFMA_PERSIST && kernel_id != KERNEL_MFMA_BIG && kernel_id != KERNEL_MFMA_SPLITK)
         return BNN_ERR_INVALID_ARG;
     if ((kernel_id == KERNEL_MFMA || kernel_id == KERNEL_MFMA128 || kernel_id == KERNEL_MFMA_PERSIST ||
          kernel_id == KERNEL_MFMA_BIG) &&
@@ -587,11 +607,14 @@ static int xnor_gemm_bn_sign_pack_dispatch(const uint32_t* A, int64_t lda, const
         kernel_id = choose_kernel(M, N, K, /*fused=*/true, mfma_shortk_supports(A, lda, B, ldb, K),
                                   mfma_persist_supports(A, lda, B, ldb, 0, M, N, K, true, false),
                                   mfma_persist_supports(A, lda, B, ldb, 0, M, N, K, true, true),
-                                  mfma_big_supports(A, lda, B, ldb, M, N, K, bn));
+                                  mfma_big_supports(A, lda, B, ldb, M, N, K, bn),
+                                  K >= 512 && mfma_splitk_supports(A, lda, B, ldb, M, N, K));
     if (kernel_id == KERNEL_MFMA_SHORTK) return launch_xnor_gemm_mfma_shortk_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_MFMA_PERSIST)
         return launch_xnor_gemm_mfma_persist(A, lda, B, ldb, nullptr, 0, M, N, K, true, true, bn, stream);
     if (kernel_id == KERNEL_MFMA_BIG) return launch_xnor_gemm_mfma_big(A, lda, B, ldb, M, N, K, bn, stream);
+    if (kernel_id == KERNEL_MFMA_SPLITK)
+        return launch_xnor_gemm_mfma_splitk(A, lda, B, ldb, nullptr, 0, M, N, K, true, bn, stream);
     if (kernel_id == KERNEL_MFMA) return launch_xnor_gemm_mfma_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_MFMA128) return launch_xnor_gemm_mfma128_fused(A, lda, B, ldb, M, N, K, bn, stream);
     if (kernel_id == KERNEL_TILED128)

@@ -214,9 +214,9 @@ def test_xnor_gemm_randomized_shapes_strides_alignments_and_kernels(seed):
     base offsets (so both the 16-byte and the word-wise loaders run), poisoned pad bits, every kernel id.
     A kernel either returns the exact product and the exact fused bits, or refuses with UNSUPPORTED."""
     rng = np.random.default_rng(4242 + seed)
-    ids = list(GEMM_KERNELS.values()) + [bnn.KERNEL_MFMA_SHORTK, bnn.KERNEL_MFMA_PERSIST]
+    ids = list(GEMM_KERNELS.values()) + [bnn.KERNEL_MFMA_SHORTK, bnn.KERNEL_MFMA_PERSIST, bnn.KERNEL_MFMA_SPLITK]
     fused_ids = {bnn.KERNEL_AUTO, bnn.KERNEL_TILED128, bnn.KERNEL_TILED64, bnn.KERNEL_MFMA, bnn.KERNEL_MFMA128,
-                 bnn.KERNEL_MFMA_SHORTK, bnn.KERNEL_MFMA_PERSIST}
+                 bnn.KERNEL_MFMA_SHORTK, bnn.KERNEL_MFMA_PERSIST, bnn.KERNEL_MFMA_SPLITK}
     for _case in range(20):
         M, N = (int(np.exp(rng.uniform(0, np.log(600)))) for _ in range(2))
         K = int(np.exp(rng.uniform(0, np.log(5000))))
@@ -577,6 +577,67 @@ def test_one_wavefront_per_simd_kernel_at_its_largest_k():
     with pytest.raises(bnn.BnnError) as e:
         bnn.xnor_gemm_bn_sign_pack(pa[:, :kw + 16], pb[:, :kw + 16], K + 512, thr_d, flip_d, kernel=bnn.KERNEL_MFMA_BIG)
     assert e.value.status == 3
+
+
+@pytest.mark.parametrize("M,N,K,ld_extra", [
+    (256, 1024, 8192, 0),      # first fully connected layer of the ConvNet at batch 256: 256 tiles, 8 quads per lane
+    (33, 65, 128, 4),          # one quad per row: seven of the eight lane groups multiply zeros; ragged M and N
+    (1, 1, 128, 0),
+    (100, 1000, 4096, 0),      # ragged last row tile and last column word
+    (31, 33, 256, 8),
+    (512, 512, 2048, 0),
+    (64, 40, 1152, 0),         # 9 quads per row: a second, mostly empty pass of the lanes
+    (7, 300, 16384, 0),        # 128 quads per row: four batches per lane
+    (256, 256, 8576, 12),      # 67 quads per row: the last batch is ragged across the wavefronts
+    (1024, 1024, 4096, 0),     # 1024 tiles, the most the automatic choice gives this kernel
+])
+def test_k_split_matrix_engine_kernel_int32_and_fused(M, N, K, ld_extra):
+    """Kernel id 10 (32 x 32 output tiles, K split over the wavefronts of a workgroup), by explicit id and
+    through the automatic choice (which takes it for these small outputs once K >= 512), on padded operand rows
+    filled with junk: every int32 result and every fused output bit against the oracle; words of the output
+    beyond ceil(N / 32) untouched."""
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    A, Bm = synth.pm1(rng, (M, K), 0.55), synth.pm1(rng, (K, N))
+    bn = synth.bn_params(rng, N, K, adversarial=True)
+    S, a_next = oracle.dense_layer(A, Bm, bn, eps=EPS)
+    kw = K // 32
+    pa = _offset_words(oracle.pack_bits(A), kw + ld_extra, 0)
+    pb = _offset_words(oracle.pack_bits(np.ascontiguousarray(Bm.T)), kw + ld_extra, 4)
+    thr, flip = _fold_to_dev(bn, K)
+    want = oracle.pack_bits(a_next)
+    nw = (N + 31) // 32
+    for kernel in (bnn.KERNEL_MFMA_SPLITK, bnn.KERNEL_AUTO):
+        got = bnn.xnor_gemm(pa, pb, K, kernel=kernel).cpu().numpy()
+        bad = np.argwhere(got != S)
+        assert bad.size == 0, f"kernel {kernel}: first mismatch at {bad[0]}"
+        out = torch.full((M, nw + 1), 0x55AA55AA, dtype=torch.int32, device=DEV)
+        bnn.xnor_gemm_bn_sign_pack(pa, pb, K, thr, flip, out=out[:, :nw], kernel=kernel)
+        host = words_to_host(out)
+        assert (host[:, :nw] == want).all(), f"kernel {kernel}"
+        assert (host[:, nw] == 0x55AA55AA).all(), f"kernel {kernel}: wrote past the row's words"
+
+
+def test_k_split_matrix_engine_kernel_refuses_what_it_does_not_take():
+    """Kernel id 10 answers BNN_ERR_UNSUPPORTED, launching nothing, outside its shapes: K not a multiple of
+    128 (or zero), operands that do not allow 16-byte loads."""
+    def refused(M, N, K, ld_extra=0, first=0, fused=False):
+        kw = (K + 31) // 32
+        a = torch.zeros(first + M * (kw + ld_extra), dtype=torch.int32, device=DEV)[first:].view(M, kw + ld_extra)[:, :kw]
+        b = torch.zeros((N, kw + ld_extra), dtype=torch.int32, device=DEV)[:, :kw]
+        with pytest.raises(bnn.BnnError) as e:
+            if fused:
+                thr = torch.zeros(N, dtype=torch.int32, device=DEV)
+                flip = torch.zeros((N + 31) // 32, dtype=torch.int32, device=DEV)
+                bnn.xnor_gemm_bn_sign_pack(a, b, K, thr, flip, kernel=bnn.KERNEL_MFMA_SPLITK)
+            else:
+                bnn.xnor_gemm(a, b, K, kernel=bnn.KERNEL_MFMA_SPLITK)
+        return e.value.status == 3
+    for fused in (False, True):
+        assert refused(64, 64, 1000, fused=fused)
+        assert refused(64, 64, 96, fused=fused)
+        assert refused(64, 64, 1024 + 64, fused=fused)
+        assert refused(64, 64, 1024, ld_extra=2, fused=fused)
+        assert refused(64, 64, 1024, first=1, fused=fused)
 
 
 def test_one_wavefront_per_simd_kernel_refuses_what_it_does_not_take():

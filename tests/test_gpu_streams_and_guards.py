@@ -107,6 +107,19 @@ def _cases():
                   lambda o: bnn.xnor_gemm_bn_sign_pack(pag, pbg, Kg, thrg, flipg, out=o, kernel=bnn.KERNEL_MFMA_BIG),
                   oracle.pack_bits(ag_next).view(np.int32)))
 
+    # 32 x 32 tiles with K split inside the workgroup (kernel id 10): ragged last row tile and last column word
+    Ms, Ns, Ks = 70, 150, 1152
+    As, Bs = synth.pm1(rng, (Ms, Ks)), synth.pm1(rng, (Ks, Ns))
+    bns = synth.bn_params(rng, Ns, Ks, adversarial=True)
+    Ss, as_next = oracle.dense_layer(As, Bs, bns, eps=EPS)
+    pas, pbs = _dev_words(oracle.pack_bits(As)), _dev_words(oracle.pack_bits(np.ascontiguousarray(Bs.T)))
+    thrs, flips = _fold(bns, Ks)
+    cases.append(("xnor_gemm[mfma_splitk]", lambda: Guarded(Ms, Ns),
+                  lambda o: bnn.xnor_gemm(pas, pbs, Ks, out=o, kernel=bnn.KERNEL_MFMA_SPLITK), Ss))
+    cases.append(("xnor_gemm_bn_sign_pack[mfma_splitk]", lambda: Guarded(Ms, (Ns + 31) // 32),
+                  lambda o: bnn.xnor_gemm_bn_sign_pack(pas, pbs, Ks, thrs, flips, out=o, kernel=bnn.KERNEL_MFMA_SPLITK),
+                  oracle.pack_bits(as_next).view(np.int32)))
+
     # bnn_bn_sign_pack
     Sd = torch.from_numpy(S).to(DEV)
     cases.append(("bn_sign_pack", lambda: Guarded(M, (N + 31) // 32), lambda o: bnn.bn_sign_pack(Sd, thr, flip, out=o),

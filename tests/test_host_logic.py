@@ -103,6 +103,12 @@ def test_argument_validation_of_the_fused_bitplane_and_conv_entry_points():
     assert lib.bnn_xnor_gemm_bn_sign_pack_kernel(p, 128, p, 128, 10000, 768, 4096, p, p, p, 24, 9, None) == UNSUPPORTED
     assert lib.bnn_xnor_gemm_bn_sign_pack_kernel(p, 128, p, 128, 4000, 4096, 4096, p, p, p, 128, 9, None) == UNSUPPORTED
     assert lib.bnn_xnor_gemm_bn_sign_pack_kernel(p, 128, p, 128, 10000, 4096, 4096, p, p, p, 129, 9, None) == UNSUPPORTED  # ld_out odd
+    # kernel id 10: K a multiple of 128, rows that allow 16-byte loads
+    assert lib.bnn_xnor_gemm_kernel(p, 32, p, 32, p, 64, 64, 64, 1000, 10, None) == UNSUPPORTED
+    assert lib.bnn_xnor_gemm_kernel(p, 34, p, 34, p, 64, 64, 64, 1024, 10, None) == UNSUPPORTED
+    assert lib.bnn_xnor_gemm_bn_sign_pack_kernel(p, 32, p, 32, 64, 64, 1000, p, p, p, 2, 10, None) == UNSUPPORTED
+    assert lib.bnn_xnor_gemm_bn_sign_pack_kernel(p, 34, p, 34, 64, 64, 1024, p, p, p, 2, 10, None) == UNSUPPORTED
+    assert lib.bnn_xnor_gemm_kernel(p, 32, p, 32, p, 64, 64, 64, 1024, 11, None) == INVALID
     # 8-bit first layer: a row holds 8 words per K-word
     assert lib.bnn_pack_bitplanes(p, -1, 4, 4, p, 8, None) == INVALID
     assert lib.bnn_pack_bitplanes(p, 2, 40, 40, p, 15, None) == INVALID                           # ld_out < 8 * ceil(cols/32)
