@@ -215,7 +215,8 @@ def gemm_only(args, bnn, torch, dev):
     kid = {"auto": bnn.KERNEL_AUTO, "naive": bnn.KERNEL_NAIVE, "tiled128": bnn.KERNEL_TILED128,
            "ksplit": bnn.KERNEL_KSPLIT, "tiled64": bnn.KERNEL_TILED64, "mfma": bnn.KERNEL_MFMA,
            "mfma128": bnn.KERNEL_MFMA128, "mfma_shortk": bnn.KERNEL_MFMA_SHORTK,
-           "mfma_persist": bnn.KERNEL_MFMA_PERSIST, "mfma_big": bnn.KERNEL_MFMA_BIG}.get(args.kernel)
+           "mfma_persist": bnn.KERNEL_MFMA_PERSIST, "mfma_big": bnn.KERNEL_MFMA_BIG,
+           "mfma_splitk": bnn.KERNEL_MFMA_SPLITK}.get(args.kernel)
     if args.kernel == "i8":
         a8, b8 = bnn.unpack_i8(a, K), bnn.unpack_i8(b, K)
         c = torch.empty((M, N), dtype=torch.int32, device=dev)
@@ -322,7 +323,7 @@ def main():
                     help="also run a plain 1 GiB device copy (known traffic, for scaling profiler byte counters)")
     ap.add_argument("--gemm", default=None, metavar="M,N,K",
                     help="time only bnn_xnor_gemm on random packed operands of this shape (for profiler runs)")
-    ap.add_argument("--kernel", default="auto", choices=["auto", "naive", "tiled128", "ksplit", "tiled64", "mfma", "mfma128", "mfma_shortk", "mfma_persist", "mfma_big", "i8"],
+    ap.add_argument("--kernel", default="auto", choices=["auto", "naive", "tiled128", "ksplit", "tiled64", "mfma", "mfma128", "mfma_shortk", "mfma_persist", "mfma_big", "mfma_splitk", "i8"],
                     help="kernel for --gemm (i8 = the int8 MFMA variant on unpacked operands)")
     ap.add_argument("--fused", action="store_true", help="with --gemm: the fused BN+Sign entry point instead")
     ap.add_argument("--stream", default=None, choices=["pack_sign", "bn_sign_pack"],
