@@ -140,9 +140,13 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
         const int yl = t / cv.W, x = t - yl * cv.W;
         coord_s[tid] = (g << 20) | (yl << 10) | x;
     }
+    // Thresholds and flip words go to registers here and to LDS after the patch loads have been issued: every
+    // global load of the prologue (these, the filters, the patch) is in flight before the first one is waited for.
+    int thr_reg = 0;
+    uint32_t flip_reg = 0u;
     if (FUSED) {
-        if (tid < BN) thr_s[tid] = col0 + tid < N ? max(-K - 1, min(K + 1, bn.thr[col0 + tid])) : 0;
-        if (tid < BN / 32) flip_s[tid] = col0 + 32 * tid < N ? bn.flip_bits[(col0 >> 5) + tid] : 0u;
+        if (tid < BN && col0 + tid < N) thr_reg = bn.thr[col0 + tid];
+        if (tid < BN / 32 && col0 + 32 * tid < N) flip_reg = bn.flip_bits[(col0 >> 5) + tid];
     }
     // The filter loads are issued first, so that they are in flight while the patch is addressed and loaded.
     uint4 all_b[BRES ? kResidentKTiles : 1][LOADS_B];
@@ -164,30 +168,85 @@ __global__ __launch_bounds__(256, WM >= 4 ? 2 : 3) void conv_patch_mfma_kernel(
     const int hw = cv.H * cv.W;
     const int b0 = row0 / hw, y0 = (row0 - b0 * hw) / cv.W;
     const int group_slots = pg.prows * pg.pw;
-    for (int s = tid; s < pg.slots; s += 256) {
-        const int g = s / group_slots, t = s - g * group_slots;
-        const int py = t / pg.pw, px = t - py * pg.pw;
-        const int b = b0 + g, y = y0 + py - cv.pad, x = px - cv.pad;
-        const bool inside = b < n_images && y >= 0 && y < cv.H && x >= 0 && x < cv.W;
-        const uint32_t pix = inside ? uint32_t((b * cv.H + y) * cv.W + x) : 0u;
-        const uint32_t* p = in + size_t(pix) * uint32_t(cv.Cw);
-        int pop = 0;
-        if (WORDS) {
-            for (int cw = 0; cw < cv.Cw; ++cw) {
-                const uint32_t v = inside ? p[cw] : ~0u;
-                patchw[cw * pg.slots + s] = v;
-                pop += __popc(v);
+    if (WORDS || !FUSED) {
+        // Slot by slot (the word-granular patch, and the int32 form, whose epilogue leaves no registers for
+        // more loads in flight).
+        for (int s = tid; s < pg.slots; s += 256) {
+            const int g = s / group_slots, t = s - g * group_slots;
+            const int py = t / pg.pw, px = t - py * pg.pw;
+            const int b = b0 + g, y = y0 + py - cv.pad, x = px - cv.pad;
+            const bool inside = b < n_images && y >= 0 && y < cv.H && x >= 0 && x < cv.W;
+            const uint32_t pix = inside ? uint32_t((b * cv.H + y) * cv.W + x) : 0u;
+            const uint32_t* p = in + size_t(pix) * uint32_t(cv.Cw);
+            int pop = 0;
+            if (WORDS) {
+                for (int cw = 0; cw < cv.Cw; ++cw) {
+                    const uint32_t v = inside ? p[cw] : ~0u;
+                    patchw[cw * pg.slots + s] = v;
+                    pop += __popc(v);
+                }
+            } else {
+                for (int cq = 0; cq < pg.cqn; ++cq) {
+                    uint4 v = *reinterpret_cast<const uint4*>(p + 4 * cq);
+                    if (!inside) v = make_uint4(~0u, ~0u, ~0u, ~0u);
+                    patch[(2 * cq) * pg.slots + s] = make_uint2(v.x, v.y);
+                    patch[(2 * cq + 1) * pg.slots + s] = make_uint2(v.z, v.w);
+                    pop += popc4(v);
+                }
             }
-        } else {
-            for (int cq = 0; cq < pg.cqn; ++cq) {
-                uint4 v = *reinterpret_cast<const uint4*>(p + 4 * cq);
-                if (!inside) v = make_uint4(~0u, ~0u, ~0u, ~0u);
-                patch[(2 * cq) * pg.slots + s] = make_uint2(v.x, v.y);
-                patch[(2 * cq + 1) * pg.slots + s] = make_uint2(v.z, v.w);
-                pop += popc4(v);
-            }
+            pix_pop[s] = pop;
         }
-        pix_pop[s] = pop;
+    } else {
+        // Two slots per thread and pass, up to four channel quads of each at a time: all (up to eight) loads
+        // of a pass are issued before the first LDS write waits for one.  Slots that do not exist and cells
+        // outside the image load input pixel 0 (a valid address) and are not written / written as all ones.
+        constexpr int kSlotsPerPass = 2, kQuadsPerPass = 4;
+        for (int s_base = 0; s_base < pg.slots; s_base += kSlotsPerPass * 256) {
+            const uint32_t* p[kSlotsPerPass];
+            bool live[kSlotsPerPass], inside[kSlotsPerPass];
+            int pop[kSlotsPerPass];
+#pragma unroll
+            for (int u = 0; u < kSlotsPerPass; ++u) {
+                const int s = s_base + u * 256 + tid;
+                live[u] = s < pg.slots;
+                const int g = s / group_slots, t = s - g * group_slots;
+                const int py = t / pg.pw, px = t - py * pg.pw;
+                const int b = b0 + g, y = y0 + py - cv.pad, x = px - cv.pad;
+                inside[u] = live[u] && b < n_images && y >= 0 && y < cv.H && x >= 0 && x < cv.W;
+                const uint32_t pix = inside[u] ? uint32_t((b * cv.H + y) * cv.W + x) : 0u;
+                p[u] = in + size_t(pix) * uint32_t(cv.Cw);
+                pop[u] = 0;
+            }
+            for (int cq0 = 0; cq0 < pg.cqn; cq0 += kQuadsPerPass) {
+                uint4 v[kSlotsPerPass][kQuadsPerPass];
+#pragma unroll
+                for (int u = 0; u < kSlotsPerPass; ++u)
+#pragma unroll
+                    for (int c = 0; c < kQuadsPerPass; ++c)
+                        if (cq0 + c < pg.cqn) v[u][c] = *reinterpret_cast<const uint4*>(p[u] + 4 * (cq0 + c));
+#pragma unroll
+                for (int u = 0; u < kSlotsPerPass; ++u) {
+                    const int s = s_base + u * 256 + tid;
+#pragma unroll
+                    for (int c = 0; c < kQuadsPerPass; ++c)
+                        if (cq0 + c < pg.cqn) {
+                            const uint4 w = inside[u] ? v[u][c] : make_uint4(~0u, ~0u, ~0u, ~0u);
+                            if (live[u]) {
+                                patch[(2 * (cq0 + c)) * pg.slots + s] = make_uint2(w.x, w.y);
+                                patch[(2 * (cq0 + c) + 1) * pg.slots + s] = make_uint2(w.z, w.w);
+                            }
+                            pop[u] += popc4(w);
+                        }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kSlotsPerPass; ++u)
+                if (live[u]) pix_pop[s_base + u * 256 + tid] = pop[u];
+        }
+    }
+    if (FUSED) {
+        if (tid < BN) thr_s[tid] = max(-K - 1, min(K + 1, thr_reg));
+        if (tid < BN / 32) flip_s[tid] = flip_reg;
     }
     if (WORDS) {
         // K-word kwi of a receptive field = channel word kwi % Cw of tap kwi / Cw; words past the field's
