@@ -446,17 +446,19 @@ static void launch_tiled(const uint32_t* A, int64_t lda, const uint32_t* B, int6
 // kernel gains (20000 x 1024 x 2048 19.3 vs 21.0, 10000 x 2048 x 4096 32.8 vs 33.1).
 static int choose_kernel(int64_t M, int64_t N, int64_t K, bool fused, bool short_ok, bool whole_ok, bool walk_ok,
                          bool big_ok, bool splitk_ok) {
-    if (!fused && (N <= 16 || M <= 4)) return KERNEL_KSPLIT;
     // Small outputs: 32 x 32 tiles with K split inside the workgroup, while the tiles are few enough for the
     // workgroup dispatch rate.  Launches replayed from a graph, fused, against the choice below:
     // 256 x 1024 (256 tiles) K = 512 3.3 vs 3.6 us, 1024 3.7 vs 4.2, 8192 5.3 vs 12.9, 16384 8.1 vs 23.0;
     // 512 x 1024 (512 tiles) K = 1024 4.7 vs 4.2, 2048 4.7 vs 5.5, 8192 7.1 vs 12.9;
-    // 1024 x 1024 (1024 tiles) K = 2048 6.7 vs 5.5, 4096 6.8 vs 8.0, 16384 19.3 vs 23.2.  The int32 form alike.
+    // 1024 x 1024 (1024 tiles) K = 2048 6.7 vs 5.5, 4096 6.8 vs 8.0, 16384 19.3 vs 23.2.  The int32 form alike,
+    // skinny outputs included (against the lane-group kernel below: 10000 x 10, K = 4096, 4.3 vs 5.1 us,
+    // 16384 x 16 4.6 vs 6.8, 1 x 4096 3.2 vs 3.6, 4 x 1024, K = 8192, 4.6 vs 4.3).
     if (splitk_ok) {
         const int64_t tiles32 = ceil_div(M, 32) * ceil_div(N, 32);
         if (tiles32 <= 256 || (tiles32 <= 512 && K >= 2048) || (tiles32 <= 1024 && K >= 4096))
             return KERNEL_MFMA_SPLITK;
     }
+    if (!fused && (N <= 16 || M <= 4)) return KERNEL_KSPLIT;
     if (fused && big_ok && mfma_big_prefers(M, N)) return KERNEL_MFMA_BIG;
     const int64_t tiles128 = ceil_div(M, 128) * ceil_div(N, 128);
     const int64_t tiles256 = ceil_div(M, 256) * ceil_div(N, 128);
