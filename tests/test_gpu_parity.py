@@ -319,12 +319,13 @@ def test_shortk_kernel_rejects_what_it_cannot_take():
         assert (got == oracle.matmul_pm1(A, Bm)).all()
 
 
-@pytest.mark.parametrize("kernel", ["mfma", "mfma128"])
+@pytest.mark.parametrize("kernel", ["mfma", "mfma128", "mfma_splitk"])
 def test_mfma_kernels_at_the_exact_accumulation_limit(kernel):
     """K = 2^24 is the largest K the matrix-engine kernels accept: their fp32 sums of 0/1 products reach
     2^24 exactly when every bit of both operands is set.  One K beyond that they refuse, and the default
     dispatch serves the same product on the vector ALU."""
     K = 1 << 24
+    kid = bnn.KERNEL_MFMA_SPLITK if kernel == "mfma_splitk" else GEMM_KERNELS[kernel]
     rng = np.random.default_rng(24)
     A = synth.pm1(rng, (4, K))
     Bm = synth.pm1(rng, (K, 3))
@@ -335,12 +336,12 @@ def test_mfma_kernels_at_the_exact_accumulation_limit(kernel):
     assert want[0, 0] == K and want[1, 0] == -K
     pa = words_to_dev(oracle.pack_bits(A))
     pb = words_to_dev(oracle.pack_bits(np.ascontiguousarray(Bm.T)))
-    got = bnn.xnor_gemm(pa, pb, K, kernel=GEMM_KERNELS[kernel]).cpu().numpy()
+    got = bnn.xnor_gemm(pa, pb, K, kernel=kid).cpu().numpy()
     assert (got == want).all()
     # fused form at this K compares in integers (thresholds are folded into fp32 sums only up to K = 2^19)
     thr = torch.tensor([K, 0, -K + 2], dtype=torch.int32, device=DEV)
     flip = torch.tensor([0b100], dtype=torch.int32, device=DEV)
-    bits = words_to_host(bnn.xnor_gemm_bn_sign_pack(pa, pb, K, thr, flip, kernel=GEMM_KERNELS[kernel]))
+    bits = words_to_host(bnn.xnor_gemm_bn_sign_pack(pa, pb, K, thr, flip, kernel=kid))
     want_bits = ((want >= thr.cpu().numpy()[None, :]) != np.array([False, False, True])[None, :])
     assert (bits[:, 0] == (want_bits * (1 << np.arange(3))[None, :]).sum(axis=1)).all()
     # one word more: outside the exact range
@@ -350,7 +351,7 @@ def test_mfma_kernels_at_the_exact_accumulation_limit(kernel):
     pa2 = words_to_dev(oracle.pack_bits(A2))
     pb2 = words_to_dev(oracle.pack_bits(np.ascontiguousarray(B2.T)))
     with pytest.raises(bnn.BnnError) as e:
-        bnn.xnor_gemm(pa2, pb2, K2, kernel=GEMM_KERNELS[kernel])
+        bnn.xnor_gemm(pa2, pb2, K2, kernel=kid)
     assert e.value.status == 3
     assert (bnn.xnor_gemm(pa2, pb2, K2).cpu().numpy() == want + oracle.matmul_pm1(A2[:, K:], B2[K:, :])).all()
 
