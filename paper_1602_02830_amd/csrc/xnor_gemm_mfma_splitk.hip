@@ -1,7 +1,8 @@
 // Bits-in, matrix-engine-inside binary product (Sec. 4 Eq. (5), the XnorDotProduct of Alg. 4) for
 // small outputs with a long K: the fully connected layers of a network at inference batch sizes
-// (Sec. 2.2, 2.3: 256 x 1024 outputs over K = 8192), where 128 x 128 or 256 x 128 output tiles
-// would leave most of the 256 compute units without a tile.
+// (in the ConvNet architecture that Sec. 2.2 refers to, at batch 256: 256 x 1024 outputs over
+// K = 8192), where 128 x 128 or 256 x 128 output tiles would leave most of the 256 compute units
+// without a tile.
 //
 // A workgroup owns one 32 x 32 output tile, so a 256 x 1024 output is 256 workgroups, and splits K
 // over its four wavefronts: of every aligned group of 8 quads (a quad = 4 words = 128 bits of a
