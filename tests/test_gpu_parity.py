@@ -618,6 +618,27 @@ def test_k_split_matrix_engine_kernel_int32_and_fused(M, N, K, ld_extra):
         assert (host[:, nw] == 0x55AA55AA).all(), f"kernel {kernel}: wrote past the row's words"
 
 
+@pytest.mark.parametrize("M,N", [(256, 1024), (257, 1024), (512, 1024), (513, 1024), (1024, 1024), (1025, 1024),
+                                 (10000, 10), (16385, 16), (3, 16384), (4, 2048)])
+@pytest.mark.parametrize("K", [384, 512, 1920, 2048, 4096])
+def test_automatic_choice_on_both_sides_of_the_small_output_limits(M, N, K):
+    """The automatic choice hands small outputs to kernel 10 up to 256 tiles of 32 x 32 (K >= 512), 512 tiles
+    (K >= 2048) and 1024 tiles (K >= 4096), skinny int32 outputs included, and everything else to the other
+    kernels: on both sides of each limit the int32 product and the fused bits equal the oracle's."""
+    rng = np.random.default_rng(M * 31 + N * 17 + K)
+    A, Bm = synth.pm1(rng, (M, K), 0.45), synth.pm1(rng, (K, N))
+    bn = synth.bn_params(rng, N, K, adversarial=True)
+    S, a_next = oracle.dense_layer(A, Bm, bn, eps=EPS)
+    pa = words_to_dev(oracle.pack_bits(A))
+    pb = words_to_dev(oracle.pack_bits(np.ascontiguousarray(Bm.T)))
+    got = bnn.xnor_gemm(pa, pb, K).cpu().numpy()
+    bad = np.argwhere(got != S)
+    assert bad.size == 0, f"first mismatch at {bad[0]}"
+    thr, flip = _fold_to_dev(bn, K)
+    bits = words_to_host(bnn.xnor_gemm_bn_sign_pack(pa, pb, K, thr, flip))
+    assert (bits == oracle.pack_bits(a_next)).all()
+
+
 def test_k_split_matrix_engine_kernel_refuses_what_it_does_not_take():
     """Kernel id 10 answers BNN_ERR_UNSUPPORTED, launching nothing, outside its shapes: K not a multiple of
     128 (or zero), operands that do not allow 16-byte loads."""
