@@ -639,6 +639,29 @@ def test_automatic_choice_on_both_sides_of_the_small_output_limits(M, N, K):
     assert (bits == oracle.pack_bits(a_next)).all()
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_k_split_matrix_engine_kernel_randomized(seed):
+    """Seeded random cases for kernel 10: M, N log-uniform up to 700, K a random multiple of 128 up to 10240, P(+1)
+    anywhere in (0, 1), operand rows padded by a random multiple of 4 words and based a random multiple of 16 bytes
+    into a junk-filled buffer: the exact product and the exact fused bits."""
+    rng = np.random.default_rng(9090 + seed)
+    for _case in range(15):
+        M, N = (int(np.exp(rng.uniform(0, np.log(700)))) for _ in range(2))
+        K = 128 * int(rng.integers(1, 81))
+        p = rng.uniform(0.02, 0.98)
+        A, Bm = synth.pm1(rng, (M, K), p), synth.pm1(rng, (K, N), p)
+        bn = synth.bn_params(rng, N, K, adversarial=True)
+        S, a_next = oracle.dense_layer(A, Bm, bn, eps=EPS)
+        kw = K // 32
+        da = _offset_words(oracle.pack_bits(A), kw + 4 * int(rng.integers(0, 4)), 4 * int(rng.integers(0, 3)))
+        db = _offset_words(oracle.pack_bits(np.ascontiguousarray(Bm.T)), kw + 4 * int(rng.integers(0, 4)), 4 * int(rng.integers(0, 3)))
+        thr, flip = _fold_to_dev(bn, K)
+        tag = f"seed {seed} M={M} N={N} K={K}"
+        assert (bnn.xnor_gemm(da, db, K, kernel=bnn.KERNEL_MFMA_SPLITK).cpu().numpy() == S).all(), tag
+        bits = words_to_host(bnn.xnor_gemm_bn_sign_pack(da, db, K, thr, flip, kernel=bnn.KERNEL_MFMA_SPLITK))
+        assert (bits == oracle.pack_bits(a_next)).all(), tag
+
+
 def test_k_split_matrix_engine_kernel_refuses_what_it_does_not_take():
     """Kernel id 10 answers BNN_ERR_UNSUPPORTED, launching nothing, outside its shapes: K not a multiple of
     128 (or zero), operands that do not allow 16-byte loads."""
