@@ -13,8 +13,9 @@
 //     The whole K extent of a tile sits in LDS at once, so a tile costs two barriers and its MFMA
 //     steps run without any in between; the global loads of the next tile are in flight while the
 //     current one is multiplied, and are written to LDS before the current tile's epilogue;
-//   - only the K words that exist are multiplied: ceil(K / 128) * 2 steps of 64 bits instead of
-//     whole 512-bit K-tiles (14 instead of 16 steps at K = 784).
+//   - only the K words that exist are multiplied: ceil(K / 128) * 2 steps of 64 bits, less the last one
+//     where it would multiply nothing but zeros, instead of whole 512-bit K-tiles (13 instead of 16 steps
+//     at K = 784).
 //
 // LDS layout of an operand tile: planes [quad q][half h] of 8-byte slots, slot r = row r's words
 // 4q + 2h, 4q + 2h + 1.  Lane (row r = l % 32, half h = l / 32) of an MFMA operand reads slot r
@@ -240,6 +241,9 @@ __global__ __launch_bounds__(256, 3) void xnor_gemm_mfma_shortk_kernel(
     const uint2* rd_a = lds_a + fh * PLANE + wm * 32 * WM + fr;
     const uint2* rd_b = lds_b + fh * PLANE + wn * 32 * WN + fr;
 
+    // Steps of 64 bits: two per quad, except that a last quad holding a single word (K words = 4q + 1) has
+    // nothing but zeros in its second step (words 4q + 1 and 4q + 3), which is then left out.
+    const int n_steps = 2 * kq - ((((K + 31) >> 5) & 3) == 1 ? 1 : 0);
     int buf = 0;
     for (int tile_m = group; tile_m < tiles_m; tile_m += groups, buf ^= 1) {
         const bool more = tile_m + groups < tiles_m;
@@ -268,6 +272,7 @@ __global__ __launch_bounds__(256, 3) void xnor_gemm_mfma_shortk_kernel(
             for (int j = 0; j < WN; ++j) b_nxt[j] = rd_b[2 * qn * PLANE + j * 32];
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
+                if (s == 1 && 2 * q + 1 >= n_steps) break;          // the last quad's second words are all beyond K
                 v8i fa[WM], fb[WN];
 #pragma unroll
                 for (int i = 0; i < WM; ++i) fa[i] = widen_fp4_a(s == 0 ? a_cur[i].x : a_cur[i].y);
