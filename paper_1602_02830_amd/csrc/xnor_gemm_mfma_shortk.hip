@@ -34,6 +34,7 @@
 // image are +1, i.e. all-ones words (zero padding through Eq. (1)), chosen at staging so that
 // the loads stay unconditional (address clamped into the input).
 #include <algorithm>
+#include <type_traits>
 #include <cstdint>
 
 #include "bnn_internal.h"
@@ -250,51 +251,67 @@ __global__ __launch_bounds__(256, 3) void xnor_gemm_mfma_shortk_kernel(
         if (more) fetch_a(tile_m + groups, ra);                      // in flight during the MFMA steps
 
         v16f acc[WM][WN];
+        if constexpr (!FUSED) {                     // (the int32 form has no registers to spare for the peeled first step)
 #pragma unroll
-        for (int i = 0; i < WM; ++i)
+            for (int i = 0; i < WM; ++i)
 #pragma unroll
-            for (int j = 0; j < WN; ++j)
+                for (int j = 0; j < WN; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
+                    for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+        }
         uint2 a_cur[WM], b_cur[WN];
 #pragma unroll
         for (int i = 0; i < WM; ++i) a_cur[i] = rd_a[i * 32];
 #pragma unroll
         for (int j = 0; j < WN; ++j) b_cur[j] = rd_b[j * 32];
-        for (int q = 0; q < kq; ++q) {
-            // Pairs of the next quad (the last iteration re-reads its own: no branch in the loop).
+        // One step of 64 bits on word s of the current pairs.  first: the tile's first step, which in the fused
+        // form starts the sums with a zero addend instead of cleared accumulators.
+        auto step = [&](int s, auto first_tag) {
+            constexpr bool FIRST = FUSED && decltype(first_tag)::value;
+            v8i fa[WM], fb[WN];
+#pragma unroll
+            for (int i = 0; i < WM; ++i) fa[i] = widen_fp4_a(s == 0 ? a_cur[i].x : a_cur[i].y);
+#pragma unroll
+            for (int j = 0; j < WN; ++j) fb[j] = widen_fp4_b(s == 0 ? b_cur[j].x : b_cur[j].y);
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int j = 0; j < WN; ++j) {
+                    v16f addend = acc[i][j];
+                    if (FIRST) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) addend[v] = 0.0f;
+                    }
+                    // fused: operands swapped, the accumulators hold the transposed blocks (mfma_epilogue_bits)
+                    if (FUSED)
+                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[j], fa[i], addend, 4 /* fp4 */,
+                                                                                    4 /* fp4 */, 0, 0, 0, 0);
+                    else
+                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fa[i], fb[j], addend, 4 /* A: fp4 */,
+                                                                                    4 /* B: fp4 */, 0, 0, 0, 0);
+                }
+        };
+        // A quad is two steps (n_steps says whether the last quad's second one exists); the pairs of the next
+        // quad are read during the current one (the last quad re-reads its own: no branch around the reads).
+        auto quad = [&](int q, auto first_tag) {
             const int qn = min(q + 1, kq - 1);
             uint2 a_nxt[WM], b_nxt[WN];
 #pragma unroll
             for (int i = 0; i < WM; ++i) a_nxt[i] = rd_a[2 * qn * PLANE + i * 32];
 #pragma unroll
             for (int j = 0; j < WN; ++j) b_nxt[j] = rd_b[2 * qn * PLANE + j * 32];
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                if (s == 1 && 2 * q + 1 >= n_steps) break;          // the last quad's second words are all beyond K
-                v8i fa[WM], fb[WN];
-#pragma unroll
-                for (int i = 0; i < WM; ++i) fa[i] = widen_fp4_a(s == 0 ? a_cur[i].x : a_cur[i].y);
-#pragma unroll
-                for (int j = 0; j < WN; ++j) fb[j] = widen_fp4_b(s == 0 ? b_cur[j].x : b_cur[j].y);
-#pragma unroll
-                for (int i = 0; i < WM; ++i)
-#pragma unroll
-                    for (int j = 0; j < WN; ++j) {
-                        // fused: operands swapped, the accumulators hold the transposed blocks (mfma_epilogue_bits)
-                        if (FUSED)
-                            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                                fb[j], fa[i], acc[i][j], 4 /* fp4 */, 4 /* fp4 */, 0, 0, 0, 0);
-                        else
-                            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                                fa[i], fb[j], acc[i][j], 4 /* A: fp4 */, 4 /* B: fp4 */, 0, 0, 0, 0);
-                    }
-            }
+            step(0, first_tag);
+            if (2 * q + 1 < n_steps) step(1, std::false_type{});
 #pragma unroll
             for (int i = 0; i < WM; ++i) a_cur[i] = a_nxt[i];
 #pragma unroll
             for (int j = 0; j < WN; ++j) b_cur[j] = b_nxt[j];
+        };
+        if constexpr (FUSED) {
+            quad(0, std::true_type{});
+            for (int q = 1; q < kq; ++q) quad(q, std::false_type{});
+        } else {
+            for (int q = 0; q < kq; ++q) quad(q, std::false_type{});
         }
 
         __syncthreads();                            // every wavefront has read this tile's planes
