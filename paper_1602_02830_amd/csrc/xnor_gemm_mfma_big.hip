@@ -149,11 +149,15 @@ __device__ inline void epilogue_bits(v16f (&acc)[WM][WN], const Shared& sh, cons
 
 // The output tiles of `count` row tiles of 64 * WM rows each, at rows min(first_row + 64 * WM * i, last_row0)
 // and columns [col0, col0 + 256), i = 0 .. count - 1 (count >= 1), n_ktiles >= 4.  The thresholds of the
-// column tile are in sh.thr / sh.flip and a barrier has been passed since they were written.
+// column tile are either in sh.thr / sh.flip, a barrier having been passed since they were written, or
+// (write_thr) still in this thread's registers - thr_reg of column col0 + threadIdx.x, flip_reg of word
+// threadIdx.x < 8 - and written here, once the first operand loads are under way: their first readers, the
+// row sums of the first tile, are several barriers further on.
 template <int WM>
 __device__ inline void run_row_tiles(const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B,
                                      int64_t ldb, int K, const BnSignArgs& bn, Shared& sh, int first_row,
-                                     int last_row0, int count, int col0) {
+                                     int last_row0, int count, int col0, bool write_thr, int thr_reg,
+                                     uint32_t flip_reg) {
     constexpr int BM = 64 * WM;
     constexpr int LOADS_A = BM / ST_ROWS;
     constexpr int MFMAS = WM * WN;                      // per K-step
@@ -335,6 +339,11 @@ __device__ inline void run_row_tiles(const uint32_t* __restrict__ A, int64_t lda
     fetch_a(ra);
     const uint32_t* f_b_pending = f_b;                   // B's half of a fetch follows A's half a step later
     advance_fetch();
+    if (write_thr) {
+        // Clamped to the result range, which changes no output bit and keeps the folded terms exact.
+        sh.thr[tid] = max(-K - 1, min(K + 1, thr_reg));
+        if (tid < BN / 32) sh.flip[tid] = flip_reg;
+    }
     stage_a(1, qa0);
     stage_b(1, qb0);
     count_a(qa0);
@@ -427,31 +436,31 @@ __device__ inline void run_row_tiles(const uint32_t* __restrict__ A, int64_t lda
 // block of die_strips strips times die_cols column tiles, chosen by the launcher so that the rows of A and
 // B a die reads are as few as possible and its B tiles stay in its L2 over the strip's row tiles.
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void xnor_gemm_mfma_big_kernel(
-    const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B, int64_t ldb, int M, int K,
-    int tiles_n, int strips, int die_strips, int die_cols, BnSignArgs bn) {
+    const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B, int64_t ldb, int K, int tiles_n,
+    int strip_rows, int strip_extra, int die_strips, int die_cols, BnSignArgs bn) {
     using namespace big;
     __shared__ Shared sh;
     const int die = int(blockIdx.x) % 8, idx = int(blockIdx.x) / 8;     // idx < die_strips * die_cols
     const int dies_n = tiles_n / die_cols;
     const int strip = __builtin_amdgcn_readfirstlane((die / dies_n) * die_strips + idx / die_cols);
     const int col0 = __builtin_amdgcn_readfirstlane(((die % dies_n) * die_cols + idx % die_cols) * BN);
-    // Rows [r_begin, r_end) of the strip (at least 256).
-    const int r_begin = int(int64_t(strip) * M / strips), r_end = int(int64_t(strip + 1) * M / strips);
+    // The column tile's thresholds and flip words, into registers: they go to LDS after the first operand
+    // loads have been issued (run_row_tiles), so that no load of the kernel's start waits for another.
+    const int thr_reg = bn.thr[col0 + threadIdx.x];
+    uint32_t flip_reg = 0u;
+    if (threadIdx.x < BN / 32) flip_reg = bn.flip_bits[(col0 >> 5) + threadIdx.x];
+    // Rows [r_begin, r_end) of the strip (at least 256): strip_rows each, one more in the first strip_extra strips.
+    const int r_begin = strip * strip_rows + min(strip, strip_extra);
+    const int r_end = r_begin + strip_rows + (strip < strip_extra ? 1 : 0);
     const int rows = r_end - r_begin;
     const int rest = rows % BM_MAX;
     const int full = rows / BM_MAX + (rest > BM_MAX / 2 ? 1 : 0);      // 256-row tiles, the last one shifted up if partial
     const bool half = rest > 0 && rest <= BM_MAX / 2;                  // one 128-row tile at the strip's end
 
-    // The column tile's thresholds (clamped to the result range, which changes no output bit and keeps the
-    // folded terms exact) and flip words.
-    sh.thr[threadIdx.x] = max(-K - 1, min(K + 1, bn.thr[col0 + threadIdx.x]));
-    if (threadIdx.x < BN / 32) sh.flip[threadIdx.x] = bn.flip_bits[(col0 >> 5) + threadIdx.x];
-    __syncthreads();
-
-    run_row_tiles<4>(A, lda, B, ldb, K, bn, sh, r_begin, r_end - BM_MAX, full, col0);
+    run_row_tiles<4>(A, lda, B, ldb, K, bn, sh, r_begin, r_end - BM_MAX, full, col0, true, thr_reg, flip_reg);
     if (half) {
         __syncthreads();                                               // LDS buffers and row sums change hands
-        run_row_tiles<2>(A, lda, B, ldb, K, bn, sh, r_end - BM_MAX / 2, r_end - BM_MAX / 2, 1, col0);
+        run_row_tiles<2>(A, lda, B, ldb, K, bn, sh, r_end - BM_MAX / 2, r_end - BM_MAX / 2, 1, col0, false, 0, 0u);
     }
 }
 
@@ -520,8 +529,8 @@ int launch_xnor_gemm_mfma_big(const uint32_t* A, int64_t lda, const uint32_t* B,
     }
     if (best_s == 0) return BNN_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(xnor_gemm_mfma_big_kernel, dim3(unsigned(strips * tiles_n)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), A, lda, B, ldb, int(M), int(K), int(tiles_n), int(strips),
-                       int(best_s), int(per_die / best_s), bn);
+                       static_cast<hipStream_t>(stream), A, lda, B, ldb, int(K), int(tiles_n), int(M / strips),
+                       int(M % strips), int(best_s), int(per_die / best_s), bn);
     return check_launch();
 }
 
