@@ -53,26 +53,55 @@ __global__ __launch_bounds__(kPackThreads) void pack_sign_kernel(
         int64_t word_of[kPackUnroll];
         int64_t row_of[kPackUnroll];
         int64_t row = row0, w = w0;
+        if (VEC && cols >= 4) {
+            // Four unconditional 16-byte loads, all in flight together: a lane whose four elements do not all
+            // exist (a slice past the last group, the tail of a row) loads the row's last whole quad of
+            // elements instead - an address inside the matrix - and what it needs is sorted out afterwards.
+            const int64_t c_last = (cols & ~int64_t(3)) - 4;         // first element of that quad (16-byte aligned)
+            float4 f[kPackUnroll];
+            bool whole[kPackUnroll];
+            int64_t c_of[kPackUnroll];
 #pragma unroll
-        for (int u = 0; u < kPackUnroll; ++u) {
-            const bool live = g0 + u * kSlice < n_words;
-            row_of[u] = live ? row : -1;
-            word_of[u] = w;
-            const int64_t c0 = w * 32 + q * 4;
-            const float* p = x + row * ld_x + c0;
-            // Out-of-range elements take a negative value: bit 0.
-            v[u][0] = v[u][1] = v[u][2] = v[u][3] = -1.0f;
-            if (live) {
-                if (VEC && c0 + 3 < cols) {
-                    const float4 f = *reinterpret_cast<const float4*>(p);
-                    v[u][0] = f.x; v[u][1] = f.y; v[u][2] = f.z; v[u][3] = f.w;
-                } else {
+            for (int u = 0; u < kPackUnroll; ++u) {
+                const bool live = g0 + u * kSlice < n_words;
+                row_of[u] = live ? row : -1;
+                word_of[u] = w;
+                c_of[u] = w * 32 + q * 4;
+                whole[u] = live && c_of[u] + 3 < cols;
+                f[u] = *reinterpret_cast<const float4*>(x + (live ? row : 0) * ld_x + (whole[u] ? c_of[u] : c_last));
+                advance(row, w, slice, kw);
+            }
+#pragma unroll
+            for (int u = 0; u < kPackUnroll; ++u) {
+                // Out-of-range elements take a negative value: bit 0.
+                v[u][0] = whole[u] ? f[u].x : -1.0f;
+                v[u][1] = whole[u] ? f[u].y : -1.0f;
+                v[u][2] = whole[u] ? f[u].z : -1.0f;
+                v[u][3] = whole[u] ? f[u].w : -1.0f;
+                if (!whole[u] && row_of[u] >= 0 && c_of[u] < cols) {   // a row's last, partial quad (cols % 4 != 0)
+                    const float* p = x + row_of[u] * ld_x + c_of[u];
+#pragma unroll
+                    for (int e = 0; e < 3; ++e)
+                        if (c_of[u] + e < cols) v[u][e] = p[e];
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < kPackUnroll; ++u) {
+                const bool live = g0 + u * kSlice < n_words;
+                row_of[u] = live ? row : -1;
+                word_of[u] = w;
+                const int64_t c0 = w * 32 + q * 4;
+                const float* p = x + row * ld_x + c0;
+                // Out-of-range elements take a negative value: bit 0.
+                v[u][0] = v[u][1] = v[u][2] = v[u][3] = -1.0f;
+                if (live) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
                         if (c0 + e < cols) v[u][e] = p[e];
                 }
+                advance(row, w, slice, kw);
             }
-            advance(row, w, slice, kw);
         }
 #pragma unroll
         for (int u = 0; u < kPackUnroll; ++u) {
