@@ -39,32 +39,69 @@ __global__ __launch_bounds__(kBnThreads) void bn_sign_pack_kernel(
     int64_t row0 = g0 / nw, w0 = g0 - row0 * nw;
 
     for (; g0 < n_words; g0 += pass_groups) {
-        int4 c[kBnUnroll];
+        int4 c[kBnUnroll], t[kBnUnroll];
         int64_t row_of[kBnUnroll], word_of[kBnUnroll];
         int64_t row = row0, w = w0;
+        if (VEC && N >= 4) {
+            // Unconditional 16-byte loads of the pre-activations and of their thresholds, all in flight
+            // together: a lane whose four channels do not all exist (a slice past the last group, the tail
+            // of a row) loads the row's last whole quad of channels instead - an address inside the matrix -
+            // and what it needs is sorted out afterwards.
+            const int64_t n_last = (N & ~int64_t(3)) - 4;
+            bool whole[kBnUnroll];
 #pragma unroll
-        for (int u = 0; u < kBnUnroll; ++u) {
-            const bool live = g0 + u * kSlice < n_words;
-            row_of[u] = live ? row : -1;
-            word_of[u] = w;
-            const int64_t n0 = w * 32 + q * 4;
-            const int32_t* p = C + row * ldc + n0;
-            c[u] = make_int4(0, 0, 0, 0);
-            if (live) {
-                if (VEC && n0 + 3 < N) {
-                    c[u] = *reinterpret_cast<const int4*>(p);
-                } else {
-                    if (n0 + 0 < N) c[u].x = p[0];
-                    if (n0 + 1 < N) c[u].y = p[1];
-                    if (n0 + 2 < N) c[u].z = p[2];
-                    if (n0 + 3 < N) c[u].w = p[3];
+            for (int u = 0; u < kBnUnroll; ++u) {
+                const bool live = g0 + u * kSlice < n_words;
+                row_of[u] = live ? row : -1;
+                word_of[u] = w;
+                const int64_t n0 = w * 32 + q * 4;
+                whole[u] = live && n0 + 3 < N;
+                const int64_t n_at = whole[u] ? n0 : n_last;
+                c[u] = *reinterpret_cast<const int4*>(C + (live ? row : 0) * ldc + n_at);
+                t[u] = *reinterpret_cast<const int4*>(thr + n_at);
+                row += slice_row;
+                w += slice_word;
+                if (w >= nw) {
+                    w -= nw;
+                    ++row;
                 }
             }
-            row += slice_row;
-            w += slice_word;
-            if (w >= nw) {
-                w -= nw;
-                ++row;
+#pragma unroll
+            for (int u = 0; u < kBnUnroll; ++u) {
+                const int64_t n0 = word_of[u] * 32 + q * 4;
+                if (!whole[u]) {
+                    c[u] = make_int4(0, 0, 0, 0);
+                    t[u] = make_int4(0, 0, 0, 0);
+                    if (row_of[u] >= 0 && n0 < N) {                    // a row's last, partial quad (N % 4 != 0)
+                        const int32_t* p = C + row_of[u] * ldc + n0;
+                        if (n0 + 0 < N) { c[u].x = p[0]; t[u].x = thr[n0 + 0]; }
+                        if (n0 + 1 < N) { c[u].y = p[1]; t[u].y = thr[n0 + 1]; }
+                        if (n0 + 2 < N) { c[u].z = p[2]; t[u].z = thr[n0 + 2]; }
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < kBnUnroll; ++u) {
+                const bool live = g0 + u * kSlice < n_words;
+                row_of[u] = live ? row : -1;
+                word_of[u] = w;
+                const int64_t n0 = w * 32 + q * 4;
+                const int32_t* p = C + row * ldc + n0;
+                c[u] = make_int4(0, 0, 0, 0);
+                t[u] = make_int4(0, 0, 0, 0);
+                if (live) {
+                    if (n0 + 0 < N) { c[u].x = p[0]; t[u].x = thr[n0 + 0]; }
+                    if (n0 + 1 < N) { c[u].y = p[1]; t[u].y = thr[n0 + 1]; }
+                    if (n0 + 2 < N) { c[u].z = p[2]; t[u].z = thr[n0 + 2]; }
+                    if (n0 + 3 < N) { c[u].w = p[3]; t[u].w = thr[n0 + 3]; }
+                }
+                row += slice_row;
+                w += slice_word;
+                if (w >= nw) {
+                    w -= nw;
+                    ++row;
+                }
             }
         }
         row0 += pass_row;
@@ -76,19 +113,10 @@ __global__ __launch_bounds__(kBnThreads) void bn_sign_pack_kernel(
 #pragma unroll
         for (int u = 0; u < kBnUnroll; ++u) {
             const int64_t n0 = word_of[u] * 32 + q * 4;
-            int4 t = make_int4(0, 0, 0, 0);
-            if (VEC && n0 + 3 < N) {
-                t = *reinterpret_cast<const int4*>(thr + n0);
-            } else {
-                if (n0 + 0 < N) t.x = thr[n0 + 0];
-                if (n0 + 1 < N) t.y = thr[n0 + 1];
-                if (n0 + 2 < N) t.z = thr[n0 + 2];
-                if (n0 + 3 < N) t.w = thr[n0 + 3];
-            }
             // Bits of channels >= N: flip word has zero pad bits, and the mask below clears them.
             const uint32_t flip = (flip_bits[word_of[u]] >> (4 * q)) & 0xFu;
-            uint32_t nib = uint32_t(c[u].x >= t.x) | (uint32_t(c[u].y >= t.y) << 1) |
-                           (uint32_t(c[u].z >= t.z) << 2) | (uint32_t(c[u].w >= t.w) << 3);
+            uint32_t nib = uint32_t(c[u].x >= t[u].x) | (uint32_t(c[u].y >= t[u].y) << 1) |
+                           (uint32_t(c[u].z >= t[u].z) << 2) | (uint32_t(c[u].w >= t[u].w) << 3);
             nib ^= flip;
             const int64_t valid = N - n0;                       // channels left from this lane's first
             const uint32_t vmask = valid >= 4 ? 0xFu : (valid <= 0 ? 0u : ((1u << valid) - 1u));
