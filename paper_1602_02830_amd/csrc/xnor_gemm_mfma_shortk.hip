@@ -65,19 +65,16 @@ __device__ inline int sum_over_lanes(int c) {
 
 // Words `first` .. `first + 3` of a quad that was loaded from the row's last four words
 // (kw - 4 .. kw - 1): entries beyond the row read 0, the row's last word is masked.
-__device__ inline uint4 align_last_quad(uint4 v, int shift, int valid, uint32_t tmask) {
-    // shift = 4 - valid: the quad's word e is loaded word e + shift.
-    const uint32_t l0 = v.x, l1 = v.y, l2 = v.z, l3 = v.w;
-    uint4 o;
-    o.x = shift == 0 ? l0 : shift == 1 ? l1 : shift == 2 ? l2 : l3;
-    o.y = shift == 0 ? l1 : shift == 1 ? l2 : shift == 2 ? l3 : 0u;
-    o.z = shift == 0 ? l2 : shift == 1 ? l3 : 0u;
-    o.w = shift == 0 ? l3 : 0u;
-    if (valid == 1) o.x &= tmask;
-    else if (valid == 2) o.y &= tmask;
-    else if (valid == 3) o.z &= tmask;
-    else o.w &= tmask;
-    return o;
+__device__ inline uint4 align_last_quad(uint4 v, int shift, uint32_t tmask) {
+    // shift = 4 - (valid words): the quad's word e is loaded word e + shift, and the row's last word is always
+    // the last loaded one.  shift is the same for every thread: a branch, then one AND and register moves.
+    const uint32_t last = v.w & tmask;
+    switch (shift) {
+        case 0: return make_uint4(v.x, v.y, v.z, last);
+        case 1: return make_uint4(v.y, v.z, last, 0u);
+        case 2: return make_uint4(v.z, last, 0u, 0u);
+        default: return make_uint4(last, 0u, 0u, 0u);
+    }
 }
 
 // Output pixel (image b, row y, column x) of a GEMM row, and a step of a fixed number of rows.
@@ -190,7 +187,7 @@ __global__ __launch_bounds__(256, 3) void xnor_gemm_mfma_shortk_kernel(
 #pragma unroll
         for (int l = 0; l < PASSES; ++l) {
             uint4 v = r[l];
-            if (st_q >= n_fast) v = align_last_quad(v, 4 - last_valid, last_valid, tmask);
+            if (st_q >= n_fast) v = align_last_quad(v, 4 - last_valid, tmask);
             if (CONV && ((ones >> l) & 1u)) v = make_uint4(~0u, ~0u, ~0u, ~0u);
             cnt[l] = 0;
             if (st_q < kq) {
