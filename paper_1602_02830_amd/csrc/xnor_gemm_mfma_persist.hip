@@ -35,18 +35,27 @@ __device__ inline uint4 load16_at(const uint32_t* uniform_base, uint32_t lane_by
     return *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(uniform_base) + lane_byte_offset);
 }
 
-// One non-temporal 4-byte vector store at `uniform row address + per-lane byte offset (+ 128 * J)`:
-// the scalar-base form of global_store_dword, spelled out because the compiler otherwise forms (and
-// keeps, and spills) a 64-bit address per lane and element.
-template <int J>
-__device__ inline void store_nt_at(int32_t* uniform_row, uint32_t lane_byte_offset, int value) {
+// One 4-byte vector store at `uniform row address + per-lane byte offset (+ 128 * J)`: the scalar-base form
+// of global_store_dword, spelled out because the compiler otherwise forms (and keeps, and spills) a 64-bit
+// address per lane and element.  Cache policy of the store: THROUGH = agent scope (sc1: written through the
+// die's L2), else non-temporal.  Measured on whole int32 products (8192^3: 189.5 vs 194.0 us; 8192 x 8192 x 2048:
+// 70.4 vs 80.4 us; 8192 x 4096 x 8192: 97.1 vs 101.6 us; from about 330 MB of output on the two are level, one
+// shape of 537 MB 3 % slower written through): the launcher writes through up to kThroughMaxBytes of output.
+template <int J, bool THROUGH>
+__device__ inline void store_at(int32_t* uniform_row, uint32_t lane_byte_offset, int value) {
     static_assert(J == 0 || J == 1, "column block of the wavefront");
-    if (J == 0)
+    if (J == 0 && THROUGH)
+        asm volatile("global_store_dword %0, %1, %2 sc1" : : "v"(lane_byte_offset), "v"(value), "s"(uniform_row) : "memory");
+    else if (J == 0)
         asm volatile("global_store_dword %0, %1, %2 nt" : : "v"(lane_byte_offset), "v"(value), "s"(uniform_row) : "memory");
+    else if (THROUGH)
+        asm volatile("global_store_dword %0, %1, %2 offset:128 sc1"
+                     : : "v"(lane_byte_offset), "v"(value), "s"(uniform_row) : "memory");
     else
         asm volatile("global_store_dword %0, %1, %2 offset:128 nt"
                      : : "v"(lane_byte_offset), "v"(value), "s"(uniform_row) : "memory");
 }
+constexpr int64_t kThroughMaxBytes = int64_t(320) << 20;
 
 // int32 epilogue for tiles that lie wholly inside the matrix: dot = K - 2pa - 2pb + 4S for the
 // wavefront's 4 x 2 accumulator blocks (register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column
@@ -54,7 +63,7 @@ __device__ inline void store_nt_at(int32_t* uniform_row, uint32_t lane_byte_offs
 // registers) plus one per-lane 32-bit offset; the wavefront's second column block is 128 bytes
 // further on.  wm / wn / row0 / col0 must be wavefront-uniform.  pop_a / pop_b hold 2 * popcount
 // per tile row / column.
-template <int WM, int WN>
+template <int WM, int WN, bool THROUGH>
 __device__ inline void persist_epilogue_int32(const v16f (&acc)[WM][WN], const int* pop_a, const int* pop_b,
                                               int32_t* __restrict__ C, int64_t ldc, int K, int row0, int col0, int wm,
                                               int wn, int fr, int fh) {
@@ -74,13 +83,13 @@ __device__ inline void persist_epilogue_int32(const v16f (&acc)[WM][WN], const i
             for (int e = 0; e < 4; ++e) {
                 const int pa = e == 0 ? pa2.x : e == 1 ? pa2.y : e == 2 ? pa2.z : pa2.w;
                 int32_t* row = tile_base + int64_t(ml + e) * ldc;
-                store_nt_at<0>(row, lane_off, base_n[0] - pa + (int(acc[i][0][4 * vq + e]) << 2));
-                store_nt_at<1>(row, lane_off, base_n[1] - pa + (int(acc[i][1][4 * vq + e]) << 2));
+                store_at<0, THROUGH>(row, lane_off, base_n[0] - pa + (int(acc[i][0][4 * vq + e]) << 2));
+                store_at<1, THROUGH>(row, lane_off, base_n[1] - pa + (int(acc[i][1][4 * vq + e]) << 2));
             }
         }
 }
 
-template <bool FUSED>
+template <bool FUSED, bool THROUGH>
 __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_persist_kernel(
     const uint32_t* __restrict__ A, int64_t lda, const uint32_t* __restrict__ B, int64_t ldb,
     int32_t* __restrict__ C, int64_t ldc, int M, int N, int K, int tiles_m, int tiles_n, BnSignArgs bn) {
@@ -264,7 +273,7 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_persist_kernel(
             mfma_epilogue_bits<WM, WN>(acc, pop_a, pop_af, pop_b, thr_s, flip_s, colfix_s, bn, M, N, K, out_row0,
                                        out_col0, wm, wn, fr, fh);
         else
-            persist_epilogue_int32<WM, WN>(acc, pop_a, pop_b, C, ldc, K, out_row0, out_col0, wm, wn, fr, fh);
+            persist_epilogue_int32<WM, WN, THROUGH>(acc, pop_a, pop_b, C, ldc, K, out_row0, out_col0, wm, wn, fr, fh);
         more = has_next;
         if (more) {
             // The next tile's first K-tile is already staged.  The epilogue has read the row sums and
@@ -325,11 +334,14 @@ int launch_xnor_gemm_mfma_persist(const uint32_t* A, int64_t lda, const uint32_t
     const int64_t slots = walk ? mfma_persist_slots() : tiles_m * tiles_n;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (fused)
-        hipLaunchKernelGGL(xnor_gemm_mfma_persist_kernel<true>, dim3(unsigned(slots)), dim3(256), 0, s, A, lda, B, ldb,
-                           C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn);
+        hipLaunchKernelGGL((xnor_gemm_mfma_persist_kernel<true, false>), dim3(unsigned(slots)), dim3(256), 0, s, A, lda, B,
+                           ldb, C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn);
+    else if (M * N * int64_t(sizeof(int32_t)) <= kThroughMaxBytes)
+        hipLaunchKernelGGL((xnor_gemm_mfma_persist_kernel<false, true>), dim3(unsigned(slots)), dim3(256), 0, s, A, lda, B,
+                           ldb, C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn);
     else
-        hipLaunchKernelGGL(xnor_gemm_mfma_persist_kernel<false>, dim3(unsigned(slots)), dim3(256), 0, s, A, lda, B, ldb,
-                           C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn);
+        hipLaunchKernelGGL((xnor_gemm_mfma_persist_kernel<false, false>), dim3(unsigned(slots)), dim3(256), 0, s, A, lda, B,
+                           ldb, C, ldc, int(M), int(N), int(K), int(tiles_m), int(tiles_n), bn);
     return check_launch();
 }
 
