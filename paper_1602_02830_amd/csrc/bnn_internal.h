@@ -28,6 +28,14 @@ inline int check_launch() {
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// Store of an int32 result with agent scope (global_store_dword ... sc1: written through the die's L2).
+// Measured against plain and non-temporal stores on whole int32 products, it is the fastest policy while the
+// output is not much larger than the last-level cache, and by far the fastest where rows of the output are
+// not whole 128-byte lines (3000 x 3000 x 784: 13.6 vs 20.0 us).
+__device__ inline void store_result(int32_t* p, int32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Mask of the valid bits of the last word of a K-bit row (all ones if K % 32 == 0).
 __host__ __device__ inline uint32_t tail_mask(int64_t K) {
     const int r = int(K & 31);

@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) void gemm_i8_mfma_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int m = row0 + wm * 32 * WM + i * 32 + 8 * (v / 4) + 4 * fk + (v % 4);
-                if (m < M && n < N) C[int64_t(m) * ldc + n] = acc[i][j][v];
+                if (m < M && n < N) store_result(&C[int64_t(m) * ldc + n], acc[i][j][v]);
             }
         }
 }

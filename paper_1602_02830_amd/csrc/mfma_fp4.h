@@ -71,7 +71,7 @@ __device__ inline void mfma_epilogue(const v16f (&acc)[WM][WN], const int* pop_a
                         const int m = row0 + ml + e;
                         const int pa = e == 0 ? pa2.x : e == 1 ? pa2.y : e == 2 ? pa2.z : pa2.w;
                         const int dot = base_n - pa + (int(acc[i][j][4 * vq + e]) << kShift);
-                        if (m < M && n < N) __builtin_nontemporal_store(dot, &C[int64_t(m) * ldc + n]);
+                        if (m < M && n < N) store_result(&C[int64_t(m) * ldc + n], dot);
                     }
                 }
         }

@@ -187,7 +187,7 @@ __global__ __launch_bounds__(256, 3) void xnor_gemm_tiled_kernel(
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const int n = col0 + tx + 16 * j;
-                    if (n < N) crow[n] = K - 2 * int(acc[i][j]);
+                    if (n < N) store_result(crow + n, K - 2 * int(acc[i][j]));
                 }
             }
         }
