@@ -181,20 +181,33 @@ __device__ inline void mfma_output_words(v16f (&acc)[WM][WN], const int* pop_a, 
     float left[WN];
 #pragma unroll
     for (int j = 0; j < WN; ++j) left[j] = fh == 0 ? colfix_s[wn * 32 * WN + j * 32 + fr] : 1.0f;
+    if (fold) {
+        // All rank-2 updates first: the vector-ALU work on a block then never waits for its own MFMA.
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+            const float right = fh == 0 ? 1.0f : -pop_af[wm * 32 * WM + i * 32 + fr];
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(left[j], right, acc[i][j], 0, 0, 0);
+        }
+    }
 #pragma unroll
     for (int i = 0; i < WM; ++i) {
         const int ml = wm * 32 * WM + i * 32 + fr;                       // this lane's row of the tile
-        uint32_t part[WN];                                               // this lane's 16 columns, spread out
+        uint32_t part[WN];                                               // this lane's 16 columns: nibble g at bit 8g + 4*fh
         if (fold) {
-            const float right = fh == 0 ? 1.0f : -pop_af[ml];
 #pragma unroll
             for (int j = 0; j < WN; ++j) {
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(left[j], right, acc[i][j], 0, 0, 0);
-                uint32_t neg = 0u;                                       // bit k = sign of register k
+                // Sign bits of the block's 16 registers, nibble g (columns 8g + 4*fh ...) moved to bit 8g on the way.
+                uint32_t neg = 0u;
 #pragma unroll
-                for (int v = 15; v >= 0; --v)
-                    neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[i][j][v]), 31);
-                part[j] = ~neg & 0xFFFFu;
+                for (int g = 3; g >= 0; --g) {
+#pragma unroll
+                    for (int e = 3; e >= 0; --e)
+                        neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[i][j][4 * g + e]), 31);
+                    if (g > 0) neg <<= 4;
+                }
+                part[j] = (~neg & 0x0F0F0F0Fu) << (4 * fh);
             }
         } else {
             const int base_m = K - pop_a[ml];
@@ -214,16 +227,12 @@ __device__ inline void mfma_output_words(v16f (&acc)[WM][WN], const int* pop_a, 
                         bits = (bits << 1) | (dot >= t ? 1u : 0u);
                     }
                 }
-                part[j] = bits;
+                // Bit 4g + e of bits is column 8g + 4*fh + e of block j: move nibble g to bit 8g + 4*fh.
+                uint32_t x = bits;
+                x = (x | (x << 8)) & 0x00FF00FFu;
+                x = (x | (x << 4)) & 0x0F0F0F0Fu;
+                part[j] = x << (4 * fh);
             }
-        }
-        // Bit 4g + e of part[j] is column 8g + 4*fh + e of block j: move nibble g to bit 8g + 4*fh.
-#pragma unroll
-        for (int j = 0; j < WN; ++j) {
-            uint32_t x = part[j];
-            x = (x | (x << 8)) & 0x00FF00FFu;
-            x = (x | (x << 4)) & 0x0F0F0F0Fu;
-            part[j] = x << (4 * fh);
         }
         // Lanes 32-63 of part[0] <-> lanes 0-31 of part[1]: afterwards lane l holds, in the two
         // registers, the two halves of the word of column block l / 32.
